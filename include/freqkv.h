@@ -1,0 +1,168 @@
+/*
+ * freqkv.h - C ABI of libfreqkv: frequency-domain compression of an LLM KV cache
+ * on AMD MI355X (gfx950).
+ *
+ * The operation (FreqKV, arXiv 2505.00570):
+ *   When a cache of `window` tokens is full, the span after the first `n_sink`
+ *   tokens (n = window - n_sink rows of every per-head K and V matrix) is taken
+ *   through an orthonormal DCT-II along the token axis (Sec. 3.3 Eq. 2,
+ *   Appendix A), only the Lc = floor(retain_ratio * n) lowest-frequency
+ *   coefficients are kept (Sec. 3.3), an Lc-point inverse DCT brings them back to
+ *   Lc time-domain rows, scaled by sqrt(Lc/n) (Sec. 3.3 Eq. 3), and those rows
+ *   replace the span in place: [sinks | Lc compressed rows | later tokens]
+ *   (Sec. 3.4, Fig. 2b).  Sink rows are never touched (Sec. 3.4).
+ *
+ * All entry points are plain C, take plain pointers and sizes, never throw and
+ * never abort.  Unless a comment says "host", a pointer is a DEVICE pointer.
+ * The caller owns every buffer it passes; the library owns only its cached
+ * basis tables (freed by freqkv_shutdown).
+ */
+#ifndef FREQKV_H
+#define FREQKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FREQKV_OK            = 0,   /* work was enqueued on the stream                          */
+    FREQKV_NOOP          = 1,   /* cur_len < window: cache not full, nothing enqueued       */
+    FREQKV_E_INVALID     = -1,  /* an argument violates the documented ranges               */
+    FREQKV_E_UNSUPPORTED = -2,  /* valid but not implemented (e.g. odd head_dim)            */
+    FREQKV_E_WORKSPACE   = -3,  /* layout.workspace missing, misaligned or too small        */
+    FREQKV_E_HIP         = -4,  /* a HIP runtime call failed                                */
+    FREQKV_E_ALLOC       = -5   /* the library could not allocate a basis table             */
+} freqkv_status_t;
+
+typedef enum {
+    FREQKV_BF16 = 0,            /* cache holds bfloat16; fp16 MFMA operands, fp32 accumulate */
+    FREQKV_F32  = 1             /* cache holds float32; fp32 FMA throughout                  */
+} freqkv_dtype_t;
+
+/* layout.flags */
+#define FREQKV_FLAG_NO_RESCALE 0x1u   /* omit the sqrt(Lc/n) factor (rescaling ablation, appendix "Effect of rescaling") */
+
+/*
+ * Memory description of the cache ("layout"): everything the scalar arguments of
+ * freqkv_compress do not say.  One head-tensor is the [token][dim] matrix of one
+ * (K|V, layer, batch, head); its element (token t, channel c) lives at
+ *     base(K|V, layer) + b*stride_batch + h*stride_head + t*stride_token + c      (in elements)
+ * where base = k (or v) + layer*stride_layer when pointer_table == 0, and
+ *       base = ((void* const*)k)[layer]      when pointer_table == 1 (k and v are then HOST
+ *              arrays of n_layers device pointers, read before the call returns).
+ * The channel stride is 1.  Head-major caches ([layer][batch][head][token][dim],
+ * stride_token == head_dim) are the fast, fully coalesced case; any stride_token >= head_dim works.
+ * Every stride must be a multiple of 8 elements and every base pointer 16-byte aligned.
+ * The batch shares one cur_len (Sec. 4.1: identical settings for all layers and heads).
+ */
+typedef struct freqkv_layout {
+    int32_t  dtype;             /* freqkv_dtype_t                                               */
+    int32_t  n_layers;          /* >= 1                                                         */
+    int32_t  batch;             /* >= 1                                                         */
+    int32_t  token_capacity;    /* rows allocated per head-tensor, >= cur_len                   */
+    int64_t  stride_layer;      /* elements; ignored when pointer_table == 1                    */
+    int64_t  stride_batch;      /* elements                                                     */
+    int64_t  stride_head;       /* elements                                                     */
+    int64_t  stride_token;      /* elements, >= head_dim                                        */
+    int32_t  pointer_table;     /* 0 or 1, see above                                            */
+    uint32_t flags;             /* FREQKV_FLAG_*                                                */
+    void*    workspace;         /* device scratch, 256-byte aligned, see freqkv_plan            */
+    size_t   workspace_bytes;
+    float*   tap_f32;           /* optional (may be NULL): device array
+                                   [2 (K,V)][n_layers][batch][n_heads][Lc][head_dim] that receives
+                                   the fp32 results before they are rounded to the cache dtype    */
+} freqkv_layout_t;
+
+/* Result of the buffer-plan query (host arithmetic only). */
+typedef struct freqkv_plan {
+    int32_t span_len;           /* n  = window - n_sink                                          */
+    int32_t retained_len;       /* Lc = clamp(floor(retain_ratio*n + 1e-9), 1, n)                */
+    int32_t new_len;            /* cache length after the call: n_sink + Lc + (cur_len - window) */
+    int32_t head_tensors;       /* 2 * n_layers * batch * n_heads                                */
+    int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA */
+    int32_t reserved;
+    size_t  workspace_bytes;    /* scratch for all head-tensors in one pass (fastest)            */
+    size_t  workspace_min_bytes;/* smallest scratch accepted (one (layer,K|V) slab per pass)     */
+    size_t  basis_bytes;        /* device memory the library itself holds for this (n, Lc)       */
+    double  flops_dense;        /* 2*Lc*n*d per head-tensor, summed: the fused operator as one contraction */
+    double  flops_executed;     /* what the chosen variant executes (no padding counted)         */
+    double  bytes_algorithmic;  /* (n + Lc)*d*e per head-tensor + 2*(cur_len-window)*d*e, summed */
+} freqkv_plan_t;
+
+/* Per-kernel GPU time, accumulated by HIP events while profiling is on. */
+typedef struct freqkv_profile {
+    int64_t calls;              /* freqkv_compress calls that enqueued work                      */
+    int64_t launches_prepare;   /* fold/convert (or copy) launches                               */
+    int64_t launches_contract;  /* contraction launches                                          */
+    int64_t launches_tail;      /* tail-move launches                                            */
+    double  ms_prepare;
+    double  ms_contract;
+    double  ms_tail;
+} freqkv_profile_t;
+
+/*
+ * Buffer-plan query (Sec. 3.3 / Sec. 4.1 arithmetic).  HOST only: needs no GPU, touches no
+ * device memory; layout.workspace / tap_f32 are ignored.  `layout` and `out` are host pointers.
+ * Returns FREQKV_OK, FREQKV_NOOP (cur_len < window; the plan is still filled for a full cache)
+ * or a negative status for invalid arguments.
+ *
+ * Valid ranges: n_heads >= 1; head_dim >= 8 and a multiple of 8; n_sink >= 0;
+ * window >= n_sink + 2; cur_len <= layout.token_capacity; 0 < retain_ratio <= 1.
+ */
+freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim,
+                            int cur_len, int window, int n_sink, double retain_ratio,
+                            freqkv_plan_t* out);
+
+/*
+ * One compression trigger over every layer's K and V (Sec. 3.3 Eq. 2-3, Sec. 3.4).
+ *   k, v     device base pointers of the K and V caches (or host pointer tables, see layout)
+ *   layout   host pointer; read before the call returns
+ *   cur_len  tokens currently in the cache; the span is rows [n_sink, window); rows
+ *            [window, cur_len) are a recent tail that is moved, bit for bit, to start at
+ *            n_sink + Lc.  After the call the cache holds freqkv_plan(...).new_len tokens;
+ *            rows at and beyond new_len (up to the old cur_len) hold unspecified values.
+ *            Nothing outside rows [n_sink, cur_len) of any head-tensor is written.
+ *   stream   hipStream_t (NULL = the default stream).  The call only enqueues work: it does not
+ *            synchronise the device and never reads results back.  The first call for a new
+ *            (device, n, Lc, dtype, flags) builds and caches the basis table (one allocation).
+ * retain_ratio == 1 (Lc == n) is the identity and enqueues nothing (FREQKV_OK).
+ * On a negative status no device memory has been written.
+ */
+freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
+                                int n_heads, int head_dim, int cur_len, int window, int n_sink,
+                                double retain_ratio, void* stream);
+
+/*
+ * Build and cache the basis table for (window - n_sink, retain_ratio, dtype, flags) on the current
+ * device ahead of the first trigger (Appendix A cosine bases fused into one operator).  Optional.
+ */
+freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink,
+                               double retain_ratio, void* stream);
+
+/* Human-readable name of a status code (static string, host). */
+const char* freqkv_status_string(freqkv_status_t status);
+
+/* Text of the last HIP error seen by the calling thread's most recent failing call ("" if none). */
+const char* freqkv_last_error(void);
+
+/* Free every cached basis table on every device.  Safe to call more than once. */
+void freqkv_shutdown(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int freqkv_version(void);
+
+/*
+ * Kernel timing with HIP events recorded on the caller's stream around each launch.
+ * freqkv_profile_enable(1) starts accumulating (and resets the counters), (0) stops.
+ * freqkv_profile_read synchronises on the recorded events and fills *out (host pointer).
+ */
+freqkv_status_t freqkv_profile_enable(int on);
+freqkv_status_t freqkv_profile_read(freqkv_profile_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FREQKV_H */

@@ -1,0 +1,195 @@
+"""ctypes binding with the same names as include/freqkv.h (argument marshalling only).
+
+Every step of the compression runs inside libfreqkv's HIP kernels; this module only builds
+the C structs from torch tensors (device memory, strides, stream) and raises when the
+library is missing or returns an error.  There is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "lib", "libfreqkv.so")
+_lib = None
+
+BF16, F32 = 0, 1
+FLAG_NO_RESCALE = 0x1
+
+OK, NOOP = 0, 1
+E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_HIP, E_ALLOC = -1, -2, -3, -4, -5
+
+
+class FreqKVError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        name = status_string(status) if _lib is not None else str(status)
+        super().__init__(f"{name}{(': ' + detail) if detail else ''}")
+
+
+class Layout(C.Structure):
+    """struct freqkv_layout (include/freqkv.h)."""
+    _fields_ = [
+        ("dtype", C.c_int32), ("n_layers", C.c_int32), ("batch", C.c_int32), ("token_capacity", C.c_int32),
+        ("stride_layer", C.c_int64), ("stride_batch", C.c_int64), ("stride_head", C.c_int64),
+        ("stride_token", C.c_int64),
+        ("pointer_table", C.c_int32), ("flags", C.c_uint32),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("tap_f32", C.c_void_p),
+    ]
+
+
+class Plan(C.Structure):
+    """struct freqkv_plan (include/freqkv.h)."""
+    _fields_ = [
+        ("span_len", C.c_int32), ("retained_len", C.c_int32), ("new_len", C.c_int32),
+        ("head_tensors", C.c_int32), ("variant", C.c_int32), ("reserved", C.c_int32),
+        ("workspace_bytes", C.c_size_t), ("workspace_min_bytes", C.c_size_t), ("basis_bytes", C.c_size_t),
+        ("flops_dense", C.c_double), ("flops_executed", C.c_double), ("bytes_algorithmic", C.c_double),
+    ]
+
+
+class Profile(C.Structure):
+    """struct freqkv_profile (include/freqkv.h)."""
+    _fields_ = [
+        ("calls", C.c_int64), ("launches_prepare", C.c_int64), ("launches_contract", C.c_int64),
+        ("launches_tail", C.c_int64),
+        ("ms_prepare", C.c_double), ("ms_contract", C.c_double), ("ms_tail", C.c_double),
+    ]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> C.CDLL:
+    """Load libfreqkv.so; fails loudly when it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FreqKVError(E_HIP, f"{_LIB_PATH} is missing: run `python -m paper_2505_00570_amd.build`")
+        lib = C.CDLL(_LIB_PATH)
+        LP, PP = C.POINTER(Layout), C.POINTER(Plan)
+        lib.freqkv_plan.argtypes = [LP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, PP]
+        lib.freqkv_plan.restype = C.c_int
+        lib.freqkv_compress.argtypes = [C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_int, C.c_double, C.c_void_p]
+        lib.freqkv_compress.restype = C.c_int
+        lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
+        lib.freqkv_prepare.restype = C.c_int
+        lib.freqkv_status_string.argtypes = [C.c_int]
+        lib.freqkv_status_string.restype = C.c_char_p
+        lib.freqkv_last_error.argtypes = []
+        lib.freqkv_last_error.restype = C.c_char_p
+        lib.freqkv_shutdown.argtypes = []
+        lib.freqkv_shutdown.restype = None
+        lib.freqkv_version.argtypes = []
+        lib.freqkv_version.restype = C.c_int
+        lib.freqkv_profile_enable.argtypes = [C.c_int]
+        lib.freqkv_profile_enable.restype = C.c_int
+        lib.freqkv_profile_read.argtypes = [C.POINTER(Profile)]
+        lib.freqkv_profile_read.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().freqkv_status_string(int(status)).decode()
+
+
+def last_error() -> str:
+    return load().freqkv_last_error().decode()
+
+
+def version() -> int:
+    return load().freqkv_version()
+
+
+def shutdown() -> None:
+    load().freqkv_shutdown()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise FreqKVError(rc, last_error())
+    return rc
+
+
+def plan(layout: Layout, n_heads: int, head_dim: int, cur_len: int, window: int, n_sink: int,
+         retain_ratio: float, check: bool = True):
+    """freqkv_plan: returns (status, Plan).  Host arithmetic only."""
+    out = Plan()
+    rc = load().freqkv_plan(C.byref(layout), n_heads, head_dim, cur_len, window, n_sink,
+                            float(retain_ratio), C.byref(out))
+    if check:
+        _check(rc)
+    return rc, out
+
+
+def prepare(dtype: int, flags: int, window: int, n_sink: int, retain_ratio: float, stream=None) -> int:
+    return _check(load().freqkv_prepare(dtype, flags, window, n_sink, float(retain_ratio), _stream_ptr(stream)))
+
+
+def compress(k, v, layout: Layout, n_heads: int, head_dim: int, cur_len: int, window: int, n_sink: int,
+             retain_ratio: float, stream=None, check: bool = True) -> int:
+    """freqkv_compress.  k, v: torch CUDA tensors, raw device addresses (int), or ctypes arrays of
+    per-layer device pointers when layout.pointer_table == 1.  Returns the status (0 or 1)."""
+    rc = load().freqkv_compress(_dev_ptr(k), _dev_ptr(v), C.byref(layout), n_heads, head_dim, cur_len,
+                                window, n_sink, float(retain_ratio), _stream_ptr(stream))
+    return _check(rc) if check else rc
+
+
+def profile_enable(on: bool) -> None:
+    _check(load().freqkv_profile_enable(1 if on else 0))
+
+
+def profile_read() -> Profile:
+    out = Profile()
+    _check(load().freqkv_profile_read(C.byref(out)))
+    return out
+
+
+# ---------------------------------------------------------------- marshalling helpers
+
+def _dev_ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return C.c_void_p(x)
+    if isinstance(x, C.Array):
+        return C.cast(x, C.c_void_p)
+    if hasattr(x, "data_ptr"):
+        return C.c_void_p(x.data_ptr())
+    return x
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)          # torch.cuda.Stream
+
+
+def layout_for(k, *, batch_dim: bool = True, workspace=None, tap=None, flags: int = 0) -> Layout:
+    """Layout of a torch cache tensor shaped [layer, batch, head, token, dim] (any strides with
+    unit dim stride); `workspace` / `tap` are torch CUDA tensors or None."""
+    import torch
+    if k.dim() != 5:
+        raise ValueError("expected a [layer, batch, head, token, dim] tensor")
+    if k.stride(4) != 1:
+        raise ValueError("channel stride must be 1")
+    dt = {torch.bfloat16: BF16, torch.float32: F32}[k.dtype]
+    L = Layout()
+    L.dtype = dt
+    L.n_layers, L.batch = k.shape[0], k.shape[1]
+    L.token_capacity = k.shape[3]
+    L.stride_layer, L.stride_batch, L.stride_head, L.stride_token = k.stride(0), k.stride(1), k.stride(2), k.stride(3)
+    L.pointer_table = 0
+    L.flags = flags
+    if workspace is not None:
+        L.workspace = workspace.data_ptr()
+        L.workspace_bytes = workspace.numel() * workspace.element_size()
+    if tap is not None:
+        L.tap_f32 = tap.data_ptr()
+    return L

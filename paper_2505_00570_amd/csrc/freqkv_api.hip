@@ -1,0 +1,410 @@
+// Host side of libfreqkv: argument checks, the buffer plan, the per-device basis cache and the
+// launch sequence of one trigger.  Everything here is plain C ABI on the outside (freqkv.h).
+#include "freqkv.h"
+#include "freqkv_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+using namespace freqkv;
+
+namespace {
+
+thread_local char g_last_error[256] = "";
+
+void set_error(const char* what, hipError_t e)
+{
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) {                         \
+            set_error(#expr, _e);                       \
+            return FREQKV_E_HIP;                        \
+        }                                               \
+    } while (0)
+
+inline long long round_up(long long a, long long b) { return (a + b - 1) / b * b; }
+
+// Sec. 3.3: L = gamma * N, floored to an integer, at least one row.
+int retained_len(int n, double ratio)
+{
+    long long lc = (long long)std::floor(ratio * (double)n + 1e-9);
+    if (lc < 1) lc = 1;
+    if (lc > n) lc = n;
+    return (int)lc;
+}
+
+struct Shape {
+    int n, Lc, S, W, d, n_heads, batch, n_layers, cur_len, tail;
+    int variant;
+    int elem;                 // bytes per cache element
+    long long hts_per_slab;   // batch * n_heads
+    int nslabs;               // 2 * n_layers
+};
+
+// Geometry for a pass over `slabs` slabs (static part depends only on the shape).
+Geom make_geom(const Shape& sh, const freqkv_layout_t& L, int slabs, int slab0)
+{
+    Geom g;
+    memset(&g, 0, sizeof(g));
+    g.n = sh.n; g.Lc = sh.Lc; g.S = sh.S; g.d = sh.d;
+    g.hts_per_slab = (int)sh.hts_per_slab;
+    g.n_heads = sh.n_heads;
+    g.ncols = (int)((long long)slabs * sh.hts_per_slab * sh.d);
+    g.ncoltiles = (g.ncols + kColTile - 1) / kColTile;
+    g.fold = sh.variant == kFoldF16;
+    if (sh.variant == kFoldF16) {
+        g.Kh = sh.n / 2; g.Mh = sh.Lc / 2;
+        g.Mpad = (int)round_up(g.Mh, kRowsFold);
+        g.Grows = 2 * g.Mpad;
+        g.nmtiles = g.Mpad / kRowsFold;
+    } else {
+        g.Kh = sh.n; g.Mh = sh.Lc;
+        g.Mpad = (int)round_up(g.Mh, kRowsPlain);
+        g.Grows = g.Mpad;
+        g.nmtiles = g.Mpad / kRowsPlain;
+    }
+    g.Kpad = (int)round_up(g.Kh, kKStage);
+    g.nkstages = g.Kpad / kKStage;
+    g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
+    g.tap_slab0 = slab0;
+    return g;
+}
+
+size_t basis_bytes(const Shape& sh, const Geom& g)
+{
+    if (sh.variant == kF32) return (size_t)sh.n * sh.Lc * sizeof(float);
+    if (sh.variant == kNone) return 0;
+    return (size_t)(g.Kpad / 8) * g.Grows * 16;
+}
+
+// Workspace bytes for a pass over `slabs` slabs.
+size_t pass_workspace(const Shape& sh, int slabs)
+{
+    long long ncols = (long long)slabs * sh.hts_per_slab * sh.d;
+    if (sh.variant == kF32) return (size_t)sh.n * (size_t)round_up(ncols, 64) * sizeof(float);
+    int P = sh.variant == kFoldF16 ? 2 : 1;
+    long long Kh = sh.variant == kFoldF16 ? sh.n / 2 : sh.n;
+    long long nks = round_up(Kh, kKStage) / kKStage;
+    long long ncoltiles = (ncols + kColTile - 1) / kColTile;
+    return (size_t)ncoltiles * nks * P * 8192;
+}
+
+freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim, int cur_len, int window,
+                            int n_sink, double ratio, Shape* out)
+{
+    if (!L) return FREQKV_E_INVALID;
+    if (L->dtype != FREQKV_BF16 && L->dtype != FREQKV_F32) return FREQKV_E_INVALID;
+    if (L->n_layers < 1 || L->batch < 1 || n_heads < 1) return FREQKV_E_INVALID;
+    if (head_dim < 8) return FREQKV_E_INVALID;
+    if (head_dim % 8 != 0) return FREQKV_E_UNSUPPORTED;
+    if (n_sink < 0 || window < n_sink + 2) return FREQKV_E_INVALID;
+    if (cur_len < 0 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
+    if (!(ratio > 0.0) || !(ratio <= 1.0)) return FREQKV_E_INVALID;      // also rejects NaN
+    if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
+    if (L->flags & ~FREQKV_FLAG_NO_RESCALE) return FREQKV_E_INVALID;
+    if (L->stride_token < head_dim) return FREQKV_E_INVALID;
+    if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
+    if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;
+    if (L->stride_head < 0 || L->stride_batch < 0) return FREQKV_E_INVALID;
+    if (window - n_sink > (1 << 20)) return FREQKV_E_UNSUPPORTED;        // 64-bit angle reduction of the basis
+    long long hts = (long long)L->batch * n_heads;
+    if (hts * head_dim > (1LL << 30) / 192) return FREQKV_E_UNSUPPORTED; // virtual column index stays in int
+    if (L->n_layers > (1 << 20)) return FREQKV_E_UNSUPPORTED;
+
+    Shape sh;
+    sh.W = window; sh.S = n_sink; sh.n = window - n_sink;
+    sh.Lc = retained_len(sh.n, ratio);
+    sh.d = head_dim; sh.n_heads = n_heads; sh.batch = L->batch; sh.n_layers = L->n_layers;
+    sh.cur_len = cur_len;
+    sh.tail = cur_len >= window ? cur_len - window : 0;
+    sh.elem = L->dtype == FREQKV_BF16 ? 2 : 4;
+    sh.hts_per_slab = hts;
+    sh.nslabs = 2 * L->n_layers;
+    if (sh.Lc == sh.n) sh.variant = kNone;
+    else if (L->dtype == FREQKV_F32) sh.variant = kF32;
+    else sh.variant = (sh.n % 2 == 0 && sh.Lc % 2 == 0) ? kFoldF16 : kPlainF16;
+    *out = sh;
+    return FREQKV_OK;
+}
+
+// ---------------------------------------------------------------- basis cache
+struct BasisKey {
+    int device, n, Lc, variant, rescale;
+    bool operator<(const BasisKey& o) const
+    {
+        return std::tie(device, n, Lc, variant, rescale) < std::tie(o.device, o.n, o.Lc, o.variant, o.rescale);
+    }
+};
+struct BasisEntry {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+    hipEvent_t ready = nullptr;   // recorded after the build kernel; other streams wait on it
+};
+
+std::mutex g_mu;
+std::map<BasisKey, BasisEntry> g_basis;
+
+freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream_t st, void** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    BasisKey key{dev, sh.n, sh.Lc, sh.variant, rescale};
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto it = g_basis.find(key);
+    if (it == g_basis.end()) {
+        BasisEntry e;
+        e.bytes = basis_bytes(sh, g);
+        hipError_t err = hipMalloc(&e.ptr, e.bytes);
+        if (err != hipSuccess) {
+            set_error("hipMalloc(basis)", err);
+            (void)hipGetLastError();
+            return FREQKV_E_ALLOC;
+        }
+        if (sh.variant == kF32) err = launch_basis_f32((float*)e.ptr, sh.n, sh.Lc, rescale, st);
+        else                    err = launch_basis_f16((_Float16*)e.ptr, g, rescale, st);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&e.ready, hipEventDisableTiming);
+        if (err == hipSuccess) err = hipEventRecord(e.ready, st);
+        if (err != hipSuccess) {
+            set_error("basis build", err);
+            (void)hipFree(e.ptr);
+            return FREQKV_E_HIP;
+        }
+        it = g_basis.emplace(key, e).first;
+    } else {
+        // built on some stream earlier: order this stream after the build
+        HIP_TRY(hipStreamWaitEvent(st, it->second.ready, 0));
+    }
+    *out = it->second.ptr;
+    return FREQKV_OK;
+}
+
+// ---------------------------------------------------------------- profiling
+struct ProfSpan { hipEvent_t a, b; int kind; };
+bool g_prof_on = false;
+std::vector<ProfSpan> g_prof_spans;
+freqkv_profile_t g_prof_acc;
+
+hipError_t prof_begin(hipStream_t st, int kind, ProfSpan* sp)
+{
+    sp->kind = kind; sp->a = sp->b = nullptr;
+    if (!g_prof_on) return hipSuccess;
+    hipError_t e = hipEventCreate(&sp->a);
+    if (e == hipSuccess) e = hipEventCreate(&sp->b);
+    if (e == hipSuccess) e = hipEventRecord(sp->a, st);
+    return e;
+}
+hipError_t prof_end(hipStream_t st, ProfSpan* sp)
+{
+    if (!g_prof_on || !sp->a) return hipSuccess;
+    hipError_t e = hipEventRecord(sp->b, st);
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_prof_spans.push_back(*sp);
+    return e;
+}
+
+}  // namespace
+
+// ================================================================== C ABI
+
+extern "C" {
+
+const char* freqkv_status_string(freqkv_status_t s)
+{
+    switch (s) {
+        case FREQKV_OK: return "FREQKV_OK";
+        case FREQKV_NOOP: return "FREQKV_NOOP";
+        case FREQKV_E_INVALID: return "FREQKV_E_INVALID";
+        case FREQKV_E_UNSUPPORTED: return "FREQKV_E_UNSUPPORTED";
+        case FREQKV_E_WORKSPACE: return "FREQKV_E_WORKSPACE";
+        case FREQKV_E_HIP: return "FREQKV_E_HIP";
+        case FREQKV_E_ALLOC: return "FREQKV_E_ALLOC";
+    }
+    return "FREQKV_E_UNKNOWN";
+}
+
+const char* freqkv_last_error(void) { return g_last_error; }
+
+int freqkv_version(void) { return 100; }
+
+freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim, int cur_len,
+                            int window, int n_sink, double retain_ratio, freqkv_plan_t* out)
+{
+    if (!out) return FREQKV_E_INVALID;
+    Shape sh;
+    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, cur_len, window, n_sink, retain_ratio, &sh);
+    if (rc < 0) return rc;
+    memset(out, 0, sizeof(*out));
+    out->span_len = sh.n;
+    out->retained_len = sh.Lc;
+    out->new_len = sh.S + sh.Lc + sh.tail;
+    out->head_tensors = (int)(sh.nslabs * sh.hts_per_slab);
+    out->variant = sh.variant;
+    double hts = (double)sh.nslabs * (double)sh.hts_per_slab;
+    if (sh.variant != kNone) {
+        Geom g = make_geom(sh, *layout, sh.nslabs, 0);
+        int max_slabs = sh.nslabs < kMaxSlabs ? sh.nslabs : kMaxSlabs;
+        out->workspace_bytes = pass_workspace(sh, max_slabs);
+        out->workspace_min_bytes = pass_workspace(sh, 1);
+        out->basis_bytes = basis_bytes(sh, g);
+        out->flops_dense = 2.0 * sh.Lc * (double)sh.n * sh.d * hts;
+        out->flops_executed = sh.variant == kFoldF16 ? out->flops_dense * 0.5 : out->flops_dense;
+        out->bytes_algorithmic = ((double)sh.n + sh.Lc + 2.0 * sh.tail) * sh.d * sh.elem * hts;
+    }
+    return cur_len < window ? FREQKV_NOOP : FREQKV_OK;
+}
+
+freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink, double retain_ratio,
+                               void* stream)
+{
+    freqkv_layout_t L;
+    memset(&L, 0, sizeof(L));
+    L.dtype = dtype; L.n_layers = 1; L.batch = 1; L.token_capacity = window;
+    L.stride_token = 8; L.flags = flags;
+    Shape sh;
+    freqkv_status_t rc = check_shape(&L, 1, 8, window, window, n_sink, retain_ratio, &sh);
+    if (rc < 0) return rc;
+    if (sh.variant == kNone) return FREQKV_OK;
+    Geom g = make_geom(sh, L, 1, 0);
+    void* basis = nullptr;
+    return get_basis(sh, g, !(flags & FREQKV_FLAG_NO_RESCALE), (hipStream_t)stream, &basis);
+}
+
+freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
+                                int cur_len, int window, int n_sink, double retain_ratio, void* stream)
+{
+    g_last_error[0] = 0;
+    Shape sh;
+    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, cur_len, window, n_sink, retain_ratio, &sh);
+    if (rc < 0) return rc;
+    if (!k || !v) return FREQKV_E_INVALID;
+    const freqkv_layout_t& L = *layout;
+
+    // per-slab base pointers in the caller's [K|V][layer] order
+    std::vector<char*> bases((size_t)sh.nslabs);
+    for (int kv = 0; kv < 2; ++kv) {
+        void* root = kv ? v : k;
+        for (int l = 0; l < sh.n_layers; ++l) {
+            char* p = L.pointer_table ? (char*)((void* const*)root)[l]
+                                      : (char*)root + (long long)l * L.stride_layer * sh.elem;
+            if (!p || ((uintptr_t)p & 15)) return FREQKV_E_INVALID;
+            bases[(size_t)kv * sh.n_layers + l] = p;
+        }
+    }
+    if (cur_len < window) return FREQKV_NOOP;
+    if (sh.variant == kNone) return FREQKV_OK;                // retain_ratio == 1: identity
+
+    size_t min_ws = pass_workspace(sh, 1);
+    if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < min_ws) return FREQKV_E_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    const int rescale = !(L.flags & FREQKV_FLAG_NO_RESCALE);
+
+    // slabs per pass: as many as the workspace and the pointer table hold
+    int per_pass = sh.nslabs < kMaxSlabs ? sh.nslabs : kMaxSlabs;
+    while (per_pass > 1 && pass_workspace(sh, per_pass) > L.workspace_bytes) --per_pass;
+
+    void* basis = nullptr;
+    {
+        Geom g0 = make_geom(sh, L, per_pass, 0);
+        rc = get_basis(sh, g0, rescale, st, &basis);
+        if (rc < 0) return rc;
+    }
+    if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
+
+    for (int s0 = 0; s0 < sh.nslabs; s0 += per_pass) {
+        int slabs = sh.nslabs - s0 < per_pass ? sh.nslabs - s0 : per_pass;
+        Geom g = make_geom(sh, L, slabs, s0);
+        SlabTable tab;
+        memset(&tab, 0, sizeof(tab));
+        for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
+
+        ProfSpan sp;
+        // 1. span -> workspace (fold + convert, or copy)
+        HIP_TRY(prof_begin(st, 0, &sp));
+        if (sh.variant == kF32) HIP_TRY(launch_prepare_f32(tab, g, (float*)L.workspace, st));
+        else                    HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st));
+        HIP_TRY(prof_end(st, &sp));
+
+        // 2. recent tail: rows [W, cur_len) -> [S+Lc, ...).  The span has been copied out, so the
+        //    destination is free; chunks of at most (n - Lc) rows never overlap their source.
+        if (sh.tail > 0) {
+            HIP_TRY(prof_begin(st, 2, &sp));
+            const int gap = sh.n - sh.Lc;
+            for (int r0 = 0; r0 < sh.tail; r0 += gap) {
+                int rows = sh.tail - r0 < gap ? sh.tail - r0 : gap;
+                HIP_TRY(launch_move_rows(tab, g, sh.elem, sh.W + r0, sh.S + sh.Lc + r0, rows, st));
+            }
+            HIP_TRY(prof_end(st, &sp));
+        }
+
+        // 3. contraction, written straight into rows [S, S+Lc)
+        float* tap = L.tap_f32;
+        HIP_TRY(prof_begin(st, 1, &sp));
+        if (sh.variant == kF32)
+            HIP_TRY(launch_contract_f32(tab, g, (const float*)basis, (const float*)L.workspace, tap, st));
+        else
+            HIP_TRY(launch_contract_f16(tab, g, (const _Float16*)basis, (const _Float16*)L.workspace, tap, st));
+        HIP_TRY(prof_end(st, &sp));
+    }
+    return FREQKV_OK;
+}
+
+void freqkv_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    bool have_dev = hipGetDevice(&cur) == hipSuccess;
+    for (auto& kv : g_basis) {
+        if (hipSetDevice(kv.first.device) != hipSuccess) continue;
+        if (kv.second.ready) {
+            (void)hipEventSynchronize(kv.second.ready);
+            (void)hipEventDestroy(kv.second.ready);
+        }
+        (void)hipFree(kv.second.ptr);
+    }
+    g_basis.clear();
+    for (auto& sp : g_prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    g_prof_spans.clear();
+    if (have_dev) (void)hipSetDevice(cur);
+    (void)hipGetLastError();
+}
+
+freqkv_status_t freqkv_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (auto& sp : g_prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    g_prof_spans.clear();
+    memset(&g_prof_acc, 0, sizeof(g_prof_acc));
+    g_prof_on = on != 0;
+    return FREQKV_OK;
+}
+
+freqkv_status_t freqkv_profile_read(freqkv_profile_t* out)
+{
+    if (!out) return FREQKV_E_INVALID;
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (auto& sp : g_prof_spans) {
+        HIP_TRY(hipEventSynchronize(sp.b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
+        if (sp.kind == 0) { g_prof_acc.ms_prepare += ms; g_prof_acc.launches_prepare++; }
+        else if (sp.kind == 1) { g_prof_acc.ms_contract += ms; g_prof_acc.launches_contract++; }
+        else { g_prof_acc.ms_tail += ms; g_prof_acc.launches_tail++; }
+        (void)hipEventDestroy(sp.a);
+        (void)hipEventDestroy(sp.b);
+    }
+    g_prof_spans.clear();
+    *out = g_prof_acc;
+    return FREQKV_OK;
+}
+
+}  // extern "C"

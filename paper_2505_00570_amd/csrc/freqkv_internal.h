@@ -1,0 +1,67 @@
+// Internal interface between the host side of libfreqkv (argument checks, plans,
+// basis cache, launch sequence) and its gfx950 kernels.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace freqkv {
+
+// One launch group addresses at most this many (layer, K|V) slabs; their base
+// pointers travel by value in the kernel arguments.
+constexpr int kMaxSlabs = 192;
+
+struct SlabTable {
+    char* base[kMaxSlabs];
+};
+
+// Tile constants of the fp16-MFMA contraction.
+constexpr int kColTile   = 128;   // virtual columns per workgroup tile
+constexpr int kKStage    = 32;    // contraction rows staged per pipeline step
+constexpr int kRowsFold  = 256;   // rows per parity per workgroup tile (folded variant)
+constexpr int kRowsPlain = 512;   // rows per workgroup tile (plain variant)
+
+// Geometry of one pass (by-value kernel argument).
+struct Geom {
+    int n;               // span length
+    int Lc;              // retained length
+    int S;               // sink rows
+    int d;               // head_dim
+    int hts_per_slab;    // batch * n_heads
+    int n_heads;
+    int ncols;           // virtual columns in this pass = slabs * hts_per_slab * d
+    int ncoltiles;       // ceil(ncols / kColTile)
+    int fold;            // 1: even/odd folded operator, 0: plain
+    int Kh;              // contraction length: n/2 (fold) or n
+    int Kpad;            // Kh rounded up to kKStage
+    int nkstages;        // Kpad / kKStage
+    int Mh;              // output rows per parity: Lc/2 (fold) or Lc
+    int Mpad;            // Mh rounded up to the workgroup tile
+    int Grows;           // rows of the stored basis: 2*Mpad (fold) or Mpad
+    int nmtiles;         // Mpad / tile rows
+    long long stride_batch, stride_head, stride_token;   // elements
+    long long tap_slab0; // index of this pass's first slab in the caller's [2][n_layers] order
+};
+
+enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3 };
+
+// ---- basis construction (fp64 closed form, rounded once) -------------------------
+// G: [Kpad/8][Grows][8] fp16.  Folded: rows [0,Mpad) even part, rows [Mpad,2Mpad) odd part.
+hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t st);
+// Mf: [Lc][n] fp32 row-major.
+hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, hipStream_t st);
+
+// ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
+hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
+hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
+                               const _Float16* ws, float* tap, hipStream_t st);
+
+// ---- fp32 cache ------------------------------------------------------------------------
+hipError_t launch_prepare_f32(const SlabTable& tab, const Geom& g, float* ws, hipStream_t st);
+hipError_t launch_contract_f32(const SlabTable& tab, const Geom& g, const float* Mf,
+                               const float* ws, float* tap, hipStream_t st);
+
+// ---- tail move: rows [src, src+rows) -> [dst, dst+rows) of every head-tensor; ranges must not overlap
+hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes, int src_row,
+                            int dst_row, int rows, hipStream_t st);
+
+}  // namespace freqkv

@@ -1,0 +1,598 @@
+// gfx950 kernels of libfreqkv.
+//
+// The whole compression of one span (orthonormal DCT-II, keep Lc coefficients,
+// Lc-point inverse, sqrt(Lc/n) rescale: Sec. 3.3 Eq. 2-3 with the Appendix-A
+// transforms) is ONE linear map y = M x per channel, with
+//     M[m][j] = (1/2n) * ( D(a_m - b_j) + D(a_m + b_j) ),
+//     a_m = pi(2m+1)/(2Lc),  b_j = pi(2j+1)/(2n),  D(t) = sin((Lc-1/2)t)/sin(t/2),
+// (the two cosine sums collapse to Dirichlet kernels).  M is centro-symmetric,
+// M[Lc-1-m][n-1-j] = M[m][j], so for even n and Lc the map splits into two
+// half-size maps on the symmetric and antisymmetric parts of x:
+//     xe_j = x_j + x_{n-1-j},  xo_j = x_j - x_{n-1-j}           (j < n/2)
+//     E = Ge xe,  O = Go xo,   Ge/Go[m][j] = (M[m][j] +/- M[Lc-1-m][j]) / 2   (m < Lc/2)
+//     y_m = E_m + O_m,         y_{Lc-1-m} = E_m - O_m
+// which halves the multiply-adds.  The kernels below build Ge/Go (or M), fold and
+// convert the span into an MFMA-ready fp16 workspace, and contract on the matrix
+// cores with fp32 accumulation, writing the Lc rows straight into the cache.
+#include "freqkv_internal.h"
+
+namespace freqkv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Register
+// arrays indexed through it can never fall back to dynamic indexing (and hence to scratch memory).
+template <int I> struct IC { static constexpr int value = I; };
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// addressing helpers
+// ------------------------------------------------------------------------------------------
+
+// Byte address of (token 0, channel c) of the head-tensor that owns virtual column vcol.
+__device__ __forceinline__ char* column_base(const SlabTable& tab, const Geom& g, int vcol,
+                                             int elem_bytes, int* ht_out)
+{
+    int ht   = vcol / g.d;
+    int c    = vcol - ht * g.d;
+    int slab = ht / g.hts_per_slab;
+    int r    = ht - slab * g.hts_per_slab;
+    int b    = r / g.n_heads;
+    int h    = r - b * g.n_heads;
+    if (ht_out) *ht_out = ht;
+    long long off = (long long)b * g.stride_batch + (long long)h * g.stride_head + c;
+    return tab.base[slab] + off * elem_bytes;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// round-to-nearest-even float -> bfloat16 bits
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ------------------------------------------------------------------------------------------
+// basis: fp64 closed form with integer range reduction
+// ------------------------------------------------------------------------------------------
+
+// D(theta) for theta = pi*q/(2*n*Lc), i.e. sin(pi*q*(2Lc-1)/Q) / sin(pi*q/Q), Q = 4*n*Lc.
+__device__ double dirichlet_q(long long q, long long Q, long long twoLm1)
+{
+    if (q == 0) return (double)twoLm1;
+    long long r = (q % (2 * Q)) * 1;          // |q| < Q already
+    long long num = (r * twoLm1) % (2 * Q);   // |r*twoLm1| < 2^63 for spans up to 2^20 rows
+    double s_num = sinpi((double)num / (double)Q);
+    double s_den = sinpi((double)q / (double)Q);
+    return s_num / s_den;
+}
+
+__device__ double operator_entry(int m, int j, long long n, long long Lc, double scale)
+{
+    long long Q  = 4 * n * Lc;
+    long long am = (2LL * m + 1) * n;
+    long long bj = (2LL * j + 1) * Lc;
+    double v = dirichlet_q(am - bj, Q, 2 * Lc - 1) + dirichlet_q(am + bj, Q, 2 * Lc - 1);
+    return v * scale / (2.0 * (double)n);
+}
+
+// G[kg][row][8]: one thread fills one 16-byte group of 8 consecutive k.
+__global__ void k_basis_f16(_Float16* __restrict__ G, Geom g, double scale)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    long long total = (long long)(g.Kpad / 8) * g.Grows;
+    if (idx >= total) return;
+    int kg  = (int)(idx / g.Grows);
+    int row = (int)(idx - (long long)kg * g.Grows);
+    int parity = 0, m = row;
+    if (g.fold && row >= g.Mpad) { parity = 1; m = row - g.Mpad; }
+    half8 out;
+    for (int i = 0; i < 8; ++i) {
+        int j = kg * 8 + i;
+        double v = 0.0;
+        if (m < g.Mh && j < g.Kh) {
+            double a = operator_entry(m, j, g.n, g.Lc, scale);
+            if (g.fold) {
+                double b = operator_entry(g.Lc - 1 - m, j, g.n, g.Lc, scale);
+                v = parity ? 0.5 * (a - b) : 0.5 * (a + b);
+            } else {
+                v = a;
+            }
+        }
+        out[i] = (_Float16)v;
+    }
+    *(half8*)(G + idx * 8) = out;
+}
+
+__global__ void k_basis_f32(float* __restrict__ Mf, int n, int Lc, double scale)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long long)n * Lc) return;
+    int m = (int)(idx / n), j = (int)(idx - (long long)m * n);
+    Mf[idx] = (float)operator_entry(m, j, n, Lc, scale);
+}
+
+hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t st)
+{
+    double scale = rescale ? 1.0 : sqrt((double)g.n / (double)g.Lc);
+    long long total = (long long)(g.Kpad / 8) * g.Grows;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(k_basis_f16, dim3(blocks), dim3(256), 0, st, G, g, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, hipStream_t st)
+{
+    double scale = rescale ? 1.0 : sqrt((double)n / (double)Lc);
+    long long total = (long long)n * Lc;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(k_basis_f32, dim3(blocks), dim3(256), 0, st, Mf, n, Lc, scale);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// prepare (bf16 cache): fold + convert the span into the MFMA-ready workspace
+//
+// Workspace layout, in 16-byte groups of 8 consecutive k (fp16):
+//     ws[coltile][kstage][parity][kgroup 0..3][column 0..127][8]
+// so one pipeline stage of one column tile is P*8 KiB of contiguous memory, already in
+// the order the contraction's LDS fragments are read.
+// ------------------------------------------------------------------------------------------
+
+template <bool FOLD>
+__global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Float16* __restrict__ ws)
+{
+    constexpr int P = FOLD ? 2 : 1;
+    const int ct   = blockIdx.x;
+    const int ks   = blockIdx.y;
+    const int kg   = threadIdx.x >> 6;        // one wave per group of 8 k
+    const int lane = threadIdx.x & 63;
+    const int col  = lane * 2;                // two adjacent channels per lane
+    const int vcol = ct * kColTile + col;
+    const int j0   = (ks * 4 + kg) * 8;
+
+    uint32_t a[8], b[8];
+    const bool colok = vcol < g.ncols;
+    const char* base = colok ? column_base(tab, g, vcol, 2, nullptr) : nullptr;
+    const long long rowb = g.stride_token * 2;   // bytes per token row
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int j = j0 + i;
+        bool ok = colok && j < g.Kh;
+        a[i] = ok ? *(const uint32_t*)(base + (long long)(g.S + j) * rowb) : 0u;
+        b[i] = (FOLD && ok) ? *(const uint32_t*)(base + (long long)(g.S + g.n - 1 - j) * rowb) : 0u;
+    }
+    half8 e0, e1, o0, o1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float a0 = bf16_to_f32(a[i] & 0xffffu), a1 = bf16_to_f32(a[i] >> 16);
+        if (FOLD) {
+            float b0 = bf16_to_f32(b[i] & 0xffffu), b1 = bf16_to_f32(b[i] >> 16);
+            e0[i] = (_Float16)(a0 + b0); e1[i] = (_Float16)(a1 + b1);
+            o0[i] = (_Float16)(a0 - b0); o1[i] = (_Float16)(a1 - b1);
+        } else {
+            e0[i] = (_Float16)a0; e1[i] = (_Float16)a1;
+        }
+    }
+    // 16-byte group index of (parity 0, kg, col)
+    size_t stage = ((size_t)ct * g.nkstages + ks) * P;
+    size_t ge = ((stage + 0) * 4 + kg) * kColTile + col;
+    half8* w = (half8*)ws;
+    w[ge] = e0; w[ge + 1] = e1;
+    if (FOLD) {
+        size_t go = ((stage + 1) * 4 + kg) * kColTile + col;
+        w[go] = o0; w[go + 1] = o1;
+    }
+}
+
+hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st)
+{
+    dim3 grid(g.ncoltiles, g.nkstages);
+    if (g.fold) hipLaunchKernelGGL(k_prepare_bf16<true>,  grid, dim3(256), 0, st, tab, g, ws);
+    else        hipLaunchKernelGGL(k_prepare_bf16<false>, grid, dim3(256), 0, st, tab, g, ws);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// contraction on the matrix cores
+//
+// Workgroup = 4 waves, each wave owns a 128(row) x 128(column) fp32 accumulator tile
+// (4x4 blocks of v_mfma_f32_32x32x16_f16).  Folded: waves are (parity, row half) of a
+// 256-row-per-parity tile.  Plain: waves are the four 128-row quarters of a 512-row tile.
+//   - operand A (basis) is private to a wave: loaded global -> registers, already in
+//     fragment order ([kgroup][row][8]: lane L takes row L%32, k group L/32);
+//   - operand B (folded span) is shared by the waves: one contiguous stage of the workspace
+//     is copied global -> LDS and read back as 16-byte fragments (lane L: column L%32,
+//     k group L/32), conflict-free.
+// ------------------------------------------------------------------------------------------
+
+// 16-byte global load the compiler does not track: the caller places the s_waitcnt vmcnt itself
+// (the three-deep pipeline below needs exact partial waits, which the automatic placement loses at
+// loop headers).  The result must not be read before that wait.
+template <int OFFSET>
+__device__ __forceinline__ half8 gload16_async(const half8* p)
+{
+    half8 v;
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(v) : "v"(p), "n"(OFFSET) : "memory");
+    return v;
+}
+
+__device__ __forceinline__ void stage_x_to_lds(const char* __restrict__ src, char* lds, int bytes,
+                                               int wave, int lane)
+{
+    // 256 lanes x 16 B = 4 KiB per round
+    for (int r = 0; r < bytes / 4096; ++r) {
+        const char* s = src + r * 4096 + wave * 1024 + lane * 16;
+        char* d = lds + r * 4096 + wave * 1024;        // wave-uniform; the hardware adds lane*16
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)s,
+                                         (__attribute__((address_space(3))) void*)d, 16, 0, 0);
+    }
+}
+
+template <bool FOLD>
+__global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
+                                                         const _Float16* __restrict__ G,
+                                                         const _Float16* __restrict__ ws,
+                                                         float* __restrict__ tap)
+{
+    constexpr int P = FOLD ? 2 : 1;
+    constexpr int XSTAGE = P * 8192;                       // bytes per pipeline stage
+    constexpr int LDS_BYTES = FOLD ? 131072 : 3 * XSTAGE;  // 3 pipeline slots; folded epilogue exchanges 4 x 32 KiB
+    __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // blockIdx -> (column tile, row tile).  Workgroups are dealt round-robin to the 8 XCDs, so
+    // within a group of 8 column tiles the XCD index picks the column tile and consecutive slots
+    // on one XCD are the row tiles of the same columns: they share that XCD's L2 for the span.
+    int ct, mt;
+    {
+        const int bid = blockIdx.x;
+        const int per_group = 8 * g.nmtiles;
+        const int full = g.ncoltiles / 8;
+        const int grp = bid / per_group;
+        if (grp < full) {
+            int local = bid - grp * per_group;
+            ct = grp * 8 + (local & 7);
+            mt = local >> 3;
+        } else {
+            int rem = g.ncoltiles - full * 8;
+            int local = bid - full * per_group;
+            ct = full * 8 + local % rem;
+            mt = local / rem;
+        }
+    }
+
+    const int par   = FOLD ? (wave >> 1) : 0;
+    const int rhalf = FOLD ? (wave & 1) : wave;
+    // first basis row of this wave in G's row order
+    const int grow0 = FOLD ? (par * g.Mpad + mt * kRowsFold + rhalf * 128)
+                           : (mt * kRowsPlain + wave * 128);
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nks = g.nkstages;
+    const char* xsrc = (const char*)ws + (size_t)ct * nks * XSTAGE;
+    const half8* Gv = (const half8*)G;
+    // lane's 16-byte group in G for (stage s, substep u, row block mb): ((s*4 + u*2 + lhi) * Grows + grow0 + mb*32 + l32)
+    const size_t a_lane = (size_t)lhi * g.Grows + grow0 + l32;
+    const size_t a_kstep = (size_t)2 * g.Grows;     // one 16-k substep
+    const size_t a_stage = (size_t)4 * g.Grows;
+
+    // Three-deep software pipeline.  In iteration s the loads of stage s+2 are issued (span stage
+    // -> LDS slot (s+2)%3, basis fragments -> register set (s+2)%3), the matrix cores work on stage
+    // s, and the wait before the closing barrier only covers stage s+1, so every load has two
+    // iterations of matrix work to arrive.  kLoadsPerStage counts one wave's vector loads per stage.
+    constexpr int kLoadsPerStage = XSTAGE / 4096 + 8;
+    half8 aset[3][2][4];
+
+    auto issue_stage = [&](int st, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        stage_x_to_lds(xsrc + (size_t)st * XSTAGE, smem + slot * XSTAGE, XSTAGE, wave, lane);
+        const size_t a0 = a_lane + (size_t)st * a_stage;
+        static_for<2>([&](auto u) {
+            const half8* pa = Gv + a0 + u.value * a_kstep;
+            static_for<4>([&](auto mb) { aset[slot][u.value][mb.value] = gload16_async<mb.value * 512>(pa); });
+        });
+    };
+
+    issue_stage(0, IC<0>{});
+    if (nks > 1) issue_stage(1, IC<1>{});
+    // Hand-placed wait + barrier: __syncthreads() would force vmcnt(0) and drain the prefetch.
+    if (nks > 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kLoadsPerStage) : "memory");
+    else         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+    // One pipeline step.  PRE (compile time): issue the loads of stage st+2.  Keeping the steps
+    // free of data-dependent branches lets the compiler count outstanding loads exactly.
+    auto step = [&](int st, auto slot_c, auto pre_c) {
+        constexpr int slot = decltype(slot_c)::value;
+        constexpr bool PRE = decltype(pre_c)::value != 0;
+        constexpr int slot2 = (slot + 2) % 3;
+        const char* xs = smem + slot * XSTAGE + par * 8192;
+        half8 xf[2][4];
+        static_for<2>([&](auto u) {
+            static_for<4>([&](auto nb) {
+                xf[u.value][nb.value] =
+                    *(const half8*)(xs + (((u.value * 2 + lhi) * kColTile) + nb.value * 32 + l32) * 16);
+            });
+        });
+        if constexpr (PRE) issue_stage(st + 2, IC<slot2>{});
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<2>([&](auto u) {
+            static_for<4>([&](auto mb) {
+                static_for<4>([&](auto nb) {
+                    acc[mb.value][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        aset[slot][u.value][mb.value], xf[u.value][nb.value], acc[mb.value][nb.value], 0, 0, 0);
+                });
+            });
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (PRE) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kLoadsPerStage) : "memory");
+        else               asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
+    // nks = 3q + r with r in {2,3,4} (or nks == 1): q full rounds of three prefetching steps, then a
+    // straight-line tail.  Slots rotate 0,1,2 and every round starts at slot 0.
+    int s = 0;
+    if (nks >= 2) {
+        const int q = (nks - 2) / 3;
+        for (int it = 0; it < q; ++it, s += 3) {
+            step(s, IC<0>{}, IC<1>{});
+            step(s + 1, IC<1>{}, IC<1>{});
+            step(s + 2, IC<2>{}, IC<1>{});
+        }
+        const int r = nks - s;
+        if (r == 2) {
+            step(s, IC<0>{}, IC<0>{});
+            step(s + 1, IC<1>{}, IC<0>{});
+        } else if (r == 3) {
+            step(s, IC<0>{}, IC<1>{});
+            step(s + 1, IC<1>{}, IC<0>{});
+            step(s + 2, IC<2>{}, IC<0>{});
+        } else {
+            step(s, IC<0>{}, IC<1>{});
+            step(s + 1, IC<1>{}, IC<1>{});
+            step(s + 2, IC<2>{}, IC<0>{});
+            step(s + 3, IC<0>{}, IC<0>{});
+        }
+    } else {
+        step(0, IC<0>{}, IC<0>{});
+    }
+
+    // ---- epilogue ------------------------------------------------------------------------
+    // Accumulator layout of a 32x32 block: register r of lane L is row 8*(r/4) + 4*(L/32) + r%4,
+    // column L%32.
+    char* colptr[4];
+    int   colht[4];
+    bool  colok[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        int vcol = ct * kColTile + nb * 32 + l32;
+        colok[nb] = vcol < g.ncols;
+        colht[nb] = 0;
+        colptr[nb] = colok[nb] ? column_base(tab, g, vcol, 2, &colht[nb]) : nullptr;
+    }
+    const long long rowb = g.stride_token * 2;
+
+    auto store_row = [&](int nb, int row, float val) {
+        // row = output row index m in [0, Lc)
+        *(uint16_t*)(colptr[nb] + (long long)(g.S + row) * rowb) = f32_to_bf16(val);
+        if (tap) {
+            int vcol = ct * kColTile + nb * 32 + l32;
+            int c = vcol - colht[nb] * g.d;
+            long long ht_global = g.tap_slab0 * g.hts_per_slab + colht[nb];
+            tap[(ht_global * g.Lc + row) * g.d + c] = val;
+        }
+    };
+
+    if constexpr (FOLD) {
+        float* ex = (float*)smem;
+        // parity-0 waves finish row blocks 0,1 and hand blocks 2,3 to their partner; parity-1 waves
+        // the other way round.  Swap so that blocks 0,1 are always the ones kept.
+        if (par != 0) {
+            static_for<2>([&](auto mb2) {
+                static_for<4>([&](auto nb) {
+                    f32x16 t = acc[mb2.value][nb.value];
+                    acc[mb2.value][nb.value] = acc[2 + mb2.value][nb.value];
+                    acc[2 + mb2.value][nb.value] = t;
+                });
+            });
+        }
+        float* mine = ex + wave * 8192;
+        static_for<2>([&](auto mb2) {
+            static_for<4>([&](auto nb) {
+                static_for<16>([&](auto r) {
+                    mine[((mb2.value * 4 + nb.value) * 16 + r.value) * 64 + lane] = acc[2 + mb2.value][nb.value][r.value];
+                });
+            });
+        });
+        __syncthreads();
+        const float* theirs = ex + (wave ^ 2) * 8192;
+        const int rbase = mt * kRowsFold + rhalf * 128 + (par == 0 ? 0 : 64);
+        const float osign = (par == 0) ? 1.f : -1.f;
+        static_for<2>([&](auto mb2) {
+            static_for<4>([&](auto nb) {
+                static_for<16>([&](auto r) {
+                    float other = theirs[((mb2.value * 4 + nb.value) * 16 + r.value) * 64 + lane];
+                    float own = acc[mb2.value][nb.value][r.value];
+                    // parity 0: own = E, other = O; parity 1: own = O, other = E
+                    float top = own + other;                    // E + O
+                    float bot = (own - other) * osign;          // E - O
+                    int rh = rbase + mb2.value * 32 + (r.value >> 2) * 8 + lhi * 4 + (r.value & 3);
+                    if (colok[nb.value] && rh < g.Mh) {
+                        store_row(nb.value, rh, top);
+                        store_row(nb.value, g.Lc - 1 - rh, bot);
+                    }
+                });
+            });
+        });
+    } else {
+        const int rbase = mt * kRowsPlain + wave * 128;
+        static_for<4>([&](auto mb) {
+            static_for<4>([&](auto nb) {
+                static_for<16>([&](auto r) {
+                    int row = rbase + mb.value * 32 + (r.value >> 2) * 8 + lhi * 4 + (r.value & 3);
+                    if (colok[nb.value] && row < g.Mh) store_row(nb.value, row, acc[mb.value][nb.value][r.value]);
+                });
+            });
+        });
+    }
+}
+
+hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
+                               const _Float16* ws, float* tap, hipStream_t st)
+{
+    dim3 grid((unsigned)g.ncoltiles * (unsigned)g.nmtiles);
+    if (g.fold) hipLaunchKernelGGL(k_contract_f16<true>,  grid, dim3(256), 0, st, tab, g, G, ws, tap);
+    else        hipLaunchKernelGGL(k_contract_f16<false>, grid, dim3(256), 0, st, tab, g, G, ws, tap);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 cache: copy the span out, then a plain LDS-tiled fp32 FMA contraction y = Mf * x
+// workspace: xs[n][ncolsf] fp32, ncolsf = ncols rounded up to 64 (pad columns are zero)
+// ------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ int f32_cols_padded(const Geom& g) { return (g.ncols + 63) & ~63; }
+
+__global__ __launch_bounds__(256) void k_prepare_f32(SlabTable tab, Geom g, float* __restrict__ ws)
+{
+    const int ncp = f32_cols_padded(g);
+    const int vcol = blockIdx.x * 256 + threadIdx.x;
+    if (vcol >= ncp) return;
+    const char* base = vcol < g.ncols ? column_base(tab, g, vcol, 4, nullptr) : nullptr;
+    for (int j = blockIdx.y; j < g.n; j += gridDim.y) {
+        float v = base ? *(const float*)(base + (long long)(g.S + j) * g.stride_token * 4) : 0.f;
+        ws[(size_t)j * ncp + vcol] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_contract_f32(SlabTable tab, Geom g, const float* __restrict__ Mf,
+                                                      const float* __restrict__ ws, float* __restrict__ tap)
+{
+    __shared__ float As[16][65];   // [k][m]
+    __shared__ float Bs[16][64];   // [k][col]
+    const int ncp = f32_cols_padded(g);
+    const int c0 = blockIdx.x * 64, m0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < g.n; k0 += 16) {
+        for (int e = threadIdx.x; e < 64 * 16; e += 256) {
+            int mm = e >> 4, kk = e & 15;
+            int m = m0 + mm, j = k0 + kk;
+            As[kk][mm] = (m < g.Lc && j < g.n) ? Mf[(size_t)m * g.n + j] : 0.f;
+        }
+        for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+            int kk = e >> 6, cc = e & 63;
+            int j = k0 + kk;
+            Bs[kk][cc] = (j < g.n) ? ws[(size_t)j * ncp + c0 + cc] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b[i] = Bs[kk][tx * 4 + i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[i][q] = fmaf(a[i], b[q], acc[i][q]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int vcol = c0 + tx * 4 + q;
+        if (vcol >= g.ncols) continue;
+        int ht;
+        char* base = column_base(tab, g, vcol, 4, &ht);
+        int c = vcol - ht * g.d;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int m = m0 + ty * 4 + i;
+            if (m >= g.Lc) continue;
+            *(float*)(base + (long long)(g.S + m) * g.stride_token * 4) = acc[i][q];
+            if (tap) {
+                long long ht_global = g.tap_slab0 * g.hts_per_slab + ht;
+                tap[(ht_global * g.Lc + m) * g.d + c] = acc[i][q];
+            }
+        }
+    }
+}
+
+hipError_t launch_prepare_f32(const SlabTable& tab, const Geom& g, float* ws, hipStream_t st)
+{
+    int ncp = (g.ncols + 63) & ~63;
+    dim3 grid((ncp + 255) / 256, g.n < 65535 ? g.n : 65535);
+    hipLaunchKernelGGL(k_prepare_f32, grid, dim3(256), 0, st, tab, g, ws);
+    return hipGetLastError();
+}
+
+hipError_t launch_contract_f32(const SlabTable& tab, const Geom& g, const float* Mf, const float* ws,
+                               float* tap, hipStream_t st)
+{
+    int ncp = (g.ncols + 63) & ~63;
+    dim3 grid(ncp / 64, (g.Lc + 63) / 64);
+    hipLaunchKernelGGL(k_contract_f32, grid, dim3(256), 0, st, tab, g, Mf, ws, tap);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// tail move: rows [src, src+rows) -> [dst, dst+rows), 16 bytes per lane; ranges are disjoint
+// ------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void k_move_rows(SlabTable tab, Geom g, int elem_bytes, int src_row,
+                                                   int dst_row, int per16)
+{
+    // per16 = elements per 16-byte group (8 for bf16, 4 for fp32); d is a multiple of 8
+    const long long grp = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long ngroups = (long long)g.ncols / per16;
+    if (grp >= ngroups) return;
+    const int row = blockIdx.y;
+    const int vcol = (int)(grp * per16);
+    char* base = column_base(tab, g, vcol, elem_bytes, nullptr);
+    const long long rowb = g.stride_token * elem_bytes;
+    u32x4 v = *(const u32x4*)(base + (long long)(src_row + row) * rowb);
+    *(u32x4*)(base + (long long)(dst_row + row) * rowb) = v;
+}
+
+hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes, int src_row, int dst_row,
+                            int rows, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    int per16 = 16 / elem_bytes;
+    long long ngroups = (long long)g.ncols / per16;
+    // gridDim.y is limited to 65535 rows per launch
+    for (int r0 = 0; r0 < rows; r0 += 65535) {
+        int nr = rows - r0 < 65535 ? rows - r0 : 65535;
+        dim3 grid((unsigned)((ngroups + 255) / 256), nr);
+        hipLaunchKernelGGL(k_move_rows, grid, dim3(256), 0, st, tab, g, elem_bytes, src_row + r0,
+                           dst_row + r0, per16);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace freqkv

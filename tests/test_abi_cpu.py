@@ -1,0 +1,179 @@
+"""CPU-only checks of the C ABI: the library loads, exports what the header declares, and its host
+logic (plan arithmetic, argument validation) agrees with the paper's integers and the oracle's rules."""
+import ctypes as C
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+import paper_2505_00570_amd as fk
+from paper_2505_00570_amd import binding
+from paper_2505_00570_amd.binding import Layout, Plan, Profile
+from oracle import freqkv_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "freqkv.h")
+
+
+def _layout(dtype=fk.BF16, n_layers=32, batch=1, n_heads=8, cap=8192, d=128):
+    L = Layout()
+    L.dtype, L.n_layers, L.batch, L.token_capacity = dtype, n_layers, batch, cap
+    L.stride_token = d
+    L.stride_head = cap * d
+    L.stride_batch = n_heads * cap * d
+    L.stride_layer = batch * n_heads * cap * d
+    return L
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(freqkv_[a-z_0-9]+)\s*\(", text))
+    assert {"freqkv_plan", "freqkv_compress", "freqkv_status_string", "freqkv_shutdown"} <= declared
+    lib = fk.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert fk.version() >= 100
+
+
+def test_struct_layout_matches_header():
+    """sizeof/offsetof of the ctypes mirrors equal what a C compiler sees in freqkv.h."""
+    src = r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "freqkv.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu %zu\n", sizeof(freqkv_layout_t), offsetof(freqkv_layout_t, stride_token),
+         offsetof(freqkv_layout_t, workspace), offsetof(freqkv_layout_t, tap_f32),
+         sizeof(freqkv_plan_t), sizeof(freqkv_profile_t));
+  printf("%zu %zu %zu\n", offsetof(freqkv_plan_t, workspace_bytes), offsetof(freqkv_plan_t, flops_dense),
+         offsetof(freqkv_profile_t, ms_prepare));
+  return 0; }
+'''
+    with tempfile.TemporaryDirectory() as td:
+        c = os.path.join(td, "t.c")
+        open(c, "w").write(src)
+        exe = os.path.join(td, "t")
+        subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), c, "-o", exe])
+        out = subprocess.check_output([exe]).decode().split()
+    got = [int(x) for x in out]
+    want = [C.sizeof(Layout), Layout.stride_token.offset, Layout.workspace.offset, Layout.tap_f32.offset,
+            C.sizeof(Plan), C.sizeof(Profile), Plan.workspace_bytes.offset, Plan.flops_dense.offset,
+            Profile.ms_prepare.offset]
+    assert got == want
+
+
+def test_status_strings():
+    assert fk.status_string(0) == "FREQKV_OK"
+    assert fk.status_string(1) == "FREQKV_NOOP"
+    assert fk.status_string(-3) == "FREQKV_E_WORKSPACE"
+    assert "UNKNOWN" in fk.status_string(-99)
+
+
+def test_plan_matches_paper_integers():
+    # Sec. 4.1: window 4096, 4 sinks, ratio 0.5: 4092 states -> 2046
+    rc, p = fk.plan(_layout(n_heads=32, cap=4096), 32, 128, 4096, 4096, 4, 0.5)
+    assert rc == 0 and (p.span_len, p.retained_len, p.new_len) == (4092, 2046, 2050)
+    assert p.head_tensors == 2 * 32 * 32
+    # LLaMA-3 window
+    rc, p = fk.plan(_layout(), 8, 128, 8192, 8192, 4, 0.5)
+    assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 1)
+    assert p.flops_dense == pytest.approx(2.0 * 4094 * 8188 * 128 * 512)
+    assert p.flops_executed == pytest.approx(p.flops_dense / 2)
+    assert p.bytes_algorithmic == pytest.approx((8188 + 4094) * 128 * 2 * 512)
+    assert p.workspace_min_bytes <= p.workspace_bytes
+    assert p.basis_bytes == 2 * 2048 * 4096 * 2
+
+
+@pytest.mark.parametrize("window,sink,ratio,cur", [(4096, 4, 0.5, 4096), (4096, 0, 0.25, 5000), (512, 4, 0.5, 512),
+                                                   (701, 4, 0.5, 701), (100, 8, 0.75, 130), (64, 2, 0.01, 64),
+                                                   (50, 8, 1.0, 70), (4096, 4, 0.3, 4096)])
+def test_plan_agrees_with_oracle_rules(window, sink, ratio, cur):
+    rc, p = fk.plan(_layout(cap=max(cur, window)), 8, 128, cur, window, sink, ratio)
+    assert rc == 0
+    assert p.span_len == window - sink
+    assert p.retained_len == orc.retained_len(window - sink, ratio)
+    assert p.new_len == orc.new_len(cur, window, sink, ratio)
+    if ratio == 1.0:
+        assert p.variant == 0 and p.workspace_bytes == 0
+    elif (window - sink) % 2 == 0 and p.retained_len % 2 == 0:
+        assert p.variant == 1
+    else:
+        assert p.variant == 2
+
+
+def test_plan_noop_below_window():
+    rc, p = fk.plan(_layout(), 8, 128, 100, 8192, 4, 0.5)
+    assert rc == 1 and p.retained_len == 4094
+    assert p.new_len == 4 + 4094            # plan for a full cache without a tail
+
+
+def test_trigger_schedule_from_plan_matches_paper_counts():
+    # count compressions while T tokens stream in, using only the library's plan arithmetic
+    def count(total, window, sink, ratio):
+        cur, fed, n = 0, 0, 0
+        while fed < total:
+            if cur >= window:
+                _, p = fk.plan(_layout(cap=window), 8, 128, cur, window, sink, ratio)
+                cur, n = p.new_len, n + 1
+            take = min(total - fed, window - cur)
+            cur, fed = cur + take, fed + take
+        return n
+    for total, expect in [(4096, 0), (8192, 3), (12288, 5), (16384, 7), (32768, 15), (65536, 31),
+                          (131072, 63), (262144, 127)]:
+        assert count(total, 4096, 4, 0.5) == expect
+        assert orc.trigger_count(total, 4096, 4, 0.5) == expect
+    assert count(131072, 8192, 4, 0.5) == 31
+
+
+BAD = [
+    dict(n_heads=0), dict(head_dim=4), dict(n_sink=-1), dict(window=5, n_sink=4), dict(ratio=0.0),
+    dict(ratio=1.5), dict(ratio=float("nan")), dict(cur_len=9000), dict(cur_len=-1),
+]
+
+
+@pytest.mark.parametrize("bad", BAD)
+def test_plan_rejects_invalid_arguments(bad):
+    a = dict(n_heads=8, head_dim=128, cur_len=8192, window=8192, n_sink=4, ratio=0.5)
+    a.update(bad)
+    rc, _ = fk.plan(_layout(), a["n_heads"], a["head_dim"], a["cur_len"], a["window"], a["n_sink"], a["ratio"],
+                    check=False)
+    assert rc == binding.E_INVALID
+
+
+def test_plan_rejects_bad_layout():
+    for field, val in [("dtype", 7), ("n_layers", 0), ("batch", 0), ("stride_token", 64), ("stride_token", 132),
+                       ("stride_head", 12), ("pointer_table", 2), ("flags", 0x80)]:
+        L = _layout()
+        setattr(L, field, val)
+        rc, _ = fk.plan(L, 8, 128, 8192, 8192, 4, 0.5, check=False)
+        assert rc == binding.E_INVALID, field
+    rc, _ = fk.plan(_layout(d=12), 8, 12, 8192, 8192, 4, 0.5, check=False)
+    assert rc == binding.E_UNSUPPORTED
+    assert fk.load().freqkv_plan(None, 8, 128, 1, 1, 0, 0.5, None) == binding.E_INVALID
+
+
+def test_compress_validates_before_touching_the_device():
+    """Every one of these returns before the first HIP call, so it runs without a GPU."""
+    L = _layout()
+    fake = 0x7F0000000000          # 16-byte aligned, never dereferenced on these paths
+    # cache not full -> NOOP
+    assert fk.compress(fake, fake, L, 8, 128, 100, 8192, 4, 0.5, check=False) == 1
+    # ratio 1 -> identity, nothing enqueued
+    assert fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 1.0, check=False) == 0
+    # null / misaligned cache pointers
+    assert fk.compress(None, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_INVALID
+    assert fk.compress(fake + 2, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_INVALID
+    # missing / small / misaligned workspace
+    assert fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_WORKSPACE
+    _, p = fk.plan(L, 8, 128, 8192, 8192, 4, 0.5)
+    L.workspace, L.workspace_bytes = fake, p.workspace_min_bytes - 1
+    assert fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_WORKSPACE
+    L.workspace, L.workspace_bytes = fake + 16, p.workspace_bytes
+    assert fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_WORKSPACE
+    with pytest.raises(fk.FreqKVError):
+        fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5)
+    # invalid scalars
+    assert fk.compress(fake, fake, L, 8, 128, 9000, 8192, 4, 0.5, check=False) == binding.E_INVALID
