@@ -214,31 +214,19 @@ hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws
 //   - operand A (basis) is private to a wave: loaded global -> registers, already in
 //     fragment order ([kgroup][row][8]: lane L takes row L%32, k group L/32);
 //   - operand B (folded span) is shared by the waves: one contiguous stage of the workspace
-//     is copied global -> LDS and read back as 16-byte fragments (lane L: column L%32,
-//     k group L/32), conflict-free.
+//     is copied global -> registers -> LDS (three slots) and read back as 16-byte fragments
+//     (lane L: column L%32, k group L/32), conflict-free.
+// Pipeline, step s: issue the global loads of span stage s+2 and basis stage s+1, read the LDS
+// fragments of stage s+1, run the 32 MFMAs of stage s, store span stage s+2 to LDS, barrier.
 // ------------------------------------------------------------------------------------------
 
-// 16-byte global load the compiler does not track: the caller places the s_waitcnt vmcnt itself
-// (the three-deep pipeline below needs exact partial waits, which the automatic placement loses at
-// loop headers).  The result must not be read before that wait.
-template <int OFFSET>
-__device__ __forceinline__ half8 gload16_async(const half8* p)
+// Workgroup barrier that orders LDS traffic only (waits lgkmcnt, not vmcnt): __syncthreads() would
+// also drain every outstanding global load and with it the register prefetch of the next stage.
+__device__ __forceinline__ void lds_barrier()
 {
-    half8 v;
-    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(v) : "v"(p), "n"(OFFSET) : "memory");
-    return v;
-}
-
-__device__ __forceinline__ void stage_x_to_lds(const char* __restrict__ src, char* lds, int bytes,
-                                               int wave, int lane)
-{
-    // 256 lanes x 16 B = 4 KiB per round
-    for (int r = 0; r < bytes / 4096; ++r) {
-        const char* s = src + r * 4096 + wave * 1024 + lane * 16;
-        char* d = lds + r * 4096 + wave * 1024;        // wave-uniform; the hardware adds lane*16
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)s,
-                                         (__attribute__((address_space(3))) void*)d, 16, 0, 0);
-    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 template <bool FOLD>
@@ -298,85 +286,99 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
     const size_t a_kstep = (size_t)2 * g.Grows;     // one 16-k substep
     const size_t a_stage = (size_t)4 * g.Grows;
 
-    // Three-deep software pipeline.  In iteration s the loads of stage s+2 are issued (span stage
-    // -> LDS slot (s+2)%3, basis fragments -> register set (s+2)%3), the matrix cores work on stage
-    // s, and the wait before the closing barrier only covers stage s+1, so every load has two
-    // iterations of matrix work to arrive.  kLoadsPerStage counts one wave's vector loads per stage.
-    constexpr int kLoadsPerStage = XSTAGE / 4096 + 8;
-    half8 aset[3][2][4];
+    constexpr int XR = XSTAGE / 4096;       // 16-byte pieces per thread per stage
+    half8 aset[2][2][4];                    // basis fragments [buffer][16-k substep][row block]
+    half8 xf[2][2][4];                      // span fragments  [buffer][16-k substep][column block]
+    half8 xr[XR];                           // span stage in flight global -> LDS
+    const int tid16 = threadIdx.x * 16;
 
-    auto issue_stage = [&](int st, auto slot_c) {
-        constexpr int slot = decltype(slot_c)::value;
-        stage_x_to_lds(xsrc + (size_t)st * XSTAGE, smem + slot * XSTAGE, XSTAGE, wave, lane);
-        const size_t a0 = a_lane + (size_t)st * a_stage;
+    auto load_a = [&](int st, auto buf) {
+        const half8* pa = Gv + a_lane + (size_t)st * a_stage;
         static_for<2>([&](auto u) {
-            const half8* pa = Gv + a0 + u.value * a_kstep;
-            static_for<4>([&](auto mb) { aset[slot][u.value][mb.value] = gload16_async<mb.value * 512>(pa); });
+            static_for<4>([&](auto mb) { aset[buf.value][u.value][mb.value] = pa[u.value * a_kstep + mb.value * 32]; });
         });
     };
-
-    issue_stage(0, IC<0>{});
-    if (nks > 1) issue_stage(1, IC<1>{});
-    // Hand-placed wait + barrier: __syncthreads() would force vmcnt(0) and drain the prefetch.
-    if (nks > 1) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kLoadsPerStage) : "memory");
-    else         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-
-    // One pipeline step.  PRE (compile time): issue the loads of stage st+2.  Keeping the steps
-    // free of data-dependent branches lets the compiler count outstanding loads exactly.
-    auto step = [&](int st, auto slot_c, auto pre_c) {
-        constexpr int slot = decltype(slot_c)::value;
-        constexpr bool PRE = decltype(pre_c)::value != 0;
-        constexpr int slot2 = (slot + 2) % 3;
-        const char* xs = smem + slot * XSTAGE + par * 8192;
-        half8 xf[2][4];
+    auto load_x = [&](int st) {
+        const char* src = xsrc + (size_t)st * XSTAGE + tid16;
+        static_for<XR>([&](auto r) { xr[r.value] = *(const half8*)(src + r.value * 4096); });
+    };
+    auto write_x = [&](int slot_off) {
+        static_for<XR>([&](auto r) { *(half8*)(smem + slot_off + r.value * 4096 + tid16) = xr[r.value]; });
+    };
+    auto read_xf = [&](int slot_off, auto buf) {
+        const char* xs = smem + slot_off + par * 8192;
         static_for<2>([&](auto u) {
             static_for<4>([&](auto nb) {
-                xf[u.value][nb.value] =
+                xf[buf.value][u.value][nb.value] =
                     *(const half8*)(xs + (((u.value * 2 + lhi) * kColTile) + nb.value * 32 + l32) * 16);
             });
         });
-        if constexpr (PRE) issue_stage(st + 2, IC<slot2>{});
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mfma_stage = [&](auto buf) {
         static_for<2>([&](auto u) {
             static_for<4>([&](auto mb) {
                 static_for<4>([&](auto nb) {
                     acc[mb.value][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        aset[slot][u.value][mb.value], xf[u.value][nb.value], acc[mb.value][nb.value], 0, 0, 0);
+                        aset[buf.value][u.value][mb.value], xf[buf.value][u.value][nb.value],
+                        acc[mb.value][nb.value], 0, 0, 0);
                 });
             });
         });
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (PRE) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kLoadsPerStage) : "memory");
-        else               asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     };
 
-    // nks = 3q + r with r in {2,3,4} (or nks == 1): q full rounds of three prefetching steps, then a
-    // straight-line tail.  Slots rotate 0,1,2 and every round starts at slot 0.
-    int s = 0;
-    if (nks >= 2) {
-        const int q = (nks - 2) / 3;
-        for (int it = 0; it < q; ++it, s += 3) {
-            step(s, IC<0>{}, IC<1>{});
-            step(s + 1, IC<1>{}, IC<1>{});
-            step(s + 2, IC<2>{}, IC<1>{});
+    // LDS slot byte offsets of stages s, s+1, s+2 (three slots, rotating)
+    int off0 = 0, off1 = XSTAGE, off2 = 2 * XSTAGE;
+    auto rotate = [&]() { int t = off0; off0 = off1; off1 = off2; off2 = t; };
+
+    // MODE 2: stages s+1 and s+2 exist (steady state); 1: only s+1; 0: last stage.
+    auto step = [&](int st, auto buf, auto mode) {
+        constexpr int B = decltype(buf)::value;
+        constexpr int MODE = decltype(mode)::value;
+        if constexpr (MODE >= 2) load_x(st + 2);
+        if constexpr (MODE >= 1) {
+            load_a(st + 1, IC<1 - B>{});
+            read_xf(off1, IC<1 - B>{});
         }
-        const int r = nks - s;
-        if (r == 2) {
-            step(s, IC<0>{}, IC<0>{});
-            step(s + 1, IC<1>{}, IC<0>{});
-        } else if (r == 3) {
-            step(s, IC<0>{}, IC<1>{});
-            step(s + 1, IC<1>{}, IC<0>{});
-            step(s + 2, IC<2>{}, IC<0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_stage(IC<B>{});
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MODE >= 2) write_x(off2);
+        if constexpr (MODE >= 1) lds_barrier();
+        rotate();
+    };
+
+    // prologue: stage 0 (and 1) into LDS, basis stage 0 into registers, fragments of stage 0 read
+    {
+        load_x(0);
+        load_a(0, IC<0>{});
+        write_x(off0);
+        if (nks > 1) {
+            load_x(1);
+            write_x(off1);
+        }
+        lds_barrier();
+        read_xf(off0, IC<0>{});
+    }
+
+    if (nks >= 2) {
+        const int nfull = nks - 2;          // steps with two further stages ahead
+        int st = 0;
+        for (; st + 1 < nfull; st += 2) {
+            step(st, IC<0>{}, IC<2>{});
+            step(st + 1, IC<1>{}, IC<2>{});
+        }
+        if (nfull & 1) {
+            step(st, IC<0>{}, IC<2>{});
+            step(st + 1, IC<1>{}, IC<1>{});
+            step(st + 2, IC<0>{}, IC<0>{});
         } else {
-            step(s, IC<0>{}, IC<1>{});
-            step(s + 1, IC<1>{}, IC<1>{});
-            step(s + 2, IC<2>{}, IC<0>{});
-            step(s + 3, IC<0>{}, IC<0>{});
+            step(st, IC<0>{}, IC<1>{});
+            step(st + 1, IC<1>{}, IC<0>{});
         }
     } else {
         step(0, IC<0>{}, IC<0>{});
     }
+    __syncthreads();      // every wave is done with the LDS slots before the epilogue reuses them
 
     // ---- epilogue ------------------------------------------------------------------------
     // Accumulator layout of a 32x32 block: register r of lane L is row 8*(r/4) + 4*(L/32) + r%4,

@@ -1,0 +1,291 @@
+"""GPU parity: libfreqkv (HIP, through the C ABI) against the fp64 CPU oracle, element by element.
+
+Inputs are the seeded synthetic tensors of paper_2505_00570_amd.synth; the oracle runs on exactly
+the bits the GPU sees (copied to the host before the call).  Tolerances are in tests/_util.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_00570_amd as fk
+from paper_2505_00570_amd import binding, synth
+from paper_2505_00570_amd.cache import CompressedKVCache
+from oracle import freqkv_oracle as orc
+
+from _util import TOL_BF16, TOL_F32, bf16_round, bf16_ulp, f64, rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _mk(wl, seed=0, capacity=None, cur_len=None):
+    """Cache tensors [L,B,H,cap,d] filled with cur_len synthetic tokens; rows beyond hold a canary."""
+    cap = capacity or wl.window
+    cur = cur_len or wl.window
+    k, v = synth.empty_cache(wl, DEV, cap)
+    k.fill_(777.0)
+    v.fill_(-777.0)
+    synth.KVSource(wl, seed, DEV).fill(k, v, 0, cur)
+    return k, v
+
+
+def _run(k, v, wl, cur_len, tap=True, ws_bytes=None, flags=0, check=True):
+    L = binding.layout_for(k, flags=flags)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, cur_len, wl.window, wl.n_sink, wl.retain_ratio)
+    nbytes = p.workspace_bytes if ws_bytes is None else ws_bytes
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), nbytes
+    tapt = None
+    if tap and p.variant != 0:
+        tapt = torch.full((2, wl.n_layers, wl.batch, wl.n_heads, p.retained_len, wl.head_dim), float("nan"),
+                          dtype=torch.float32, device=DEV)
+        L.tap_f32 = tapt.data_ptr()
+    rc = fk.compress(k, v, L, wl.n_heads, wl.head_dim, cur_len, wl.window, wl.n_sink, wl.retain_ratio, check=check)
+    torch.cuda.synchronize()
+    return rc, p, tapt
+
+
+def _check_all_heads(wl, k0, v0, k1, v1, tap, p, cur_len, tol, rescale=True):
+    """Compare every head-tensor with the oracle.  k0/v0: before (host copies), k1/v1: after."""
+    S, W, lc = wl.n_sink, wl.window, p.retained_len
+    worst_tap, worst_store = 0.0, 0.0
+    for kv, (before, after) in enumerate(((k0, k1), (v0, v1))):
+        for l in range(wl.n_layers):
+            for b in range(wl.batch):
+                for h in range(wl.n_heads):
+                    x = f64(before[l, b, h, :cur_len])
+                    ref = orc.compress_head(x, cur_len, W, S, wl.retain_ratio, rescale=rescale)
+                    got = after[l, b, h]
+                    # sinks and tail: bit for bit
+                    assert torch.equal(got[:S], before[l, b, h, :S])
+                    assert torch.equal(got[S + lc:p.new_len], before[l, b, h, W:cur_len])
+                    # rows beyond the old cur_len: untouched
+                    assert torch.equal(got[cur_len:], before[l, b, h, cur_len:])
+                    yref = ref[S:S + lc]
+                    rms = math.sqrt(float((yref ** 2).mean()))
+                    ygot = f64(got[S:S + lc])
+                    if tap is not None:
+                        yt = f64(tap[kv, l, b, h])
+                        assert not np.isnan(yt).any()
+                        worst_tap = max(worst_tap, rel_err(yt, yref))
+                        if wl.dtype == torch.bfloat16:
+                            # the stored value is exactly the fp32 result rounded once to bf16
+                            assert np.array_equal(ygot, bf16_round(yt))
+                        else:
+                            assert np.array_equal(ygot, yt)
+                    if wl.dtype == torch.bfloat16:
+                        # stored bf16: tolerance plus the unavoidable half-ulp of the bf16 grid at |y|
+                        excess = np.abs(ygot - yref) - 0.5 * bf16_ulp(yref)
+                        worst_store = max(worst_store, float(excess.max()) / rms)
+                    else:
+                        worst_store = max(worst_store, rel_err(ygot, yref))
+    _say(f"  worst fp32-tap err/rms {worst_tap:.3e}  worst stored err/rms (beyond bf16 grid) {worst_store:.3e}")
+    assert worst_tap <= tol
+    assert worst_store <= tol
+    return worst_tap
+
+
+# ------------------------------------------------------------------------------------------
+# config 1: Tiny fp32, full comparison
+# ------------------------------------------------------------------------------------------
+
+def test_tiny_fp32_full():
+    wl = synth.WORKLOADS["tiny"]
+    _say(f"tiny fp32 {wl}")
+    k, v = _mk(wl, seed=0)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, wl.window)
+    assert rc == 0 and p.variant == 3 and (p.span_len, p.retained_len) == (508, 254)
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, wl.window, TOL_F32)
+
+
+# ------------------------------------------------------------------------------------------
+# bf16, small shapes: several tiles, ragged tails, every pipeline tail length, both variants
+# ------------------------------------------------------------------------------------------
+
+SMALL = [
+    # (layers, batch, heads, d, window, sink, ratio)        what it exercises
+    (1, 1, 1, 128, 68, 4, 0.5),      # one pipeline stage (n/2 = 32)
+    (1, 1, 2, 128, 132, 4, 0.5),     # two stages
+    (1, 1, 1, 128, 196, 4, 0.5),     # three stages
+    (1, 1, 1, 128, 260, 4, 0.5),     # four stages
+    (1, 1, 1, 128, 330, 4, 0.5),     # six stages, ragged k (n/2 = 163)
+    (2, 1, 3, 128, 700, 4, 0.5),     # 11 stages, rows ragged within one tile
+    (1, 2, 2, 128, 1300, 4, 0.5),    # rows span two folded tiles (Lc/2 = 324 > 256)
+    (1, 1, 2, 128, 701, 4, 0.5),     # odd span -> plain (unfolded) variant
+    (1, 1, 1, 128, 1100, 3, 0.5),    # odd span, plain variant, rows span two 512-row tiles? (Lc = 548)
+    (1, 1, 3, 64, 516, 4, 0.5),      # head_dim 64: a column tile holds two heads
+    (1, 1, 1, 256, 516, 4, 0.5),     # head_dim 256: a head spans two column tiles
+    (1, 1, 5, 96, 260, 4, 0.5),      # head_dim 96: column tiles straddle heads, ragged last tile
+    (1, 1, 2, 128, 600, 0, 0.25),    # no sinks, ratio 0.25
+    (1, 1, 2, 128, 600, 8, 0.75),    # 8 sinks, ratio 0.75
+    (1, 1, 2, 128, 600, 2, 0.01),    # ratio 0.01 -> Lc = 5 (odd -> plain)
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[str(c) for c in SMALL])
+def test_bf16_small_full(cfg):
+    nl, b, h, d, W, S, ratio = cfg
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=nl, batch=b, n_heads=h, head_dim=d,
+                     window=W, n_sink=S, retain_ratio=ratio, total_tokens=W)
+    _say(f"bf16 small {cfg}")
+    k, v = _mk(wl, seed=3, capacity=W + 9)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, W)
+    assert rc == 0
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, W, TOL_BF16)
+
+
+def test_ratio_one_is_identity():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=300, retain_ratio=1.0)
+    k, v = _mk(wl, seed=1, capacity=320, cur_len=310)
+    k0, v0 = k.clone(), v.clone()
+    rc, p, _ = _run(k, v, wl, 310, tap=False)
+    assert rc == 0 and p.new_len == 310 and p.variant == 0
+    assert torch.equal(k, k0) and torch.equal(v, v0)
+
+
+def test_noop_below_window_leaves_cache_untouched():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=300)
+    k, v = _mk(wl, seed=1, capacity=300, cur_len=200)
+    k0 = k.clone()
+    rc, _, _ = _run(k, v, wl, 200, tap=False)
+    assert rc == 1 and torch.equal(k, k0)
+
+
+# ------------------------------------------------------------------------------------------
+# recent tail (cur_len > window), including a tail longer than the freed gap (chunked move)
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("extra", [1, 37, 148, 149, 400])
+def test_tail_is_moved_bit_for_bit(extra):
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, n_heads=2, window=300, n_sink=4)
+    cur = 300 + extra
+    _say(f"tail extra={extra}")
+    k, v = _mk(wl, seed=5, capacity=cur + 7, cur_len=cur)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, cur)
+    assert rc == 0 and p.new_len == 4 + 148 + extra
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, cur, TOL_BF16)
+
+
+# ------------------------------------------------------------------------------------------
+# layouts: token-major strides, pointer table, small workspace (several passes)
+# ------------------------------------------------------------------------------------------
+
+def test_token_major_strides():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, n_heads=3, window=260)
+    W = wl.window
+    # storage [L, B, token, H, d] viewed as [L, B, H, token, d]
+    ks = torch.empty(2, 1, W, 3, 128, dtype=torch.bfloat16, device=DEV)
+    vs = torch.empty_like(ks)
+    k, v = ks.permute(0, 1, 3, 2, 4), vs.permute(0, 1, 3, 2, 4)
+    synth.KVSource(wl, 2, DEV).fill(k, v, 0, W)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, W)
+    assert rc == 0
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, W, TOL_BF16)
+
+
+def test_pointer_table_and_multi_pass_match_single_pass():
+    import ctypes as C
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=3, n_heads=2, window=516)
+    W = wl.window
+    k, v = _mk(wl, seed=9)
+    ka, va = k.clone(), v.clone()       # single pass, base pointers
+    kb, vb = k.clone(), v.clone()       # minimum workspace -> one slab per pass
+    kc, vc = k.clone(), v.clone()       # per-layer pointer table
+    rc, p, _ = _run(ka, va, wl, W, tap=False)
+    assert rc == 0
+    rc, _, _ = _run(kb, vb, wl, W, tap=False, ws_bytes=p.workspace_min_bytes)
+    assert rc == 0
+    assert torch.equal(ka, kb) and torch.equal(va, vb)
+    L = binding.layout_for(kc)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes, L.pointer_table = ws.data_ptr(), p.workspace_bytes, 1
+    kt = (C.c_void_p * 3)(*[kc[l].data_ptr() for l in range(3)])
+    vt = (C.c_void_p * 3)(*[vc[l].data_ptr() for l in range(3)])
+    assert fk.compress(kt, vt, L, 2, 128, W, W, 4, 0.5) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(ka, kc) and torch.equal(va, vc)
+
+
+def test_errors_leave_memory_untouched():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=260)
+    k, v = _mk(wl, seed=4)
+    k0, v0 = k.clone(), v.clone()
+    L = binding.layout_for(k)
+    assert fk.compress(k, v, L, 2, 128, 260, 260, 4, 0.5, check=False) == binding.E_WORKSPACE
+    rc, _, _ = _run(k, v, wl, 260, tap=False, ws_bytes=64, check=False)
+    assert rc == binding.E_WORKSPACE
+    L.stride_token = 100
+    assert fk.compress(k, v, L, 2, 128, 260, 260, 4, 0.5, check=False) == binding.E_INVALID
+    torch.cuda.synchronize()
+    assert torch.equal(k, k0) and torch.equal(v, v0)
+
+
+def test_no_rescale_flag():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=260)
+    k, v = _mk(wl, seed=6)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, 260, flags=fk.FLAG_NO_RESCALE)
+    assert rc == 0
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, 260, TOL_BF16, rescale=False)
+
+
+# ------------------------------------------------------------------------------------------
+# iterative schedule (Sec. 3.4): teacher-forced parity at every trigger + free-running drift
+# ------------------------------------------------------------------------------------------
+
+def test_iterative_schedule_small():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_32k"], n_layers=2, n_heads=2, window=516, total_tokens=516 * 8)
+    W, S = wl.window, wl.n_sink
+    cache = CompressedKVCache(wl.n_layers, wl.batch, wl.n_heads, wl.head_dim, W, S, wl.retain_ratio, wl.dtype, DEV)
+    src = synth.KVSource(wl, 11, DEV)
+    lc = cache.plan.retained_len
+    free = cache.free_after_trigger
+    # free-running fp64 copy of one head-tensor (layer 1, head 1, V)
+    fr = None
+    fed = 0
+    worst = 0.0
+    while fed < wl.total_tokens:
+        take = min(wl.total_tokens - fed, cache.room() if cache.cur_len < W else free)
+        if cache.cur_len >= W:
+            before_k = cache.k.cpu().clone()
+            before_v = cache.v.cpu().clone()
+            assert cache.compress() == 0
+            torch.cuda.synchronize()
+            after_k = cache.k.cpu()
+            for (l, h) in ((0, 0), (1, 1)):
+                x = f64(before_k[l, 0, h, :W])
+                ref = orc.compress_head(x, W, W, S, wl.retain_ratio)
+                got = f64(after_k[l, 0, h, :S + lc])
+                rms = math.sqrt(float((ref[S:] ** 2).mean()))
+                excess = np.abs(got[S:] - ref[S:]) - 0.5 * bf16_ulp(ref[S:])
+                worst = max(worst, float(excess.max()) / rms)
+                assert np.array_equal(got[:S], ref[:S])
+            if fr is None:
+                fr = f64(before_v[1, 0, 1, :W])
+            fr = orc.compress_head(fr, W, W, S, wl.retain_ratio)
+        kn = torch.empty(wl.n_layers, 1, wl.n_heads, take, wl.head_dim, dtype=wl.dtype, device=DEV)
+        vn = torch.empty_like(kn)
+        src.fill(kn, vn, 0, take)
+        cache.append(kn, vn)
+        if fr is not None:
+            fr = np.concatenate([fr, f64(vn[1, 0, 1].cpu())])
+        fed += take
+    assert cache.triggers == orc.trigger_count(wl.total_tokens, W, S, wl.retain_ratio)
+    assert worst <= TOL_BF16
+    # free-running drift: the bf16 rounding of every earlier trigger is carried along, contracted by
+    # sqrt(Lc/n) < 1 per trigger, so it stays within a few half-ulps: allow 5e-2 of the RMS.
+    got = f64(cache.v[1, 0, 1, :cache.cur_len].cpu())
+    rms = math.sqrt(float((fr ** 2).mean()))
+    drift = float(np.max(np.abs(got - fr) - 0.5 * bf16_ulp(fr))) / rms
+    _say(f"  triggers {cache.triggers}, teacher-forced worst {worst:.3e}, free-running drift {drift:.3e}")
+    assert drift <= 5e-2
