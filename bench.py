@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the FreqKV compression hot path on one MI355X.
+
+A step = one compression trigger over the whole cache of the workload (all layers' K and V:
+fold/convert -> contraction -> in-place write) through the C ABI, inputs resident in HBM.
+Default workload: the LLaMA-3-8B GQA cache of the 128K iterative prefill (32 layers x 8 KV heads
+x head_dim 128, bf16, window 8192, 4 sinks, ratio 0.5): 512 head-tensors, span 8188 -> 4094.
+
+Prints ONE JSON line: whole-job KV-in throughput, the roofline of the dominant kernel (timed by
+HIP events on the launch stream inside the library) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(wl, k_cache, cores):
+    """The fp64 oracle, as it stands, on `cores` host threads over a bounded sample of head-tensors."""
+    import numpy as np
+    from oracle import freqkv_oracle as orc
+    n_sample = 4 * cores          # about 10-20 s of host work at span 8188
+    flat = k_cache.reshape(-1, k_cache.shape[3], k_cache.shape[4])
+    idx = [int(i) for i in np.linspace(0, flat.shape[0] - 1, n_sample)]
+    heads = [flat[i].to("cpu").float().double().numpy() for i in idx]
+    t0 = time.perf_counter()
+    orc.compress_heads(heads, wl.window, wl.window, wl.n_sink, wl.retain_ratio, threads=cores)
+    dt = time.perf_counter() - t0
+    n = wl.window - wl.n_sink
+    bytes_in = n_sample * n * wl.head_dim * 2
+    return {"value": bytes_in / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_sample} of the workload's head-tensors (K, full span {n} x {wl.head_dim}), "
+                      f"{dt:.1f} s on {cores} threads, one head-tensor per thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by head with no communication); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_00570_amd as fk
+    from paper_2505_00570_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+
+    # synthetic cache, resident in HBM
+    k, v = synth.empty_cache(wl, dev)
+    synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
+    L = binding.layout_for(k)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=dev)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, stream)
+
+    cpu = None
+    if not args.no_cpu_baseline and wl.dtype == torch.bfloat16:
+        cores = min(16, os.cpu_count() or 1)
+        cpu = cpu_baseline(wl, k, cores)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    fk.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = fk.profile_read()
+    fk.profile_enable(False)
+
+    ms_per_step = dt / args.steps * 1e3
+    n = p.span_len
+    elem = 2 if wl.dtype == torch.bfloat16 else 4
+    bytes_in = p.head_tensors * n * wl.head_dim * elem
+    value = bytes_in / (dt / args.steps) / 1e9
+
+    launches = max(int(prof.launches_contract), 1)
+    ms_contract = prof.ms_contract / launches
+    ms_prepare = prof.ms_prepare / max(int(prof.launches_prepare), 1)
+    flops_launch = p.flops_executed * args.steps / launches
+    achieved = flops_launch / (ms_contract * 1e-3) / 1e12
+    roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+            "ms_per_launch": ms_contract, "flops_per_launch": flops_launch}
+
+    out = {
+        "metric": "KV compression throughput (GB/s KV in)",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if elem == 2 else "f32",
+        "dtype_note": "bf16 cache; fp16 MFMA operands, fp32 accumulation" if elem == 2 else "fp32 cache, fp32 FMA",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.batch} x {wl.n_heads} KV heads x "
+                               f"head_dim {wl.head_dim}, window {wl.window}, {wl.n_sink} sinks, ratio "
+                               f"{wl.retain_ratio}; span {n} -> {p.retained_len}; {p.head_tensors} head-tensors "
+                               f"per trigger; one trigger per step",
+                   "variant": int(p.variant)},
+        "tflops_executed": p.flops_executed / (dt / args.steps) / 1e12,
+        "tflops_dense_equivalent": p.flops_dense / (dt / args.steps) / 1e12,
+        "gbs_algorithmic": p.bytes_algorithmic / (dt / args.steps) / 1e9,
+        "frac_hbm_roofline": p.bytes_algorithmic / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
+        "ms_prepare_kernel": ms_prepare, "ms_contract_kernel": ms_contract,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
