@@ -214,10 +214,8 @@ hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws
 //   - operand A (basis) is private to a wave: loaded global -> registers, already in
 //     fragment order ([kgroup][row][8]: lane L takes row L%32, k group L/32);
 //   - operand B (folded span) is shared by the waves: one contiguous stage of the workspace
-//     is copied global -> registers -> LDS (three slots) and read back as 16-byte fragments
+//     is copied global -> registers -> LDS (two slots) and read back as 16-byte fragments
 //     (lane L: column L%32, k group L/32), conflict-free.
-// Pipeline, step s: issue the global loads of span stage s+2 and basis stage s+1, read the LDS
-// fragments of stage s+1, run the 32 MFMAs of stage s, store span stage s+2 to LDS, barrier.
 // ------------------------------------------------------------------------------------------
 
 // Workgroup barrier that orders LDS traffic only (waits lgkmcnt, not vmcnt): __syncthreads() would
@@ -237,7 +235,7 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
 {
     constexpr int P = FOLD ? 2 : 1;
     constexpr int XSTAGE = P * 8192;                       // bytes per pipeline stage
-    constexpr int LDS_BYTES = FOLD ? 131072 : 3 * XSTAGE;  // 3 pipeline slots; folded epilogue exchanges 4 x 32 KiB
+    constexpr int LDS_BYTES = 65536;                      // pipeline: 2 slots of XSTAGE; epilogue: 4 x 16 KiB
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -286,10 +284,19 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
     const size_t a_kstep = (size_t)2 * g.Grows;     // one 16-k substep
     const size_t a_stage = (size_t)4 * g.Grows;
 
+    // Software pipeline over the K stages (32 contraction rows each).  Global loads run two stages
+    // ahead of the matrix cores so that an L2 miss (the span and the basis stream from HBM / the
+    // Infinity Cache) has two stages of MFMA work to arrive:
+    //   step s:  issue  basis(s+2) -> aset[(s+2)%3]         (global -> registers)
+    //            issue  span(s+3)  -> xr[(s+1)%2]           (global -> registers)
+    //            read   span(s+1)  LDS slot (s+1)%2 -> xf[(s+1)%2]
+    //            MFMA   stage s    (aset[s%3], xf[s%2])
+    //            write  span(s+2)  xr[s%2] -> LDS slot s%2,  barrier
+    // Register buffers rotate with periods 3 and 2, so the loop body is six steps long.
     constexpr int XR = XSTAGE / 4096;       // 16-byte pieces per thread per stage
-    half8 aset[2][2][4];                    // basis fragments [buffer][16-k substep][row block]
+    half8 aset[3][2][4];                    // basis fragments [buffer][16-k substep][row block]
     half8 xf[2][2][4];                      // span fragments  [buffer][16-k substep][column block]
-    half8 xr[XR];                           // span stage in flight global -> LDS
+    half8 xr[2][XR];                        // span stages in flight global -> LDS
     const int tid16 = threadIdx.x * 16;
 
     auto load_a = [&](int st, auto buf) {
@@ -298,15 +305,17 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
             static_for<4>([&](auto mb) { aset[buf.value][u.value][mb.value] = pa[u.value * a_kstep + mb.value * 32]; });
         });
     };
-    auto load_x = [&](int st) {
+    auto load_x = [&](int st, auto buf) {
         const char* src = xsrc + (size_t)st * XSTAGE + tid16;
-        static_for<XR>([&](auto r) { xr[r.value] = *(const half8*)(src + r.value * 4096); });
+        static_for<XR>([&](auto r) { xr[buf.value][r.value] = *(const half8*)(src + r.value * 4096); });
     };
-    auto write_x = [&](int slot_off) {
-        static_for<XR>([&](auto r) { *(half8*)(smem + slot_off + r.value * 4096 + tid16) = xr[r.value]; });
+    auto write_x = [&](auto slot, auto buf) {
+        static_for<XR>([&](auto r) {
+            *(half8*)(smem + slot.value * XSTAGE + r.value * 4096 + tid16) = xr[buf.value][r.value];
+        });
     };
-    auto read_xf = [&](int slot_off, auto buf) {
-        const char* xs = smem + slot_off + par * 8192;
+    auto read_xf = [&](auto slot, auto buf) {
+        const char* xs = smem + slot.value * XSTAGE + par * 8192;
         static_for<2>([&](auto u) {
             static_for<4>([&](auto nb) {
                 xf[buf.value][u.value][nb.value] =
@@ -314,150 +323,143 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
             });
         });
     };
-    auto mfma_stage = [&](auto buf) {
-        static_for<2>([&](auto u) {
-            static_for<4>([&](auto mb) {
-                static_for<4>([&](auto nb) {
-                    acc[mb.value][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        aset[buf.value][u.value][mb.value], xf[buf.value][u.value][nb.value],
-                        acc[mb.value][nb.value], 0, 0, 0);
-                });
+    // One step at phase PH = s mod 6.  `rem` = stages after s; STEADY (compile time) means rem >= 3.
+    // The 32 MFMAs run as 8 groups of 4 (one basis fragment against the 4 column blocks); the
+    // step's 12 global loads, 8 LDS fragment reads and XR LDS stores are dealt out between the
+    // groups, so the vector-memory and LDS queues drain while the matrix cores work instead of
+    // blocking the wave in one burst at the top of the step.
+    auto step = [&](int st, auto ph, auto steady, int rem) {
+        constexpr int PH = decltype(ph)::value;
+        constexpr bool STEADY = decltype(steady)::value != 0;
+        constexpr int A0 = PH % 3, A2 = (PH + 2) % 3, X0 = PH % 2, X1 = (PH + 1) % 2;
+        const bool do_x = STEADY || rem >= 3, do_a = STEADY || rem >= 2, do_r = STEADY || rem >= 1;
+        const bool do_w = STEADY || rem >= 2;
+        const char* xsrc_s = xsrc + (size_t)(st + 3) * XSTAGE + tid16;
+        const half8* pa = Gv + a_lane + (size_t)(st + 2) * a_stage;
+        const char* xs = smem + X1 * XSTAGE + par * 8192;
+        static_for<8>([&](auto gi) {
+            constexpr int G = decltype(gi)::value;          // group = (substep u, row block mb)
+            constexpr int U = G / 4, MB = G % 4;
+            // global loads: basis fragment G of stage s+2, and one span piece while there are any
+            if (do_a) aset[A2][U][MB] = pa[U * a_kstep + MB * 32];
+            if constexpr (G < XR) {
+                if (do_x) xr[X1][G] = *(const half8*)(xsrc_s + G * 4096);
+            }
+            // LDS: fragment G of stage s+1
+            if (do_r) xf[X1][U][MB] = *(const half8*)(xs + (((U * 2 + lhi) * kColTile) + MB * 32 + l32) * 16);
+            // LDS: store the span pieces of stage s+2 late in the step (they were loaded one step ago)
+            if constexpr (G >= 8 - XR) {
+                constexpr int R = G - (8 - XR);
+                if (do_w) *(half8*)(smem + X0 * XSTAGE + R * 4096 + tid16) = xr[X0][R];
+            }
+            static_for<4>([&](auto nb) {
+                acc[MB][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    aset[A0][U][MB], xf[X0][U][nb.value], acc[MB][nb.value], 0, 0, 0);
             });
+            __builtin_amdgcn_sched_barrier(0);
         });
+        if (do_r) lds_barrier();
     };
 
-    // LDS slot byte offsets of stages s, s+1, s+2 (three slots, rotating)
-    int off0 = 0, off1 = XSTAGE, off2 = 2 * XSTAGE;
-    auto rotate = [&]() { int t = off0; off0 = off1; off1 = off2; off2 = t; };
-
-    // MODE 2: stages s+1 and s+2 exist (steady state); 1: only s+1; 0: last stage.
-    auto step = [&](int st, auto buf, auto mode) {
-        constexpr int B = decltype(buf)::value;
-        constexpr int MODE = decltype(mode)::value;
-        if constexpr (MODE >= 2) load_x(st + 2);
-        if constexpr (MODE >= 1) {
-            load_a(st + 1, IC<1 - B>{});
-            read_xf(off1, IC<1 - B>{});
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_stage(IC<B>{});
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (MODE >= 2) write_x(off2);
-        if constexpr (MODE >= 1) lds_barrier();
-        rotate();
-    };
-
-    // prologue: stage 0 (and 1) into LDS, basis stage 0 into registers, fragments of stage 0 read
+    // prologue: span stages 0,1 -> LDS, stage 2 in flight; basis stages 0,1 in flight
     {
-        load_x(0);
+        load_x(0, IC<0>{});
         load_a(0, IC<0>{});
-        write_x(off0);
         if (nks > 1) {
-            load_x(1);
-            write_x(off1);
+            load_x(1, IC<1>{});
+            load_a(1, IC<1>{});
         }
+        write_x(IC<0>{}, IC<0>{});
+        if (nks > 1) write_x(IC<1>{}, IC<1>{});
+        if (nks > 2) load_x(2, IC<0>{});
         lds_barrier();
-        read_xf(off0, IC<0>{});
+        read_xf(IC<0>{}, IC<0>{});
     }
 
-    if (nks >= 2) {
-        const int nfull = nks - 2;          // steps with two further stages ahead
-        int st = 0;
-        for (; st + 1 < nfull; st += 2) {
-            step(st, IC<0>{}, IC<2>{});
-            step(st + 1, IC<1>{}, IC<2>{});
-        }
-        if (nfull & 1) {
-            step(st, IC<0>{}, IC<2>{});
-            step(st + 1, IC<1>{}, IC<1>{});
-            step(st + 2, IC<0>{}, IC<0>{});
-        } else {
-            step(st, IC<0>{}, IC<1>{});
-            step(st + 1, IC<1>{}, IC<0>{});
-        }
-    } else {
-        step(0, IC<0>{}, IC<0>{});
+    int st = 0;
+    for (; st + 9 <= nks; st += 6) {
+        step(st + 0, IC<0>{}, IC<1>{}, 3);
+        step(st + 1, IC<1>{}, IC<1>{}, 3);
+        step(st + 2, IC<2>{}, IC<1>{}, 3);
+        step(st + 3, IC<3>{}, IC<1>{}, 3);
+        step(st + 4, IC<4>{}, IC<1>{}, 3);
+        step(st + 5, IC<5>{}, IC<1>{}, 3);
     }
+    // tail: at most eight steps, same rotation, loads guarded at run time (st is a multiple of 6 here)
+    static_for<8>([&](auto i) {
+        const int s2 = st + i.value;
+        if (s2 < nks) step(s2, IC<i.value % 6>{}, IC<0>{}, nks - 1 - s2);
+    });
     __syncthreads();      // every wave is done with the LDS slots before the epilogue reuses them
 
     // ---- epilogue ------------------------------------------------------------------------
     // Accumulator layout of a 32x32 block: register r of lane L is row 8*(r/4) + 4*(L/32) + r%4,
-    // column L%32.
-    char* colptr[4];
-    int   colht[4];
-    bool  colok[4];
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-        int vcol = ct * kColTile + nb * 32 + l32;
-        colok[nb] = vcol < g.ncols;
-        colht[nb] = 0;
-        colptr[nb] = colok[nb] ? column_base(tab, g, vcol, 2, &colht[nb]) : nullptr;
-    }
+    // column L%32.  Each wave parks one 32-row block at a time in LDS as fp32 [32][128]; the
+    // workgroup then reads it back row-major, 8 channels per lane, so that every cache row is
+    // written with 16-byte stores (a full 256-byte row per 16 lanes).  In the folded variant this
+    // pass also pairs the even part E (parity-0 wave) with the odd part O (parity-1 wave):
+    // row m gets E+O and row Lc-1-m gets E-O.
+    float* T = (float*)smem;                       // [4 waves][32 rows][128 cols]
     const long long rowb = g.stride_token * 2;
-
-    auto store_row = [&](int nb, int row, float val) {
-        // row = output row index m in [0, Lc)
-        *(uint16_t*)(colptr[nb] + (long long)(g.S + row) * rowb) = f32_to_bf16(val);
-        if (tap) {
-            int vcol = ct * kColTile + nb * 32 + l32;
-            int c = vcol - colht[nb] * g.d;
-            long long ht_global = g.tap_slab0 * g.hts_per_slab + colht[nb];
-            tap[(ht_global * g.Lc + row) * g.d + c] = val;
-        }
-    };
-
-    if constexpr (FOLD) {
-        float* ex = (float*)smem;
-        // parity-0 waves finish row blocks 0,1 and hand blocks 2,3 to their partner; parity-1 waves
-        // the other way round.  Swap so that blocks 0,1 are always the ones kept.
-        if (par != 0) {
-            static_for<2>([&](auto mb2) {
-                static_for<4>([&](auto nb) {
-                    f32x16 t = acc[mb2.value][nb.value];
-                    acc[mb2.value][nb.value] = acc[2 + mb2.value][nb.value];
-                    acc[2 + mb2.value][nb.value] = t;
-                });
-            });
-        }
-        float* mine = ex + wave * 8192;
-        static_for<2>([&](auto mb2) {
-            static_for<4>([&](auto nb) {
-                static_for<16>([&](auto r) {
-                    mine[((mb2.value * 4 + nb.value) * 16 + r.value) * 64 + lane] = acc[2 + mb2.value][nb.value][r.value];
-                });
+    constexpr int ITEMS = FOLD ? 2 * 32 * 16 : 4 * 32 * 16;     // (wave pair | wave, row, 8-column group)
+    static_for<4>([&](auto mbc) {
+        constexpr int MB = decltype(mbc)::value;
+        static_for<4>([&](auto nb) {
+            static_for<16>([&](auto r) {
+                const int row = (r.value >> 2) * 8 + lhi * 4 + (r.value & 3);
+                T[(wave * 32 + row) * 128 + nb.value * 32 + l32] = acc[MB][nb.value][r.value];
             });
         });
         __syncthreads();
-        const float* theirs = ex + (wave ^ 2) * 8192;
-        const int rbase = mt * kRowsFold + rhalf * 128 + (par == 0 ? 0 : 64);
-        const float osign = (par == 0) ? 1.f : -1.f;
-        static_for<2>([&](auto mb2) {
-            static_for<4>([&](auto nb) {
-                static_for<16>([&](auto r) {
-                    float other = theirs[((mb2.value * 4 + nb.value) * 16 + r.value) * 64 + lane];
-                    float own = acc[mb2.value][nb.value][r.value];
-                    // parity 0: own = E, other = O; parity 1: own = O, other = E
-                    float top = own + other;                    // E + O
-                    float bot = (own - other) * osign;          // E - O
-                    int rh = rbase + mb2.value * 32 + (r.value >> 2) * 8 + lhi * 4 + (r.value & 3);
-                    if (colok[nb.value] && rh < g.Mh) {
-                        store_row(nb.value, rh, top);
-                        store_row(nb.value, g.Lc - 1 - rh, bot);
-                    }
-                });
-            });
-        });
-    } else {
-        const int rbase = mt * kRowsPlain + wave * 128;
-        static_for<4>([&](auto mb) {
-            static_for<4>([&](auto nb) {
-                static_for<16>([&](auto r) {
-                    int row = rbase + mb.value * 32 + (r.value >> 2) * 8 + lhi * 4 + (r.value & 3);
-                    if (colok[nb.value] && row < g.Mh) store_row(nb.value, row, acc[mb.value][nb.value][r.value]);
-                });
-            });
-        });
-    }
+        for (int item = threadIdx.x; item < ITEMS; item += 256) {
+            const int cg = item & 15, row = (item >> 4) & 31, w = item >> 9;
+            const int vcol = ct * kColTile + cg * 8;
+            if (vcol >= g.ncols) continue;
+            int ht;
+            char* base = column_base(tab, g, vcol, 2, &ht);
+            const int c = vcol - ht * g.d;
+            float* tp = tap ? tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c : nullptr;
+            float va[8], vb[8];
+            int row_a, row_b = -1;
+            if constexpr (FOLD) {
+                // w = row half; E from wave (0, w), O from wave (1, w)
+                const float* e = T + ((0 * 2 + w) * 32 + row) * 128 + cg * 8;
+                const float* o = T + ((1 * 2 + w) * 32 + row) * 128 + cg * 8;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { va[i] = e[i] + o[i]; vb[i] = e[i] - o[i]; }
+                const int rh = mt * kRowsFold + w * 128 + MB * 32 + row;
+                if (rh >= g.Mh) continue;
+                row_a = rh;
+                row_b = g.Lc - 1 - rh;
+            } else {
+                const float* e = T + (w * 32 + row) * 128 + cg * 8;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) va[i] = e[i];
+                row_a = mt * kRowsPlain + w * 128 + MB * 32 + row;
+                if (row_a >= g.Mh) continue;
+            }
+            u32x4 pk;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                pk[i] = (uint32_t)f32_to_bf16(va[2 * i]) | ((uint32_t)f32_to_bf16(va[2 * i + 1]) << 16);
+            *(u32x4*)(base + (long long)(g.S + row_a) * rowb) = pk;
+            if (tp) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) tp[(long long)row_a * g.d + i] = va[i];
+            }
+            if (FOLD) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    pk[i] = (uint32_t)f32_to_bf16(vb[2 * i]) | ((uint32_t)f32_to_bf16(vb[2 * i + 1]) << 16);
+                *(u32x4*)(base + (long long)(g.S + row_b) * rowb) = pk;
+                if (tp) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) tp[(long long)row_b * g.d + i] = vb[i];
+                }
+            }
+        }
+        __syncthreads();
+    });
 }
 
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
