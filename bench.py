@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA
 HBM_PEAK_GBS = 8000.0
+# HBM bytes (read + write) of one contraction launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
+# what the same counters read for the library's plain copy kernel (profiles/contract_llama3_8b_128k_pmc.txt).
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2 * 2.622e6 + 5.24e5) * 1024}
 
 
 def cpu_baseline(wl, k_cache, cores):
@@ -97,6 +100,12 @@ def main():
     prof = fk.profile_read()
     fk.profile_enable(False)
 
+    # what this device sustains: plain copy (read+write) and a register-only fp16 MFMA loop on random operands
+    calib_n = min(p.workspace_bytes // 2, 1 << 30) // 16 * 16
+    wsv = ws.view(torch.uint8)
+    copy_gbs = fk.calibrate_copy(wsv[calib_n:].data_ptr(), wsv.data_ptr(), calib_n, 10, stream) if calib_n >= 1 << 20 else None
+    mfma_tflops = fk.calibrate_mfma(20000, stream)
+
     ms_per_step = dt / args.steps * 1e3
     n = p.span_len
     elem = 2 if wl.dtype == torch.bfloat16 else 4
@@ -109,8 +118,10 @@ def main():
     flops_launch = p.flops_executed * args.steps / launches
     achieved = flops_launch / (ms_contract * 1e-3) / 1e12
     roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-            "ms_per_launch": ms_contract, "flops_per_launch": flops_launch}
+            "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+            "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+            "ms_per_launch": ms_contract, "flops_per_launch": flops_launch,
+            "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops}
 
     out = {
         "metric": "KV compression throughput (GB/s KV in)",
@@ -129,6 +140,7 @@ def main():
         "gbs_algorithmic": p.bytes_algorithmic / (dt / args.steps) / 1e9,
         "frac_hbm_roofline": p.bytes_algorithmic / (dt / args.steps) / 1e9 / HBM_PEAK_GBS,
         "ms_prepare_kernel": ms_prepare, "ms_contract_kernel": ms_contract,
+        "measured_copy_gbs": copy_gbs,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

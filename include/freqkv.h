@@ -162,6 +162,19 @@ int freqkv_version(void);
 freqkv_status_t freqkv_profile_enable(int on);
 freqkv_status_t freqkv_profile_read(freqkv_profile_t* out);
 
+/*
+ * Calibration of the device the library runs on, for quoting rooflines against measured as well as
+ * nominal peaks.  Both calls synchronise on their own events (they are measurement tools, not
+ * part of the compression path).
+ *   freqkv_calibrate_copy: times `repeats` plain 16-byte-per-lane copies of `bytes` (a multiple of
+ *       16; dst/src device pointers, 16-byte aligned, not overlapping) and returns read+write GB/s.
+ *   freqkv_calibrate_mfma: times a register-only loop of v_mfma_f32_32x32x16_f16 on random operands
+ *       (one workgroup per CU, `iters` x 16 instructions per wave) and returns TFLOP/s.
+ */
+freqkv_status_t freqkv_calibrate_copy(void* dst, const void* src, size_t bytes, int repeats,
+                                      void* stream, double* gbs_out /* host */);
+freqkv_status_t freqkv_calibrate_mfma(int iters, void* stream, double* tflops_out /* host */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -89,6 +89,11 @@ def load() -> C.CDLL:
         lib.freqkv_profile_enable.restype = C.c_int
         lib.freqkv_profile_read.argtypes = [C.POINTER(Profile)]
         lib.freqkv_profile_read.restype = C.c_int
+        lib.freqkv_calibrate_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p,
+                                              C.POINTER(C.c_double)]
+        lib.freqkv_calibrate_copy.restype = C.c_int
+        lib.freqkv_calibrate_mfma.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double)]
+        lib.freqkv_calibrate_mfma.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -147,6 +152,21 @@ def profile_read() -> Profile:
     out = Profile()
     _check(load().freqkv_profile_read(C.byref(out)))
     return out
+
+
+def calibrate_copy(dst, src, nbytes: int, repeats: int = 10, stream=None) -> float:
+    """freqkv_calibrate_copy: measured read+write GB/s of a plain device copy."""
+    out = C.c_double()
+    _check(load().freqkv_calibrate_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, repeats, _stream_ptr(stream),
+                                        C.byref(out)))
+    return out.value
+
+
+def calibrate_mfma(iters: int = 20000, stream=None) -> float:
+    """freqkv_calibrate_mfma: measured TFLOP/s of a register-only fp16 MFMA loop on random operands."""
+    out = C.c_double()
+    _check(load().freqkv_calibrate_mfma(iters, _stream_ptr(stream), C.byref(out)))
+    return out.value
 
 
 # ---------------------------------------------------------------- marshalling helpers

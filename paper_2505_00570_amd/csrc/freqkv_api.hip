@@ -378,6 +378,56 @@ void freqkv_shutdown(void)
     (void)hipGetLastError();
 }
 
+freqkv_status_t freqkv_calibrate_copy(void* dst, const void* src, size_t bytes, int repeats, void* stream,
+                                      double* gbs_out)
+{
+    if (!dst || !src || !gbs_out || bytes < 16 || (bytes & 15) || repeats < 1) return FREQKV_E_INVALID;
+    if (((uintptr_t)dst | (uintptr_t)src) & 15) return FREQKV_E_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t a, b;
+    HIP_TRY(hipEventCreate(&a));
+    HIP_TRY(hipEventCreate(&b));
+    HIP_TRY(launch_calib_copy(dst, src, bytes, st));             // warm-up
+    HIP_TRY(hipEventRecord(a, st));
+    for (int i = 0; i < repeats; ++i) HIP_TRY(launch_calib_copy(dst, src, bytes, st));
+    HIP_TRY(hipEventRecord(b, st));
+    HIP_TRY(hipEventSynchronize(b));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, a, b));
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    *gbs_out = 2.0 * (double)bytes * repeats / (ms * 1e-3) / 1e9;     // read + write
+    return FREQKV_OK;
+}
+
+freqkv_status_t freqkv_calibrate_mfma(int iters, void* stream, double* tflops_out)
+{
+    if (!tflops_out || iters < 1) return FREQKV_E_INVALID;
+    hipStream_t st = (hipStream_t)stream;
+    int dev = 0, cus = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    float* out = nullptr;
+    HIP_TRY(hipMalloc(&out, (size_t)cus * 256 * sizeof(float)));
+    hipEvent_t a, b;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    if (e == hipSuccess) e = launch_calib_mfma(out, cus, iters / 10 + 1, st);
+    if (e == hipSuccess) e = hipEventRecord(a, st);
+    if (e == hipSuccess) e = launch_calib_mfma(out, cus, iters, st);
+    if (e == hipSuccess) e = hipEventRecord(b, st);
+    if (e == hipSuccess) e = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    (void)hipFree(out);
+    if (e != hipSuccess) { set_error("calibrate_mfma", e); return FREQKV_E_HIP; }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    // one workgroup per CU, 4 waves, 16 MFMAs of 32*32*16 MACs per iteration
+    *tflops_out = (double)cus * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e-3) / 1e12;
+    return FREQKV_OK;
+}
+
 freqkv_status_t freqkv_profile_enable(int on)
 {
     std::lock_guard<std::mutex> lock(g_mu);

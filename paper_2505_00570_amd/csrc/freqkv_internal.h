@@ -64,4 +64,8 @@ hipError_t launch_contract_f32(const SlabTable& tab, const Geom& g, const float*
 hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes, int src_row,
                             int dst_row, int rows, hipStream_t st);
 
+// ---- calibration: plain 16-byte copy; register-only MFMA loop (16 x 32x32x16 f16 per iteration per wave)
+hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_calib_mfma(float* out, int blocks, int iters, hipStream_t st);
+
 }  // namespace freqkv

@@ -599,4 +599,54 @@ hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes,
     return hipSuccess;
 }
 
+// ------------------------------------------------------------------------------------------
+// calibration kernels: what this device sustains for a plain copy and for a register-only MFMA
+// loop on random (power-realistic) operands; rooflines are quoted against both nominal and these
+// ------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void k_calib_copy(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16)
+{
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_calib_mfma(float* __restrict__ out, int iters)
+{
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    half8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        h = h * 1664525u + 1013904223u; a[i] = (_Float16)((float)((int)((h >> 16) & 1023) - 512) / 512.f);
+        h = h * 1664525u + 1013904223u; b[i] = (_Float16)((float)((int)((h >> 16) & 1023) - 512) / 512.f);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(k_calib_copy, dim3(256 * 16), dim3(256), 0, st, (u32x4*)dst, (const u32x4*)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_calib_mfma(float* out, int blocks, int iters, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_calib_mfma, dim3(blocks), dim3(256), 0, st, out, iters);
+    return hipGetLastError();
+}
+
 }  // namespace freqkv
