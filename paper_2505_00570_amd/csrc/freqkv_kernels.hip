@@ -227,15 +227,19 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool FOLD>
-__global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
+template <bool FOLD, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom g,
                                                          const _Float16* __restrict__ G,
                                                          const _Float16* __restrict__ ws,
                                                          float* __restrict__ tap)
 {
     constexpr int P = FOLD ? 2 : 1;
     constexpr int XSTAGE = P * 8192;                       // bytes per pipeline stage
-    constexpr int LDS_BYTES = 65536;                      // pipeline: 2 slots of XSTAGE; epilogue: 4 x 16 KiB
+    constexpr int NT = NW * 64;                            // threads
+    constexpr int WPP = FOLD ? NW / 2 : NW;                // waves per parity
+    constexpr int WROWS = (FOLD ? kRowsFold : kRowsPlain) / WPP;   // rows per wave
+    constexpr int MBN = WROWS / 32;                        // 32-row accumulator blocks per wave
+    constexpr int LDS_BYTES = NW * 16384;                  // pipeline: 2 slots of XSTAGE; epilogue: NW x 16 KiB
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -262,15 +266,15 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
         }
     }
 
-    const int par   = FOLD ? (wave >> 1) : 0;
-    const int rhalf = FOLD ? (wave & 1) : wave;
+    const int par  = FOLD ? (wave / WPP) : 0;
+    const int rsub = FOLD ? (wave % WPP) : wave;
     // first basis row of this wave in G's row order
-    const int grow0 = FOLD ? (par * g.Mpad + mt * kRowsFold + rhalf * 128)
-                           : (mt * kRowsPlain + wave * 128);
+    const int grow0 = FOLD ? (par * g.Mpad + mt * kRowsFold + rsub * WROWS)
+                           : (mt * kRowsPlain + wave * WROWS);
 
-    f32x16 acc[4][4];
+    f32x16 acc[MBN][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MBN; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -293,8 +297,9 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
     //            MFMA   stage s    (aset[s%3], xf[s%2])
     //            write  span(s+2)  xr[s%2] -> LDS slot s%2,  barrier
     // Register buffers rotate with periods 3 and 2, so the loop body is six steps long.
-    constexpr int XR = XSTAGE / 4096;       // 16-byte pieces per thread per stage
-    half8 aset[3][2][4];                    // basis fragments [buffer][16-k substep][row block]
+    constexpr int XR = XSTAGE / (NT * 16);  // 16-byte pieces per thread per stage
+    constexpr int XPIECE = NT * 16;         // bytes the workgroup moves per piece
+    half8 aset[3][2][MBN];                  // basis fragments [buffer][16-k substep][row block]
     half8 xf[2][2][4];                      // span fragments  [buffer][16-k substep][column block]
     half8 xr[2][XR];                        // span stages in flight global -> LDS
     const int tid16 = threadIdx.x * 16;
@@ -302,16 +307,16 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
     auto load_a = [&](int st, auto buf) {
         const half8* pa = Gv + a_lane + (size_t)st * a_stage;
         static_for<2>([&](auto u) {
-            static_for<4>([&](auto mb) { aset[buf.value][u.value][mb.value] = pa[u.value * a_kstep + mb.value * 32]; });
+            static_for<MBN>([&](auto mb) { aset[buf.value][u.value][mb.value] = pa[u.value * a_kstep + mb.value * 32]; });
         });
     };
     auto load_x = [&](int st, auto buf) {
         const char* src = xsrc + (size_t)st * XSTAGE + tid16;
-        static_for<XR>([&](auto r) { xr[buf.value][r.value] = *(const half8*)(src + r.value * 4096); });
+        static_for<XR>([&](auto r) { xr[buf.value][r.value] = *(const half8*)(src + r.value * XPIECE); });
     };
     auto write_x = [&](auto slot, auto buf) {
         static_for<XR>([&](auto r) {
-            *(half8*)(smem + slot.value * XSTAGE + r.value * 4096 + tid16) = xr[buf.value][r.value];
+            *(half8*)(smem + slot.value * XSTAGE + r.value * XPIECE + tid16) = xr[buf.value][r.value];
         });
     };
     auto read_xf = [&](auto slot, auto buf) {
@@ -337,20 +342,25 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
         const char* xsrc_s = xsrc + (size_t)(st + 3) * XSTAGE + tid16;
         const half8* pa = Gv + a_lane + (size_t)(st + 2) * a_stage;
         const char* xs = smem + X1 * XSTAGE + par * 8192;
-        static_for<8>([&](auto gi) {
-            constexpr int G = decltype(gi)::value;          // group = (substep u, row block mb)
-            constexpr int U = G / 4, MB = G % 4;
+        constexpr int NG = 2 * MBN;             // MFMA groups per step: (substep u, row block mb)
+        constexpr int RPG = 8 / NG;             // LDS fragment reads per group
+        static_for<NG>([&](auto gi) {
+            constexpr int G = decltype(gi)::value;
+            constexpr int U = G / MBN, MB = G % MBN;
             // global loads: basis fragment G of stage s+2, and one span piece while there are any
             if (do_a) aset[A2][U][MB] = pa[U * a_kstep + MB * 32];
             if constexpr (G < XR) {
-                if (do_x) xr[X1][G] = *(const half8*)(xsrc_s + G * 4096);
+                if (do_x) xr[X1][G] = *(const half8*)(xsrc_s + G * XPIECE);
             }
-            // LDS: fragment G of stage s+1
-            if (do_r) xf[X1][U][MB] = *(const half8*)(xs + (((U * 2 + lhi) * kColTile) + MB * 32 + l32) * 16);
+            // LDS: fragments of stage s+1
+            static_for<RPG>([&](auto ri) {
+                constexpr int F = G * RPG + decltype(ri)::value, FU = F / 4, FN = F % 4;
+                if (do_r) xf[X1][FU][FN] = *(const half8*)(xs + (((FU * 2 + lhi) * kColTile) + FN * 32 + l32) * 16);
+            });
             // LDS: store the span pieces of stage s+2 late in the step (they were loaded one step ago)
-            if constexpr (G >= 8 - XR) {
-                constexpr int R = G - (8 - XR);
-                if (do_w) *(half8*)(smem + X0 * XSTAGE + R * 4096 + tid16) = xr[X0][R];
+            if constexpr (G >= NG - XR) {
+                constexpr int R = G - (NG - XR);
+                if (do_w) *(half8*)(smem + X0 * XSTAGE + R * XPIECE + tid16) = xr[X0][R];
             }
             static_for<4>([&](auto nb) {
                 acc[MB][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
@@ -399,10 +409,10 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
     // written with 16-byte stores (a full 256-byte row per 16 lanes).  In the folded variant this
     // pass also pairs the even part E (parity-0 wave) with the odd part O (parity-1 wave):
     // row m gets E+O and row Lc-1-m gets E-O.
-    float* T = (float*)smem;                       // [4 waves][32 rows][128 cols]
+    float* T = (float*)smem;                       // [NW waves][32 rows][128 cols]
     const long long rowb = g.stride_token * 2;
-    constexpr int ITEMS = FOLD ? 2 * 32 * 16 : 4 * 32 * 16;     // (wave pair | wave, row, 8-column group)
-    static_for<4>([&](auto mbc) {
+    constexpr int ITEMS = WPP * 32 * 16;           // (wave pair | wave, row, 8-column group)
+    static_for<MBN>([&](auto mbc) {
         constexpr int MB = decltype(mbc)::value;
         static_for<4>([&](auto nb) {
             static_for<16>([&](auto r) {
@@ -411,7 +421,7 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
             });
         });
         __syncthreads();
-        for (int item = threadIdx.x; item < ITEMS; item += 256) {
+        for (int item = threadIdx.x; item < ITEMS; item += NT) {
             const int cg = item & 15, row = (item >> 4) & 31, w = item >> 9;
             const int vcol = ct * kColTile + cg * 8;
             if (vcol >= g.ncols) continue;
@@ -422,12 +432,12 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
             float va[8], vb[8];
             int row_a, row_b = -1;
             if constexpr (FOLD) {
-                // w = row half; E from wave (0, w), O from wave (1, w)
-                const float* e = T + ((0 * 2 + w) * 32 + row) * 128 + cg * 8;
-                const float* o = T + ((1 * 2 + w) * 32 + row) * 128 + cg * 8;
+                // w = row sub-tile; E from wave (parity 0, w), O from wave (parity 1, w)
+                const float* e = T + ((0 * WPP + w) * 32 + row) * 128 + cg * 8;
+                const float* o = T + ((1 * WPP + w) * 32 + row) * 128 + cg * 8;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) { va[i] = e[i] + o[i]; vb[i] = e[i] - o[i]; }
-                const int rh = mt * kRowsFold + w * 128 + MB * 32 + row;
+                const int rh = mt * kRowsFold + w * WROWS + MB * 32 + row;
                 if (rh >= g.Mh) continue;
                 row_a = rh;
                 row_b = g.Lc - 1 - rh;
@@ -435,7 +445,7 @@ __global__ __launch_bounds__(256, 1) void k_contract_f16(SlabTable tab, Geom g,
                 const float* e = T + (w * 32 + row) * 128 + cg * 8;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) va[i] = e[i];
-                row_a = mt * kRowsPlain + w * 128 + MB * 32 + row;
+                row_a = mt * kRowsPlain + w * WROWS + MB * 32 + row;
                 if (row_a >= g.Mh) continue;
             }
             u32x4 pk;
@@ -466,8 +476,11 @@ hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float
                                const _Float16* ws, float* tap, hipStream_t st)
 {
     dim3 grid((unsigned)g.ncoltiles * (unsigned)g.nmtiles);
-    if (g.fold) hipLaunchKernelGGL(k_contract_f16<true>,  grid, dim3(256), 0, st, tab, g, G, ws, tap);
-    else        hipLaunchKernelGGL(k_contract_f16<false>, grid, dim3(256), 0, st, tab, g, G, ws, tap);
+    // Four waves (one per SIMD, 128x128 accumulators each).  Eight waves of 64x128 are correct too but
+    // measured 2.99 ms against 2.16 ms on the 8188 -> 4094 trigger: twice the LDS fragment traffic.
+    constexpr int NW = 4;
+    if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+    else        hipLaunchKernelGGL((k_contract_f16<false, NW>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
     return hipGetLastError();
 }
 
