@@ -21,6 +21,8 @@ namespace freqkv {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Register
 // arrays indexed through it can never fall back to dynamic indexing (and hence to scratch memory).
@@ -55,13 +57,12 @@ __device__ __forceinline__ char* column_base(const SlabTable& tab, const Geom& g
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-// round-to-nearest-even float -> bfloat16 bits
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+// two floats -> packed bfloat16 pair, round-to-nearest-even (gfx950's v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -412,6 +413,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     float* T = (float*)smem;                       // [NW waves][32 rows][128 cols]
     const long long rowb = g.stride_token * 2;
     constexpr int ITEMS = WPP * 32 * 16;           // (wave pair | wave, row, 8-column group)
+    static_assert(NT % 16 == 0 && ITEMS % NT == 0, "a thread keeps one 8-column group for all its items");
+    // the thread's 8-column group is the same for all of its items: resolve its head-tensor once
+    const int cg = threadIdx.x & 15;
+    const int vcol = ct * kColTile + cg * 8;
+    const bool col_ok = vcol < g.ncols;
+    char* base = nullptr;
+    float* tp = nullptr;
+    if (col_ok) {
+        int ht;
+        base = column_base(tab, g, vcol, 2, &ht);
+        const int c = vcol - ht * g.d;
+        if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c;
+    }
     static_for<MBN>([&](auto mbc) {
         constexpr int MB = decltype(mbc)::value;
         static_for<4>([&](auto nb) {
@@ -421,14 +435,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             });
         });
         __syncthreads();
-        for (int item = threadIdx.x; item < ITEMS; item += NT) {
-            const int cg = item & 15, row = (item >> 4) & 31, w = item >> 9;
-            const int vcol = ct * kColTile + cg * 8;
-            if (vcol >= g.ncols) continue;
-            int ht;
-            char* base = column_base(tab, g, vcol, 2, &ht);
-            const int c = vcol - ht * g.d;
-            float* tp = tap ? tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c : nullptr;
+#pragma unroll
+        for (int it = 0; it < ITEMS / NT; ++it) {
+            const int item = threadIdx.x + it * NT;
+            const int row = (item >> 4) & 31, w = item >> 9;
+            if (!col_ok) continue;
             float va[8], vb[8];
             int row_a, row_b = -1;
             if constexpr (FOLD) {
@@ -451,7 +462,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             u32x4 pk;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                pk[i] = (uint32_t)f32_to_bf16(va[2 * i]) | ((uint32_t)f32_to_bf16(va[2 * i + 1]) << 16);
+                pk[i] = pack_bf16x2(va[2 * i], va[2 * i + 1]);
             *(u32x4*)(base + (long long)(g.S + row_a) * rowb) = pk;
             if (tp) {
 #pragma unroll
@@ -460,7 +471,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             if (FOLD) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    pk[i] = (uint32_t)f32_to_bf16(vb[2 * i]) | ((uint32_t)f32_to_bf16(vb[2 * i + 1]) << 16);
+                    pk[i] = pack_bf16x2(vb[2 * i], vb[2 * i + 1]);
                 *(u32x4*)(base + (long long)(g.S + row_b) * rowb) = pk;
                 if (tp) {
 #pragma unroll
