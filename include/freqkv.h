@@ -23,6 +23,12 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#if defined(__GNUC__)
+#define FREQKV_API __attribute__((visibility("default")))
+#else
+#define FREQKV_API
+#endif
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -112,7 +118,7 @@ typedef struct freqkv_profile {
  * Valid ranges: n_heads >= 1; head_dim >= 8 and a multiple of 8; n_sink >= 0;
  * window >= n_sink + 2; cur_len <= layout.token_capacity; 0 < retain_ratio <= 1.
  */
-freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim,
+FREQKV_API freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim,
                             int cur_len, int window, int n_sink, double retain_ratio,
                             freqkv_plan_t* out);
 
@@ -131,7 +137,7 @@ freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head
  * retain_ratio == 1 (Lc == n) is the identity and enqueues nothing (FREQKV_OK).
  * On a negative status no device memory has been written.
  */
-freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
+FREQKV_API freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
                                 int n_heads, int head_dim, int cur_len, int window, int n_sink,
                                 double retain_ratio, void* stream);
 
@@ -139,28 +145,28 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
  * Build and cache the basis table for (window - n_sink, retain_ratio, dtype, flags) on the current
  * device ahead of the first trigger (Appendix A cosine bases fused into one operator).  Optional.
  */
-freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink,
+FREQKV_API freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink,
                                double retain_ratio, void* stream);
 
 /* Human-readable name of a status code (static string, host). */
-const char* freqkv_status_string(freqkv_status_t status);
+FREQKV_API const char* freqkv_status_string(freqkv_status_t status);
 
 /* Text of the last HIP error seen by the calling thread's most recent failing call ("" if none). */
-const char* freqkv_last_error(void);
+FREQKV_API const char* freqkv_last_error(void);
 
 /* Free every cached basis table on every device.  Safe to call more than once. */
-void freqkv_shutdown(void);
+FREQKV_API void freqkv_shutdown(void);
 
 /* Library version: major*10000 + minor*100 + patch. */
-int freqkv_version(void);
+FREQKV_API int freqkv_version(void);
 
 /*
  * Kernel timing with HIP events recorded on the caller's stream around each launch.
  * freqkv_profile_enable(1) starts accumulating (and resets the counters), (0) stops.
  * freqkv_profile_read synchronises on the recorded events and fills *out (host pointer).
  */
-freqkv_status_t freqkv_profile_enable(int on);
-freqkv_status_t freqkv_profile_read(freqkv_profile_t* out);
+FREQKV_API freqkv_status_t freqkv_profile_enable(int on);
+FREQKV_API freqkv_status_t freqkv_profile_read(freqkv_profile_t* out);
 
 /*
  * Calibration of the device the library runs on, for quoting rooflines against measured as well as
@@ -171,9 +177,9 @@ freqkv_status_t freqkv_profile_read(freqkv_profile_t* out);
  *   freqkv_calibrate_mfma: times a register-only loop of v_mfma_f32_32x32x16_f16 on random operands
  *       (one workgroup per CU, `iters` x 16 instructions per wave) and returns TFLOP/s.
  */
-freqkv_status_t freqkv_calibrate_copy(void* dst, const void* src, size_t bytes, int repeats,
+FREQKV_API freqkv_status_t freqkv_calibrate_copy(void* dst, const void* src, size_t bytes, int repeats,
                                       void* stream, double* gbs_out /* host */);
-freqkv_status_t freqkv_calibrate_mfma(int iters, void* stream, double* tflops_out /* host */);
+FREQKV_API freqkv_status_t freqkv_calibrate_mfma(int iters, void* stream, double* tflops_out /* host */);
 
 #ifdef __cplusplus
 }

@@ -289,3 +289,56 @@ def test_iterative_schedule_small():
     drift = float(np.max(np.abs(got - fr) - 0.5 * bf16_ulp(fr))) / rms
     _say(f"  triggers {cache.triggers}, teacher-forced worst {worst:.3e}, free-running drift {drift:.3e}")
     assert drift <= 5e-2
+
+
+# ------------------------------------------------------------------------------------------
+# launch plan: more (layer, K|V) slabs than one pointer table holds; caller's stream; helpers
+# ------------------------------------------------------------------------------------------
+
+def test_many_layers_split_into_passes():
+    """100 layers = 200 slabs > 192 per launch group: the call makes two passes."""
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=100, n_heads=1, head_dim=64, window=132)
+    _say("100 layers x 1 head x 64, window 132")
+    k, v = _mk(wl, seed=8, capacity=140)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, 132)
+    assert rc == 0 and p.head_tensors == 200
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, 132, TOL_BF16)
+
+
+def test_runs_on_the_callers_stream_and_prepare_is_idempotent():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=516)
+    k, v = _mk(wl, seed=12)
+    ka, va = k.clone(), v.clone()
+    rc, p, _ = _run(ka, va, wl, 516, tap=False)            # default stream
+    assert rc == 0
+    side = torch.cuda.Stream()
+    assert fk.prepare(fk.BF16, 0, 516, 4, 0.5, side) == 0   # basis already cached: only a stream wait
+    L = binding.layout_for(k)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        assert fk.compress(k, v, L, 2, 128, 516, 516, 4, 0.5, side) == 0
+    side.synchronize()
+    assert torch.equal(k, ka) and torch.equal(v, va)        # same bits whichever stream ran it
+
+
+def test_profile_and_calibration_helpers():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=4, window=516)
+    k, v = _mk(wl, seed=13)
+    fk.profile_enable(True)
+    for _ in range(3):
+        rc, p, _ = _run(k, v, wl, 516, tap=False)
+        assert rc == 0
+    prof = fk.profile_read()
+    fk.profile_enable(False)
+    assert prof.calls == 3 and prof.launches_contract == 3 and prof.launches_prepare == 3
+    assert prof.launches_tail == 0 and prof.ms_contract > 0 and prof.ms_prepare > 0
+    a = torch.empty(1 << 26, dtype=torch.uint8, device=DEV)
+    b = torch.randint(0, 255, (1 << 26,), dtype=torch.uint8, device=DEV)
+    gbs = fk.calibrate_copy(a, b, 1 << 26, 5)
+    assert torch.equal(a, b) and 100.0 < gbs < 16000.0
+    tf = fk.calibrate_mfma(2000)
+    assert 100.0 < tf < 2600.0
+    _say(f"  copy {gbs:.0f} GB/s, mfma loop {tf:.0f} TFLOP/s")
