@@ -24,14 +24,14 @@ MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # HBM bytes (read + write) of one contraction launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # what the same counters read for the library's plain copy kernel (profiles/contract_llama3_8b_128k_pmc.txt).
-TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2 * 2.622e6 + 5.24e5) * 1024}
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
 
 
 def cpu_baseline(wl, k_cache, cores):
     """The fp64 oracle, as it stands, on `cores` host threads over a bounded sample of head-tensors."""
     import numpy as np
     from oracle import freqkv_oracle as orc
-    n_sample = 4 * cores          # about 10-20 s of host work at span 8188
+    n_sample = 8 * cores          # about 10-20 s of host work at span 8188
     flat = k_cache.reshape(-1, k_cache.shape[3], k_cache.shape[4])
     idx = [int(i) for i in np.linspace(0, flat.shape[0] - 1, n_sample)]
     heads = [flat[i].to("cpu").float().double().numpy() for i in idx]
