@@ -52,6 +52,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dropping", action="store_true",
+                    help="time the Dropping variant (row moves only): the memcpy-roofline reference of the write-back step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by head with no communication); "
@@ -72,9 +74,9 @@ def main():
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)
     synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
-    L = binding.layout_for(k)
+    L = binding.layout_for(k, flags=fk.FLAG_DROPPING if args.dropping else 0)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
-    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(p.workspace_bytes, 1 << 30 if args.dropping else 256), dtype=torch.uint8, device=dev)
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
     stream = torch.cuda.current_stream()
 
@@ -82,7 +84,7 @@ def main():
         fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, stream)
 
     cpu = None
-    if not args.no_cpu_baseline and wl.dtype == torch.bfloat16:
+    if not args.no_cpu_baseline and wl.dtype == torch.bfloat16 and not args.dropping:
         cores = min(16, os.cpu_count() or 1)
         cpu = cpu_baseline(wl, k, cores)
 
@@ -101,7 +103,7 @@ def main():
     fk.profile_enable(False)
 
     # what this device sustains: plain copy (read+write) and a register-only fp16 MFMA loop on random operands
-    calib_n = min(p.workspace_bytes // 2, 1 << 30) // 16 * 16
+    calib_n = min(ws.numel() // 2, 1 << 30) // 16 * 16
     wsv = ws.view(torch.uint8)
     copy_gbs = fk.calibrate_copy(wsv[calib_n:].data_ptr(), wsv.data_ptr(), calib_n, 10, stream) if calib_n >= 1 << 20 else None
     mfma_tflops = fk.calibrate_mfma(20000, stream)
@@ -116,12 +118,21 @@ def main():
     ms_contract = prof.ms_contract / launches
     ms_prepare = prof.ms_prepare / max(int(prof.launches_prepare), 1)
     flops_launch = p.flops_executed * args.steps / launches
-    achieved = flops_launch / (ms_contract * 1e-3) / 1e12
-    roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
-            "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
-            "ms_per_launch": ms_contract, "flops_per_launch": flops_launch,
-            "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops}
+    achieved = flops_launch / max(ms_contract * 1e-3, 1e-12) / 1e12
+    if args.dropping:
+        # the whole step is k_move_rows launches (timed as one span per call by the library)
+        ms_move = prof.ms_tail / max(int(prof.calls), 1)
+        gbs = p.bytes_algorithmic / (ms_move * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "k_move_rows", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": None, "ms_per_launch": ms_move,
+                "bytes_per_launch": p.bytes_algorithmic, "measured_copy_gbs": copy_gbs,
+                "frac_of_measured_copy": gbs / copy_gbs if copy_gbs else None}
+    else:
+        roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                "ms_per_launch": ms_contract, "flops_per_launch": flops_launch,
+                "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops}
 
     out = {
         "metric": "KV compression throughput (GB/s KV in)",
@@ -134,7 +145,7 @@ def main():
                                f"head_dim {wl.head_dim}, window {wl.window}, {wl.n_sink} sinks, ratio "
                                f"{wl.retain_ratio}; span {n} -> {p.retained_len}; {p.head_tensors} head-tensors "
                                f"per trigger; one trigger per step",
-                   "variant": int(p.variant)},
+                   "variant": int(p.variant), "operator": "dropping" if args.dropping else "freqkv"},
         "tflops_executed": p.flops_executed / (dt / args.steps) / 1e12,
         "tflops_dense_equivalent": p.flops_dense / (dt / args.steps) / 1e12,
         "gbs_algorithmic": p.bytes_algorithmic / (dt / args.steps) / 1e9,

@@ -50,6 +50,9 @@ typedef enum {
 
 /* layout.flags */
 #define FREQKV_FLAG_NO_RESCALE 0x1u   /* omit the sqrt(Lc/n) factor (rescaling ablation, appendix "Effect of rescaling") */
+#define FREQKV_FLAG_DROPPING   0x2u   /* the "Dropping" variant (appendix on the compression overhead): no transform,
+                                         the Lc most recent rows of the span, [window-Lc, window), move to [n_sink, n_sink+Lc);
+                                         same sinks, same retained size, same tail rule; needs no workspace and no basis */
 
 /*
  * Memory description of the cache ("layout"): everything the scalar arguments of
@@ -88,7 +91,7 @@ typedef struct freqkv_plan {
     int32_t retained_len;       /* Lc = clamp(floor(retain_ratio*n + 1e-9), 1, n)                */
     int32_t new_len;            /* cache length after the call: n_sink + Lc + (cur_len - window) */
     int32_t head_tensors;       /* 2 * n_layers * batch * n_heads                                */
-    int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA */
+    int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA, 4 dropping (row moves only) */
     int32_t reserved;
     size_t  workspace_bytes;    /* scratch for all head-tensors in one pass (fastest)            */
     size_t  workspace_min_bytes;/* smallest scratch accepted (one (layer,K|V) slab per pass)     */

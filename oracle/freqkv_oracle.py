@@ -153,6 +153,14 @@ def compress_head(cache, cur_len: int, window: int, n_sink: int, retain_ratio: f
     return out
 
 
+def drop_head(cache, cur_len: int, window: int, n_sink: int, retain_ratio: float) -> np.ndarray:
+    """The "Dropping" variant (appendix on the compression overhead): no transform, the span keeps
+    its Lc most recent rows; same sinks, retained size and tail rule as compress_head."""
+    a = _as2d(cache)[:cur_len]
+    lc = retained_len(window - n_sink, retain_ratio)
+    return np.concatenate([a[:n_sink], a[window - lc:window], a[window:cur_len]], axis=0)
+
+
 def compress_heads(heads, cur_len: int, window: int, n_sink: int, retain_ratio: float,
                    threads: int = 1) -> list:
     """compress_head over a list of head-tensors, optionally on several host threads."""

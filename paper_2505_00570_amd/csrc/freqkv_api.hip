@@ -110,7 +110,7 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     if (cur_len < 0 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
     if (!(ratio > 0.0) || !(ratio <= 1.0)) return FREQKV_E_INVALID;      // also rejects NaN
     if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
-    if (L->flags & ~FREQKV_FLAG_NO_RESCALE) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING)) return FREQKV_E_INVALID;
     if (L->stride_token < head_dim) return FREQKV_E_INVALID;
     if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
     if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;
@@ -130,6 +130,7 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     sh.hts_per_slab = hts;
     sh.nslabs = 2 * L->n_layers;
     if (sh.Lc == sh.n) sh.variant = kNone;
+    else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
     else sh.variant = (sh.n % 2 == 0 && sh.Lc % 2 == 0) ? kFoldF16 : kPlainF16;
     *out = sh;
@@ -249,7 +250,9 @@ freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head
     out->head_tensors = (int)(sh.nslabs * sh.hts_per_slab);
     out->variant = sh.variant;
     double hts = (double)sh.nslabs * (double)sh.hts_per_slab;
-    if (sh.variant != kNone) {
+    if (sh.variant == kDrop) {
+        out->bytes_algorithmic = (2.0 * sh.Lc + 2.0 * sh.tail) * sh.d * sh.elem * hts;
+    } else if (sh.variant != kNone) {
         Geom g = make_geom(sh, *layout, sh.nslabs, 0);
         int max_slabs = sh.nslabs < kMaxSlabs ? sh.nslabs : kMaxSlabs;
         out->workspace_bytes = pass_workspace(sh, max_slabs);
@@ -272,7 +275,7 @@ freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink
     Shape sh;
     freqkv_status_t rc = check_shape(&L, 1, 8, window, window, n_sink, retain_ratio, &sh);
     if (rc < 0) return rc;
-    if (sh.variant == kNone) return FREQKV_OK;
+    if (sh.variant == kNone || sh.variant == kDrop) return FREQKV_OK;
     Geom g = make_geom(sh, L, 1, 0);
     void* basis = nullptr;
     return get_basis(sh, g, !(flags & FREQKV_FLAG_NO_RESCALE), (hipStream_t)stream, &basis);
@@ -302,10 +305,33 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
     if (cur_len < window) return FREQKV_NOOP;
     if (sh.variant == kNone) return FREQKV_OK;                // retain_ratio == 1: identity
 
+    hipStream_t st = (hipStream_t)stream;
+    if (sh.variant == kDrop) {
+        // Dropping: rows [W-Lc, W) -> [S, S+Lc), then the tail -> [S+Lc, ...); both in chunks of at most
+        // (n - Lc) rows, the distance of the move, so that no chunk overlaps its own source.
+        if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
+        const int gap = sh.n - sh.Lc;
+        for (int s0 = 0; s0 < sh.nslabs; s0 += kMaxSlabs) {
+            int slabs = sh.nslabs - s0 < kMaxSlabs ? sh.nslabs - s0 : kMaxSlabs;
+            Geom g = make_geom(sh, L, slabs, s0);
+            SlabTable tab;
+            memset(&tab, 0, sizeof(tab));
+            for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
+            ProfSpan sp;
+            HIP_TRY(prof_begin(st, 2, &sp));
+            for (int r0 = 0; r0 < sh.Lc + sh.tail; r0 += gap) {
+                int rows = sh.Lc + sh.tail - r0 < gap ? sh.Lc + sh.tail - r0 : gap;
+                // rows [W-Lc, cur_len) are contiguous: the retained rows and the tail move by the same distance
+                HIP_TRY(launch_move_rows(tab, g, sh.elem, sh.W - sh.Lc + r0, sh.S + r0, rows, st));
+            }
+            HIP_TRY(prof_end(st, &sp));
+        }
+        return FREQKV_OK;
+    }
+
     size_t min_ws = pass_workspace(sh, 1);
     if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < min_ws) return FREQKV_E_WORKSPACE;
 
-    hipStream_t st = (hipStream_t)stream;
     const int rescale = !(L.flags & FREQKV_FLAG_NO_RESCALE);
 
     // slabs per pass: as many as the workspace and the pointer table hold

@@ -42,7 +42,7 @@ struct Geom {
     long long tap_slab0; // index of this pass's first slab in the caller's [2][n_layers] order
 };
 
-enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3 };
+enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4 };
 
 // ---- basis construction (fp64 closed form, rounded once) -------------------------
 // G: [Kpad/8][Grows][8] fp16.  Folded: rows [0,Mpad) even part, rows [Mpad,2Mpad) odd part.

@@ -177,3 +177,13 @@ def test_compress_validates_before_touching_the_device():
         fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5)
     # invalid scalars
     assert fk.compress(fake, fake, L, 8, 128, 9000, 8192, 4, 0.5, check=False) == binding.E_INVALID
+
+
+def test_plan_dropping_variant_needs_no_workspace():
+    L = _layout()
+    L.flags = fk.FLAG_DROPPING
+    rc, p = fk.plan(L, 8, 128, 8192, 8192, 4, 0.5)
+    assert rc == 0 and p.variant == 4
+    assert (p.retained_len, p.new_len) == (4094, 4098)
+    assert p.workspace_bytes == 0 and p.workspace_min_bytes == 0 and p.basis_bytes == 0 and p.flops_executed == 0
+    assert p.bytes_algorithmic == pytest.approx(2 * 4094 * 128 * 2 * 512)

@@ -342,3 +342,29 @@ def test_profile_and_calibration_helpers():
     tf = fk.calibrate_mfma(2000)
     assert 100.0 < tf < 2600.0
     _say(f"  copy {gbs:.0f} GB/s, mfma loop {tf:.0f} TFLOP/s")
+
+
+# ------------------------------------------------------------------------------------------
+# Dropping variant: pure row moves, bit-exact against the oracle's index rule
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("window,sink,ratio,extra,dtype", [(300, 4, 0.5, 0, torch.bfloat16), (300, 4, 0.75, 0, torch.bfloat16),
+                                                           (300, 0, 0.25, 33, torch.bfloat16), (260, 8, 0.9, 400, torch.float32)])
+def test_dropping_variant(window, sink, ratio, extra, dtype):
+    base = "tiny" if dtype == torch.float32 else "llama2_7b_layer"
+    wl = synth.small(synth.WORKLOADS[base], n_layers=2, n_heads=3, head_dim=64, window=window, n_sink=sink,
+                     retain_ratio=ratio)
+    cur = window + extra
+    k, v = _mk(wl, seed=21, capacity=cur + 5, cur_len=cur)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    L = binding.layout_for(k, flags=fk.FLAG_DROPPING)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, cur, window, sink, ratio)
+    assert p.variant == 4
+    assert fk.compress(k, v, L, wl.n_heads, wl.head_dim, cur, window, sink, ratio) == 0   # no workspace needed
+    torch.cuda.synchronize()
+    for before, after in ((k0, k.cpu()), (v0, v.cpu())):
+        for l in range(2):
+            for h in range(3):
+                ref = orc.drop_head(f64(before[l, 0, h]), cur, window, sink, ratio)
+                assert np.array_equal(f64(after[l, 0, h, :p.new_len]), ref)
+                assert torch.equal(after[l, 0, h, cur:], before[l, 0, h, cur:])

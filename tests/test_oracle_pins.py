@@ -229,3 +229,14 @@ def test_threads_give_same_result():
     b = orc.compress_heads(heads, 40, 40, 2, 0.5, threads=4)
     for u, v in zip(a, b):
         assert np.array_equal(u, v)
+
+
+# -- Dropping variant (appendix on the compression overhead): an index rule, checked on a literal example --
+
+def test_dropping_literal_example():
+    # 10 cached tokens, window 8, 2 sinks, ratio 0.5: span = tokens 2..7, Lc = 3 most recent of it = 5,6,7; tail 8,9
+    cache = np.arange(10, dtype=np.float64)[:, None] * np.array([[1.0, 10.0]])
+    out = orc.drop_head(cache, 10, 8, 2, 0.5)
+    assert out[:, 0].tolist() == [0, 1, 5, 6, 7, 8, 9]
+    assert out[:, 1].tolist() == [0, 10, 50, 60, 70, 80, 90]
+    assert out.shape[0] == orc.new_len(10, 8, 2, 0.5)
