@@ -110,7 +110,20 @@ typedef struct freqkv_profile {
     double  ms_prepare;
     double  ms_contract;
     double  ms_tail;
+    int64_t launches_attend;    /* freqkv_attend_decode passes (both kernels of a pass as one span) */
+    double  ms_attend;
 } freqkv_profile_t;
+
+/* Result of the attention buffer-plan query (host arithmetic only). */
+typedef struct freqkv_attend_plan {
+    int32_t n_split;            /* row chunks each KV head's cache is cut into                       */
+    int32_t chunk_rows;         /* rows per chunk                                                    */
+    int32_t heads_together;     /* query heads of one KV group that one workgroup serves (1, 2 or 4) */
+    int32_t reserved;
+    size_t  workspace_bytes;    /* scratch for the per-chunk softmax states                          */
+    double  bytes_algorithmic;  /* K and V rows [0, cur_len) read once, q read, out written          */
+    double  flops;              /* 4 * cur_len * head_dim per query head (scores and weighted sum)   */
+} freqkv_attend_plan_t;
 
 /*
  * Buffer-plan query (Sec. 3.3 / Sec. 4.1 arithmetic).  HOST only: needs no GPU, touches no
@@ -150,6 +163,40 @@ FREQKV_API freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout
  */
 FREQKV_API freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink,
                                double retain_ratio, void* stream);
+
+/*
+ * Buffer plan of freqkv_attend_decode.  HOST only, like freqkv_plan.  Valid ranges: n_kv_heads >= 1,
+ * n_q_heads a multiple of n_kv_heads, 1 <= cur_len <= layout.token_capacity; head_dim 64, 128 or 256
+ * (anything else: FREQKV_E_UNSUPPORTED).
+ */
+FREQKV_API freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
+                                   int head_dim, int cur_len, freqkv_attend_plan_t* out);
+
+/*
+ * Decode attention of one incoming token per sequence over the compacted cache, for every layer the
+ * layout describes (Sec. 3.3 Eq. 4, Sec. 3.4 Eq. 5): the token attends to all rows [0, cur_len) of its
+ * KV head (sinks, compressed rows, tokens appended since, and itself: its own key and value must
+ * already be the last cached row).  Keys are cached WITHOUT the rotary embedding; the key in row p is
+ * rotated with position p, an index inside the cache, as it is read, and the query with q_pos (closing
+ * paragraph of Sec. 3.4, appendix on key states with RoPE).  Rotary pairing: channel i with channel
+ * i + head_dim/2, angle pos * rope_base^(-2i/head_dim).  Query head h reads KV head
+ * h / (n_q_heads / n_kv_heads).  Scores are scaled by 1/sqrt(head_dim).
+ *   q        [n_layers][batch][n_q_heads][head_dim], dense, layout.dtype, un-rotated queries
+ *   k, v     the caches, addressed through `layout` exactly as in freqkv_compress (n_heads = n_kv_heads)
+ *   out      [n_layers][batch][n_q_heads][head_dim], dense, layout.dtype
+ *   lse      optional (may be NULL): [n_layers][batch][n_q_heads] fp32, natural log of the sum of
+ *            exp(score); lets a caller merge results over caches sharded by token
+ *   q_pos    in-cache position of the query, or -1 for cur_len - 1
+ *   rope_base  e.g. 10000 (LLaMA-2) or 500000 (LLaMA-3); 0 applies no rotary embedding
+ *   layout.workspace  at least freqkv_attend_plan(...).workspace_bytes, 256-byte aligned
+ * q, out and lse must be 16-byte aligned.  The call only enqueues work on `stream`.  The first call
+ * for a new (device, head_dim, rope_base) builds a small cached table (one allocation).
+ * On a negative status no device memory has been written.
+ */
+FREQKV_API freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v, void* out,
+                                     float* lse, const freqkv_layout_t* layout, int n_q_heads,
+                                     int n_kv_heads, int head_dim, int cur_len, int q_pos,
+                                     double rope_base, void* stream);
 
 /* Human-readable name of a status code (static string, host). */
 FREQKV_API const char* freqkv_status_string(freqkv_status_t status);

@@ -56,6 +56,15 @@ class Profile(C.Structure):
         ("calls", C.c_int64), ("launches_prepare", C.c_int64), ("launches_contract", C.c_int64),
         ("launches_tail", C.c_int64),
         ("ms_prepare", C.c_double), ("ms_contract", C.c_double), ("ms_tail", C.c_double),
+        ("launches_attend", C.c_int64), ("ms_attend", C.c_double),
+    ]
+
+
+class AttendPlan(C.Structure):
+    """struct freqkv_attend_plan (include/freqkv.h)."""
+    _fields_ = [
+        ("n_split", C.c_int32), ("chunk_rows", C.c_int32), ("heads_together", C.c_int32), ("reserved", C.c_int32),
+        ("workspace_bytes", C.c_size_t), ("bytes_algorithmic", C.c_double), ("flops", C.c_double),
     ]
 
 
@@ -76,6 +85,11 @@ def load() -> C.CDLL:
         lib.freqkv_compress.argtypes = [C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_compress.restype = C.c_int
+        lib.freqkv_attend_plan.argtypes = [LP, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(AttendPlan)]
+        lib.freqkv_attend_plan.restype = C.c_int
+        lib.freqkv_attend_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
+                                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_void_p]
+        lib.freqkv_attend_decode.restype = C.c_int
         lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_prepare.restype = C.c_int
         lib.freqkv_status_string.argtypes = [C.c_int]
@@ -142,6 +156,25 @@ def compress(k, v, layout: Layout, n_heads: int, head_dim: int, cur_len: int, wi
     per-layer device pointers when layout.pointer_table == 1.  Returns the status (0 or 1)."""
     rc = load().freqkv_compress(_dev_ptr(k), _dev_ptr(v), C.byref(layout), n_heads, head_dim, cur_len,
                                 window, n_sink, float(retain_ratio), _stream_ptr(stream))
+    return _check(rc) if check else rc
+
+
+def attend_plan(layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int, cur_len: int, check: bool = True):
+    """freqkv_attend_plan: returns (status, AttendPlan).  Host arithmetic only."""
+    out = AttendPlan()
+    rc = load().freqkv_attend_plan(C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, C.byref(out))
+    if check:
+        _check(rc)
+    return rc, out
+
+
+def attend_decode(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                  cur_len: int, q_pos: int = -1, rope_base: float = 10000.0, stream=None, check: bool = True) -> int:
+    """freqkv_attend_decode.  q, out: dense [layer, batch, q_head, dim] device tensors of the cache dtype;
+    lse: fp32 [layer, batch, q_head] device tensor or None; k, v as in compress."""
+    rc = load().freqkv_attend_decode(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(out), _dev_ptr(lse),
+                                     C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_pos,
+                                     float(rope_base), _stream_ptr(stream))
     return _check(rc) if check else rc
 
 

@@ -188,6 +188,100 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
     return FREQKV_OK;
 }
 
+// ---------------------------------------------------------------- attention: shape, plan, rotary table
+struct AttShape {
+    int d, n_q, n_kv, G, GT, batch, n_layers, cur_len, elem;
+    int n_split, chunk;
+    long long units_all;        // n_layers * batch * n_kv
+    size_t ml_offset;           // byte offset of the (max, sum) region inside the workspace
+    size_t workspace_bytes;
+};
+
+freqkv_status_t check_attend(const freqkv_layout_t* L, int n_q, int n_kv, int d, int cur_len, AttShape* out)
+{
+    if (!L) return FREQKV_E_INVALID;
+    if (L->dtype != FREQKV_BF16 && L->dtype != FREQKV_F32) return FREQKV_E_INVALID;
+    if (L->n_layers < 1 || L->batch < 1 || n_kv < 1 || n_q < 1 || n_q % n_kv) return FREQKV_E_INVALID;
+    if (d < 8) return FREQKV_E_INVALID;
+    if (d != 64 && d != 128 && d != 256) return FREQKV_E_UNSUPPORTED;
+    if (cur_len < 1 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
+    if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING)) return FREQKV_E_INVALID;
+    if (L->stride_token < d) return FREQKV_E_INVALID;
+    if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
+    if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;
+    if (L->stride_head < 0 || L->stride_batch < 0) return FREQKV_E_INVALID;
+    if (L->n_layers > (1 << 20)) return FREQKV_E_UNSUPPORTED;
+    long long units = (long long)L->n_layers * L->batch * n_kv;
+    if (units * (n_q / n_kv) > (1LL << 24)) return FREQKV_E_UNSUPPORTED;    // grid and index ranges
+
+    AttShape a;
+    a.d = d; a.n_q = n_q; a.n_kv = n_kv; a.G = n_q / n_kv;
+    a.GT = a.G % 4 == 0 ? 4 : (a.G % 2 == 0 ? 2 : 1);
+    a.batch = L->batch; a.n_layers = L->n_layers; a.cur_len = cur_len;
+    a.elem = L->dtype == FREQKV_BF16 ? 2 : 4;
+    a.units_all = units;
+    // Row chunks: enough workgroups for two rounds over 256 compute units at two workgroups each, chunks
+    // no shorter than four loop steps and no longer than 64 rows per lane group (bounds the drift of the
+    // cos/sin recurrence and the share of the per-workgroup set-up).
+    const int step = attend_row_step(d);
+    const long long wgs_per_split = units * (a.G / a.GT);
+    long long ns = (1024 + wgs_per_split - 1) / wgs_per_split;
+    long long ns_max = cur_len / (8 * step);
+    long long ns_min = ((long long)cur_len + 64 * step - 1) / (64 * step);
+    if (ns > ns_max) ns = ns_max;
+    if (ns < ns_min) ns = ns_min;
+    if (ns < 1) ns = 1;
+    long long chunk = round_up(((long long)cur_len + ns - 1) / ns, 2 * step);
+    ns = ((long long)cur_len + chunk - 1) / chunk;
+    if (wgs_per_split * ns > (1LL << 30)) return FREQKV_E_UNSUPPORTED;
+    a.n_split = (int)ns; a.chunk = (int)chunk;
+    size_t acc_bytes = (size_t)units * a.G * ns * d * sizeof(float);
+    a.ml_offset = (size_t)round_up((long long)acc_bytes, 256);
+    a.workspace_bytes = a.ml_offset + (size_t)units * a.G * ns * 2 * sizeof(float);
+    *out = a;
+    return FREQKV_OK;
+}
+
+struct RopeKey {
+    int device, d;
+    double base;
+    bool operator<(const RopeKey& o) const { return std::tie(device, d, base) < std::tie(o.device, o.d, o.base); }
+};
+std::map<RopeKey, BasisEntry> g_rope;
+
+freqkv_status_t get_rope_table(int d, double base, hipStream_t st, RopeEntry** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    RopeKey key{dev, d, base};
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto it = g_rope.find(key);
+    if (it == g_rope.end()) {
+        BasisEntry e;
+        e.bytes = (size_t)(d / 2) * sizeof(RopeEntry);
+        hipError_t err = hipMalloc(&e.ptr, e.bytes);
+        if (err != hipSuccess) {
+            set_error("hipMalloc(rotary table)", err);
+            (void)hipGetLastError();
+            return FREQKV_E_ALLOC;
+        }
+        err = launch_rope_table((RopeEntry*)e.ptr, d, base, st);
+        if (err == hipSuccess) err = hipEventCreateWithFlags(&e.ready, hipEventDisableTiming);
+        if (err == hipSuccess) err = hipEventRecord(e.ready, st);
+        if (err != hipSuccess) {
+            set_error("rotary table build", err);
+            (void)hipFree(e.ptr);
+            return FREQKV_E_HIP;
+        }
+        it = g_rope.emplace(key, e).first;
+    } else {
+        HIP_TRY(hipStreamWaitEvent(st, it->second.ready, 0));
+    }
+    *out = (RopeEntry*)it->second.ptr;
+    return FREQKV_OK;
+}
+
 // ---------------------------------------------------------------- profiling
 struct ProfSpan { hipEvent_t a, b; int kind; };
 bool g_prof_on = false;
@@ -234,7 +328,7 @@ const char* freqkv_status_string(freqkv_status_t s)
 
 const char* freqkv_last_error(void) { return g_last_error; }
 
-int freqkv_version(void) { return 100; }
+int freqkv_version(void) { return 101; }
 
 freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim, int cur_len,
                             int window, int n_sink, double retain_ratio, freqkv_plan_t* out)
@@ -384,6 +478,89 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
     return FREQKV_OK;
 }
 
+freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
+                                   int cur_len, freqkv_attend_plan_t* out)
+{
+    if (!out) return FREQKV_E_INVALID;
+    AttShape a;
+    freqkv_status_t rc = check_attend(layout, n_q_heads, n_kv_heads, head_dim, cur_len, &a);
+    if (rc < 0) return rc;
+    memset(out, 0, sizeof(*out));
+    out->n_split = a.n_split;
+    out->chunk_rows = a.chunk;
+    out->heads_together = a.GT;
+    out->workspace_bytes = a.workspace_bytes;
+    double units = (double)a.units_all;
+    out->bytes_algorithmic = units * (2.0 * cur_len * a.d * a.elem + 2.0 * a.G * a.d * a.elem);
+    out->flops = units * a.G * 4.0 * cur_len * a.d;
+    return FREQKV_OK;
+}
+
+freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v, void* out, float* lse,
+                                     const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
+                                     int cur_len, int q_pos, double rope_base, void* stream)
+{
+    g_last_error[0] = 0;
+    AttShape a;
+    freqkv_status_t rc = check_attend(layout, n_q_heads, n_kv_heads, head_dim, cur_len, &a);
+    if (rc < 0) return rc;
+    if (!q || !k || !v || !out) return FREQKV_E_INVALID;
+    if (((uintptr_t)q | (uintptr_t)out | (uintptr_t)lse) & 15) return FREQKV_E_INVALID;
+    if (q_pos < -1 || q_pos >= (1 << 24)) return FREQKV_E_INVALID;
+    if (!(rope_base >= 0.0) || !(rope_base < 1e30)) return FREQKV_E_INVALID;      // also rejects NaN
+    if (q_pos < 0) q_pos = cur_len - 1;
+    const freqkv_layout_t& L = *layout;
+
+    std::vector<char*> bases((size_t)2 * a.n_layers);          // [layer][K|V]
+    for (int l = 0; l < a.n_layers; ++l) {
+        for (int kv = 0; kv < 2; ++kv) {
+            const void* root = kv ? v : k;
+            char* p = L.pointer_table ? (char*)((void* const*)root)[l]
+                                      : (char*)root + (long long)l * L.stride_layer * a.elem;
+            if (!p || ((uintptr_t)p & 15)) return FREQKV_E_INVALID;
+            bases[(size_t)2 * l + kv] = p;
+        }
+    }
+    if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < a.workspace_bytes)
+        return FREQKV_E_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    const int rope = rope_base > 0.0;
+    RopeEntry* rt = nullptr;
+    rc = get_rope_table(a.d, rope ? rope_base : 1.0, st, &rt);
+    if (rc < 0) return rc;
+
+    float* part_acc = (float*)L.workspace;
+    float* part_ml = (float*)((char*)L.workspace + a.ml_offset);
+    const int upl = a.batch * a.n_kv;
+    const int layers_per_pass = kMaxSlabs / 2;
+    for (int l0 = 0; l0 < a.n_layers; l0 += layers_per_pass) {
+        int layers = a.n_layers - l0 < layers_per_pass ? a.n_layers - l0 : layers_per_pass;
+        SlabTable tab;
+        memset(&tab, 0, sizeof(tab));
+        for (int i = 0; i < 2 * layers; ++i) tab.base[i] = bases[(size_t)2 * l0 + i];
+        AttGeom g;
+        memset(&g, 0, sizeof(g));
+        g.d = a.d; g.G = a.G; g.GT = a.GT; g.n_kv = a.n_kv;
+        g.units = layers * upl; g.units_per_layer = upl;
+        g.cur_len = cur_len; g.q_pos = q_pos; g.rope = rope;
+        g.n_split = a.n_split; g.chunk = a.chunk;
+        g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
+        g.qscale = (float)(1.4426950408889634 / std::sqrt((double)a.d));
+        const long long head0 = (long long)l0 * upl * a.G;                 // first query head of this pass
+        const char* qp = (const char*)q + head0 * a.d * a.elem;
+        char* op = (char*)out + head0 * a.d * a.elem;
+        float* pa = part_acc + head0 * a.n_split * a.d;
+        float* pm = part_ml + head0 * a.n_split * 2;
+        ProfSpan sp;
+        HIP_TRY(prof_begin(st, 3, &sp));
+        HIP_TRY(launch_attend_partial(tab, g, a.elem, qp, rt, pa, pm, st));
+        HIP_TRY(launch_attend_merge(g, a.elem, pa, pm, op, lse ? lse + head0 : nullptr, st));
+        HIP_TRY(prof_end(st, &sp));
+    }
+    return FREQKV_OK;
+}
+
 void freqkv_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mu);
@@ -398,6 +575,15 @@ void freqkv_shutdown(void)
         (void)hipFree(kv.second.ptr);
     }
     g_basis.clear();
+    for (auto& kv : g_rope) {
+        if (hipSetDevice(kv.first.device) != hipSuccess) continue;
+        if (kv.second.ready) {
+            (void)hipEventSynchronize(kv.second.ready);
+            (void)hipEventDestroy(kv.second.ready);
+        }
+        (void)hipFree(kv.second.ptr);
+    }
+    g_rope.clear();
     for (auto& sp : g_prof_spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     g_prof_spans.clear();
     if (have_dev) (void)hipSetDevice(cur);
@@ -474,7 +660,8 @@ freqkv_status_t freqkv_profile_read(freqkv_profile_t* out)
         HIP_TRY(hipEventElapsedTime(&ms, sp.a, sp.b));
         if (sp.kind == 0) { g_prof_acc.ms_prepare += ms; g_prof_acc.launches_prepare++; }
         else if (sp.kind == 1) { g_prof_acc.ms_contract += ms; g_prof_acc.launches_contract++; }
-        else { g_prof_acc.ms_tail += ms; g_prof_acc.launches_tail++; }
+        else if (sp.kind == 2) { g_prof_acc.ms_tail += ms; g_prof_acc.launches_tail++; }
+        else { g_prof_acc.ms_attend += ms; g_prof_acc.launches_attend++; }
         (void)hipEventDestroy(sp.a);
         (void)hipEventDestroy(sp.b);
     }

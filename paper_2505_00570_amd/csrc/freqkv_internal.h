@@ -68,4 +68,39 @@ hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes,
 hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_calib_mfma(float* out, int blocks, int iters, hipStream_t st);
 
+// ---- decode attention over the compacted cache ---------------------------------------------------
+// Geometry of one attention pass (by-value kernel argument).  A "unit" is one (layer, batch, KV head).
+struct AttGeom {
+    int d;                 // head_dim: 64, 128 or 256
+    int G;                 // query heads per KV head
+    int GT;                // query heads one workgroup handles together: 1, 2 or 4, divides G
+    int n_kv;              // KV heads
+    int units;             // layers in this pass * batch * n_kv
+    int units_per_layer;   // batch * n_kv
+    int cur_len;           // cached rows, >= 1
+    int q_pos;             // in-cache position of the query
+    int rope;              // 1: rotate query and keys at read time, 0: plain dot products
+    int n_split;           // row chunks per unit
+    int chunk;             // rows per chunk, a multiple of 2 * attend_row_step(d)
+    long long stride_batch, stride_head, stride_token;   // elements
+    float qscale;          // log2(e) / sqrt(d)
+};
+
+// One rotary pair: its frequency and the rotation that advances the position by attend_row_step(d) rows.
+struct RopeEntry {
+    double theta;
+    float cd, sd;
+};
+
+// Rows between two consecutive rows handled by one lane group of the attention kernel.
+inline int attend_row_step(int d) { return 4096 / d; }
+
+hipError_t launch_rope_table(RopeEntry* rt, int d, double base, hipStream_t st);
+// tab.base[2*i] / [2*i+1]: K / V slab of the pass's i-th layer.  part_acc: [units*G][n_split][d] fp32,
+// part_ml: [units*G][n_split][2] fp32 (running maximum in the exp2 domain, sum of weights).
+hipError_t launch_attend_partial(const SlabTable& tab, const AttGeom& g, int elem_bytes, const void* q,
+                                 const RopeEntry* rt, float* part_acc, float* part_ml, hipStream_t st);
+hipError_t launch_attend_merge(const AttGeom& g, int elem_bytes, const float* part_acc, const float* part_ml,
+                               void* out, float* lse, hipStream_t st);
+
 }  // namespace freqkv

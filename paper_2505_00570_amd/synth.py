@@ -8,6 +8,7 @@ Sec. 4.1, so that the HIP path and the CPU oracle can be fed identical bits.
       angle p * base**(-2i/d) at absolute position p, 4 outlier channels per head scaled x8.
   V : AR(1) per channel (rho 0.8).
   tiny : AR(1) rho 0.95 plus N(0, 0.1^2) noise, fp32.
+  q : decode queries, i.i.d. N(0, 0.5^2) (attention logits of a few units, as in trained models).
 
 AR(1): a_0 = e_0 / sqrt(1 - rho^2), a_t = rho a_{t-1} + e_t, e ~ N(0, 1); the state is carried
 across chunks so a stream of chunks is one long stationary sequence.
@@ -35,6 +36,11 @@ class Workload:
     rope_base: float = 10000.0
     rho_k: float = 0.9
     rho_v: float = 0.8
+    n_q_heads: int = 0    # query heads (0: same as n_heads, i.e. multi-head attention)
+
+    @property
+    def q_heads(self) -> int:
+        return self.n_q_heads or self.n_heads
 
 
 WORKLOADS = {
@@ -43,7 +49,7 @@ WORKLOADS = {
     "llama2_7b_layer": Workload("llama2_7b_layer", 1, 1, 32, 128, 4096, 4, 0.5, torch.bfloat16, 4096),
     "llama2_7b_32k": Workload("llama2_7b_32k", 32, 1, 32, 128, 4096, 4, 0.5, torch.bfloat16, 32768),
     "llama3_8b_128k": Workload("llama3_8b_128k", 32, 1, 8, 128, 8192, 4, 0.5, torch.bfloat16, 131072,
-                               rope_base=500000.0),
+                               rope_base=500000.0, n_q_heads=32),
     "decode_b8_256k": Workload("decode_b8_256k", 32, 8, 32, 128, 4096, 4, 0.5, torch.bfloat16, 262144),
 }
 
@@ -138,6 +144,14 @@ class KVSource:
             k_out[sl, :, :, row0:row0 + T, :] = k.to(k_out.dtype)
             v_out[sl, :, :, row0:row0 + T, :] = v.to(v_out.dtype)
         self.pos += T
+
+
+def queries(wl: Workload, seed: int, device, scale: float = 0.5) -> torch.Tensor:
+    """Seeded decode queries [L, B, Hq, d] ~ N(0, scale^2) in the workload's dtype (un-rotated)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed * 2654435761 % (1 << 31) + 17)
+    q = torch.randn(wl.n_layers, wl.batch, wl.q_heads, wl.head_dim, generator=g) * scale
+    return q.to(wl.dtype).to(device)
 
 
 def empty_cache(wl: Workload, device, capacity: int | None = None):
