@@ -110,7 +110,7 @@ typedef struct freqkv_profile {
     double  ms_prepare;
     double  ms_contract;
     double  ms_tail;
-    int64_t launches_attend;    /* freqkv_attend_decode passes (both kernels of a pass as one span) */
+    int64_t launches_attend;    /* freqkv_attend_decode passes: the row-chunk kernel of each (the merge kernel is not timed) */
     double  ms_attend;
 } freqkv_profile_t;
 

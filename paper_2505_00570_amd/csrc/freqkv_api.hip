@@ -189,6 +189,8 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
 }
 
 // ---------------------------------------------------------------- attention: shape, plan, rotary table
+constexpr long long kAttendTargetWgs = 768;   // 256 compute units x 3 resident workgroups
+
 struct AttShape {
     int d, n_q, n_kv, G, GT, batch, n_layers, cur_len, elem;
     int n_split, chunk;
@@ -221,16 +223,14 @@ freqkv_status_t check_attend(const freqkv_layout_t* L, int n_q, int n_kv, int d,
     a.batch = L->batch; a.n_layers = L->n_layers; a.cur_len = cur_len;
     a.elem = L->dtype == FREQKV_BF16 ? 2 : 4;
     a.units_all = units;
-    // Row chunks: enough workgroups for two rounds over 256 compute units at two workgroups each, chunks
-    // no shorter than four loop steps and no longer than 64 rows per lane group (bounds the drift of the
-    // cos/sin recurrence and the share of the per-workgroup set-up).
+    // Row chunks: a chunk is at least eight loop steps long; the number of chunks is chosen so that the
+    // workgroups fill the resident slots of the 256 compute units about once (few, long workgroups: the
+    // set-up and the final combination of a workgroup cost several microseconds).
     const int step = attend_row_step(d);
     const long long wgs_per_split = units * (a.G / a.GT);
-    long long ns = (1024 + wgs_per_split - 1) / wgs_per_split;
-    long long ns_max = cur_len / (8 * step);
-    long long ns_min = ((long long)cur_len + 64 * step - 1) / (64 * step);
+    long long ns = (kAttendTargetWgs + wgs_per_split / 2) / wgs_per_split;
+    long long ns_max = cur_len / (16 * step);
     if (ns > ns_max) ns = ns_max;
-    if (ns < ns_min) ns = ns_min;
     if (ns < 1) ns = 1;
     long long chunk = round_up(((long long)cur_len + ns - 1) / ns, 2 * step);
     ns = ((long long)cur_len + chunk - 1) / chunk;
@@ -541,7 +541,7 @@ freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v
         for (int i = 0; i < 2 * layers; ++i) tab.base[i] = bases[(size_t)2 * l0 + i];
         AttGeom g;
         memset(&g, 0, sizeof(g));
-        g.d = a.d; g.G = a.G; g.GT = a.GT; g.n_kv = a.n_kv;
+        g.d = a.d; g.G = a.G; g.GT = a.GT; g.n_kv = a.n_kv; g.P = attend_pairs_per_lane(a.d);
         g.units = layers * upl; g.units_per_layer = upl;
         g.cur_len = cur_len; g.q_pos = q_pos; g.rope = rope;
         g.n_split = a.n_split; g.chunk = a.chunk;
@@ -555,8 +555,8 @@ freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v
         ProfSpan sp;
         HIP_TRY(prof_begin(st, 3, &sp));
         HIP_TRY(launch_attend_partial(tab, g, a.elem, qp, rt, pa, pm, st));
-        HIP_TRY(launch_attend_merge(g, a.elem, pa, pm, op, lse ? lse + head0 : nullptr, st));
         HIP_TRY(prof_end(st, &sp));
+        HIP_TRY(launch_attend_merge(g, a.elem, pa, pm, op, lse ? lse + head0 : nullptr, st));
     }
     return FREQKV_OK;
 }

@@ -23,6 +23,7 @@ namespace freqkv {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -30,6 +31,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int kWaves = 4;
 constexpr int kUnroll = 2;          // rows in flight per lane group per loop step (times two: prefetch)
 constexpr float kMinusBig = -1.0e30f;
+constexpr int kReseed = 32;          // loop steps between exact recomputations of the row cos/sin
+constexpr float kSlack = 8.0f;      // log2 of the largest un-rescaled softmax weight
 
 template <int I> struct IC { static constexpr int value = I; };
 template <int N, int I = 0, class F>
@@ -41,32 +44,41 @@ __device__ __forceinline__ void static_for(F&& f)
     }
 }
 
-// ---- eight consecutive channels, as stored and as floats --------------------------------------
-template <typename T> struct Raw8;
-template <> struct Raw8<uint16_t> { u32x4 a; };                 // 8 x bf16
-template <> struct Raw8<float>    { f32x4 a, b; };              // 8 x fp32
+// ---- P consecutive channels (P = 4 or 8), as stored and as floats ---------------------------------
+template <typename T, int P> struct Raw;
+template <> struct Raw<uint16_t, 8> { u32x4 a; };
+template <> struct Raw<uint16_t, 4> { u32x2 a; };
+template <> struct Raw<float, 8>    { f32x4 a, b; };
+template <> struct Raw<float, 4>    { f32x4 a; };
 
-__device__ __forceinline__ void load8(const uint16_t* p, Raw8<uint16_t>& r) { r.a = *(const u32x4*)p; }
-__device__ __forceinline__ void load8(const float* p, Raw8<float>& r)
+__device__ __forceinline__ void load_raw(const uint16_t* p, Raw<uint16_t, 8>& r) { r.a = *(const u32x4*)p; }
+__device__ __forceinline__ void load_raw(const uint16_t* p, Raw<uint16_t, 4>& r) { r.a = *(const u32x2*)p; }
+__device__ __forceinline__ void load_raw(const float* p, Raw<float, 8>& r)
 {
     r.a = *(const f32x4*)p;
     r.b = *(const f32x4*)(p + 4);
 }
-__device__ __forceinline__ void unpack8(const Raw8<uint16_t>& r, float (&f)[8])
+__device__ __forceinline__ void load_raw(const float* p, Raw<float, 4>& r) { r.a = *(const f32x4*)p; }
+
+template <int P> __device__ __forceinline__ void unpack(const Raw<uint16_t, P>& r, float (&f)[P])
 {
-    static_for<4>([&](auto i) {
+    static_for<P / 2>([&](auto i) {
         constexpr int I = decltype(i)::value;
         f[2 * I]     = __uint_as_float(r.a[I] << 16);
         f[2 * I + 1] = __uint_as_float(r.a[I] & 0xffff0000u);
     });
 }
-__device__ __forceinline__ void unpack8(const Raw8<float>& r, float (&f)[8])
+__device__ __forceinline__ void unpack(const Raw<float, 8>& r, float (&f)[8])
 {
     static_for<4>([&](auto i) {
         constexpr int I = decltype(i)::value;
         f[I] = r.a[I];
         f[4 + I] = r.b[I];
     });
+}
+__device__ __forceinline__ void unpack(const Raw<float, 4>& r, float (&f)[4])
+{
+    static_for<4>([&](auto i) { f[decltype(i)::value] = r.a[decltype(i)::value]; });
 }
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -76,13 +88,14 @@ template <int CTRL> __device__ __forceinline__ float dpp(float x)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
 }
-// Sum over the LPR (4, 8 or 16) adjacent lanes that share a cache row; every lane gets the sum.
+// Sum over the LPR (4, 8, 16 or 32) adjacent lanes that share a cache row; every lane gets the sum.
 template <int LPR> __device__ __forceinline__ float group_sum(float x)
 {
     x += dpp<0xB1>(x);                           // quad_perm [1,0,3,2]
     x += dpp<0x4E>(x);                           // quad_perm [2,3,0,1]
     if constexpr (LPR >= 8) x += dpp<0x141>(x);  // mirror inside each half row of 8
     if constexpr (LPR >= 16) x += dpp<0x140>(x); // mirror inside the row of 16
+    if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
     return x;
 }
 
@@ -139,18 +152,20 @@ __global__ void k_rope_table(RopeEntry* rt, int d, double base, int step)
 }
 
 // T: storage type of the cache, the query and the output (uint16_t = bfloat16 bits, or float).
-// D: head_dim.  GT: query heads handled together (they share the KV head).
-template <typename T, int D, int GT>
-__global__ __launch_bounds__(kWaves * 64, sizeof(T) == 2 ? 2 : 1)
+// D: head_dim.  GT: query heads handled together (they share the KV head).  P: rotary pairs per lane
+// (the lane owns channels P*l .. P*l+P-1 and their partners D/2 + P*l ..), so D/(2P) lanes share a row.
+template <typename T, int D, int GT, int P>
+__global__ __launch_bounds__(kWaves * 64, attend_min_waves(sizeof(T), GT, P))
 void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict__ q,
                       const RopeEntry* __restrict__ rt, float* __restrict__ part_acc,
                       float* __restrict__ part_ml)
 {
-    constexpr int LPR = D / 16;            // lanes per cache row
+    constexpr int LPR = D / (2 * P);       // lanes per cache row
     constexpr int RPW = 64 / LPR;          // rows per wave per load
     constexpr int STEP = kWaves * RPW;     // rows between two consecutive rows of one lane group
     constexpr int U = kUnroll;
     constexpr int HSLOTS = kWaves * RPW / 2;
+    typedef Raw<T, P> RawT;
 
     __shared__ float red[HSLOTS * GT * D];
     __shared__ float xm[GT][kWaves];
@@ -177,77 +192,88 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     const int row_end = min(row0 + g.chunk, g.cur_len);
     const int p0 = row0 + wave * RPW + slot;           // first row of this lane group
 
-    // ---- rotary state of the 8 pairs this lane owns: pair j couples channels 8l+j and D/2+8l+j
-    float c[8], s[8], cd[8], sd[8], qc[8], qs[8];
-    static_for<8>([&](auto jj) {
-        constexpr int j = decltype(jj)::value;
-        // without the rotary embedding every angle is zero: theta = 0 and a unit step
-        RopeEntry e = rt[8 * l + j];
-        const double theta = g.rope ? e.theta : 0.0;
-        CosSin k0 = seed_sincos(theta, p0);
-        CosSin q0 = seed_sincos(theta, g.q_pos);
-        c[j] = k0.c; s[j] = k0.s;
-        qc[j] = q0.c; qs[j] = q0.s;
-        cd[j] = g.rope ? e.cd : 1.f;
-        sd[j] = g.rope ? e.sd : 0.f;
-    });
+    // ---- rotary state of the P pairs this lane owns: pair j couples channels P*l+j and D/2+P*l+j.
+    // (c, s) = cos/sin of (row position * theta_j); each processed row advances them by the fixed rotation
+    // (cd, sd) of STEP rows, and every kReseed loop steps they are recomputed exactly.
+    float c[P], s[P], cd[P], sd[P];
+    auto seed_rows = [&](int pos) {
+        static_for<P>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            RopeEntry e = rt[P * l + j];
+            CosSin k0 = seed_sincos(g.rope ? e.theta : 0.0, pos);   // no rotary embedding: every angle is zero
+            c[j] = k0.c; s[j] = k0.s;
+            cd[j] = g.rope ? e.cd : 1.f;
+            sd[j] = g.rope ? e.sd : 0.f;
+        });
+    };
+    seed_rows(p0);
 
     // ---- queries: rotated at the query's position, scaled by log2(e)/sqrt(d) so that exp is exp2
-    float ql[GT][8], qh[GT][8];
-    static_for<GT>([&](auto gg) {
-        constexpr int gi = decltype(gg)::value;
-        const T* qp = q + ((long long)unit * g.G + g0 + gi) * D;
-        Raw8<T> rl, rh;
-        load8(qp + 8 * l, rl);
-        load8(qp + D / 2 + 8 * l, rh);
-        float a[8], bb[8];
-        unpack8(rl, a);
-        unpack8(rh, bb);
-        static_for<8>([&](auto jj) {
+    float ql[GT][P], qh[GT][P];
+    {
+        float qc[P], qs[P];
+        static_for<P>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            ql[gi][j] = (a[j] * qc[j] - bb[j] * qs[j]) * g.qscale;
-            qh[gi][j] = (bb[j] * qc[j] + a[j] * qs[j]) * g.qscale;
+            CosSin q0 = seed_sincos(g.rope ? rt[P * l + j].theta : 0.0, g.q_pos);
+            qc[j] = q0.c; qs[j] = q0.s;
         });
-    });
+        static_for<GT>([&](auto gg) {
+            constexpr int gi = decltype(gg)::value;
+            const T* qp = q + ((long long)unit * g.G + g0 + gi) * D;
+            RawT rl, rh;
+            load_raw(qp + P * l, rl);
+            load_raw(qp + D / 2 + P * l, rh);
+            float a[P], bb[P];
+            unpack(rl, a);
+            unpack(rh, bb);
+            static_for<P>([&](auto jj) {
+                constexpr int j = decltype(jj)::value;
+                ql[gi][j] = (a[j] * qc[j] - bb[j] * qs[j]) * g.qscale;
+                qh[gi][j] = (bb[j] * qc[j] + a[j] * qs[j]) * g.qscale;
+            });
+        });
+    }
 
-    float m[GT], lsum[GT], acc[GT][16];
+    float m[GT], lsum[GT], acc[GT][2 * P];
     static_for<GT>([&](auto gg) {
         constexpr int gi = decltype(gg)::value;
         m[gi] = kMinusBig;
         lsum[gi] = 0.f;
-        static_for<16>([&](auto cc) { acc[gi][decltype(cc)::value] = 0.f; });
+        static_for<2 * P>([&](auto cc) { acc[gi][decltype(cc)::value] = 0.f; });
     });
 
     // ---- main loop over the rows of this lane group: p0, p0+STEP, p0+2*STEP, ...
     const int nit = (row_end - row0 + STEP * U - 1) / (STEP * U);
     const int last = g.cur_len - 1;
-    Raw8<T> kl[U], kh[U], vl[U], vh[U];
-    auto issue = [&](int it, Raw8<T> (&a)[U], Raw8<T> (&bq)[U], Raw8<T> (&cv)[U], Raw8<T> (&dv)[U]) {
+    RawT kl[U], kh[U], vl[U], vh[U];
+    auto issue = [&](int it, RawT (&a)[U], RawT (&bq)[U], RawT (&cv)[U], RawT (&dv)[U]) {
         static_for<U>([&](auto uu) {
             constexpr int u = decltype(uu)::value;
             int row = min(p0 + (it * U + u) * STEP, last);      // rows past the end re-read the last row, masked below
             const T* kp = kbase + (long long)row * g.stride_token;
             const T* vp = vbase + (long long)row * g.stride_token;
-            load8(kp + 8 * l, a[u]);
-            load8(kp + D / 2 + 8 * l, bq[u]);
-            load8(vp + 8 * l, cv[u]);
-            load8(vp + D / 2 + 8 * l, dv[u]);
+            load_raw(kp + P * l, a[u]);
+            load_raw(kp + D / 2 + P * l, bq[u]);
+            load_raw(vp + P * l, cv[u]);
+            load_raw(vp + D / 2 + P * l, dv[u]);
         });
     };
     issue(0, kl, kh, vl, vh);
     for (int it = 0; it < nit; ++it) {
-        Raw8<T> nkl[U], nkh[U], nvl[U], nvh[U];
+        // start the loads of the next step, then consume this step's rows
+        RawT nkl[U], nkh[U], nvl[U], nvh[U];
         if (it + 1 < nit) issue(it + 1, nkl, nkh, nvl, nvh);
+        if (it != 0 && (it & (kReseed - 1)) == 0) seed_rows(p0 + it * U * STEP);
 
         float sc[U][GT];
         static_for<U>([&](auto uu) {
             constexpr int u = decltype(uu)::value;
-            float a[8], bb[8];
-            unpack8(kl[u], a);
-            unpack8(kh[u], bb);
+            float a[P], bb[P];
+            unpack(kl[u], a);
+            unpack(kh[u], bb);
             float part[GT];
             static_for<GT>([&](auto gg) { part[decltype(gg)::value] = 0.f; });
-            static_for<8>([&](auto jj) {
+            static_for<P>([&](auto jj) {
                 constexpr int j = decltype(jj)::value;
                 float rl = a[j] * c[j] - bb[j] * s[j];
                 float rh = bb[j] * c[j] + a[j] * s[j];
@@ -270,28 +296,30 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
 
         static_for<GT>([&](auto gg) {
             constexpr int gi = decltype(gg)::value;
-            float mn = m[gi];
-            static_for<U>([&](auto uu) { mn = fmaxf(mn, sc[decltype(uu)::value][gi]); });
-            float f = exp2_fast(m[gi] - mn);
-            m[gi] = mn;
-            float p[U];
-            float ps = 0.f;
+            // The reference point m of the running softmax only moves when a score exceeds it by more than
+            // 2^kSlack; until then weights up to 2^kSlack are accumulated as they are (any reference point
+            // gives the same quotient), and the rescaling of the accumulators is skipped for the whole wave.
+            float mx = sc[0][gi];
+            static_for<U>([&](auto uu) { mx = fmaxf(mx, sc[decltype(uu)::value][gi]); });
+            const bool grow = mx > m[gi] + kSlack;
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                float mn = grow ? mx : m[gi];
+                float f = exp2_fast(m[gi] - mn);
+                m[gi] = mn;
+                lsum[gi] *= f;
+                static_for<2 * P>([&](auto cc) { acc[gi][decltype(cc)::value] *= f; });
+            }
             static_for<U>([&](auto uu) {
                 constexpr int u = decltype(uu)::value;
-                p[u] = exp2_fast(sc[u][gi] - mn);
-                ps += p[u];
-            });
-            lsum[gi] = lsum[gi] * f + ps;
-            static_for<16>([&](auto cc) { acc[gi][decltype(cc)::value] *= f; });
-            static_for<U>([&](auto uu) {
-                constexpr int u = decltype(uu)::value;
-                float a[8], bb[8];
-                unpack8(vl[u], a);
-                unpack8(vh[u], bb);
-                static_for<8>([&](auto jj) {
+                float pw = exp2_fast(sc[u][gi] - m[gi]);
+                lsum[gi] += pw;
+                float va[P], vb[P];
+                unpack(vl[u], va);
+                unpack(vh[u], vb);
+                static_for<P>([&](auto jj) {
                     constexpr int j = decltype(jj)::value;
-                    acc[gi][j] = fmaf(p[u], a[j], acc[gi][j]);
-                    acc[gi][8 + j] = fmaf(p[u], bb[j], acc[gi][8 + j]);
+                    acc[gi][j] = fmaf(pw, va[j], acc[gi][j]);
+                    acc[gi][P + j] = fmaf(pw, vb[j], acc[gi][P + j]);
                 });
             });
         });
@@ -320,7 +348,7 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
         for (int o = LPR; o < 64; o <<= 1) ls += __shfl_xor(ls, o);
         if (lane == 0) xl[gi][wave] = ls;
         // rescale, fold the neighbouring lane group in, park the even groups' sums in LDS
-        static_for<16>([&](auto cc) {
+        static_for<2 * P>([&](auto cc) {
             constexpr int ci = decltype(cc)::value;
             float v = acc[gi][ci] * f;
             v += __shfl_xor(v, LPR);
@@ -328,10 +356,12 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
         });
         if ((slot & 1) == 0) {
             float* dst = red + ((wave * (RPW / 2) + (slot >> 1)) * GT + gi) * D;
-            *(f32x4*)(dst + 8 * l)             = f32x4{acc[gi][0], acc[gi][1], acc[gi][2], acc[gi][3]};
-            *(f32x4*)(dst + 8 * l + 4)         = f32x4{acc[gi][4], acc[gi][5], acc[gi][6], acc[gi][7]};
-            *(f32x4*)(dst + D / 2 + 8 * l)     = f32x4{acc[gi][8], acc[gi][9], acc[gi][10], acc[gi][11]};
-            *(f32x4*)(dst + D / 2 + 8 * l + 4) = f32x4{acc[gi][12], acc[gi][13], acc[gi][14], acc[gi][15]};
+            static_for<P / 4>([&](auto qq) {
+                constexpr int o = 4 * decltype(qq)::value;
+                *(f32x4*)(dst + P * l + o) = f32x4{acc[gi][o], acc[gi][o + 1], acc[gi][o + 2], acc[gi][o + 3]};
+                *(f32x4*)(dst + D / 2 + P * l + o) =
+                    f32x4{acc[gi][P + o], acc[gi][P + o + 1], acc[gi][P + o + 2], acc[gi][P + o + 3]};
+            });
         }
     });
     __syncthreads();
@@ -394,16 +424,16 @@ hipError_t launch_rope_table(RopeEntry* rt, int d, double base, hipStream_t st)
     return hipGetLastError();
 }
 
-template <typename T, int D>
-static hipError_t launch_partial_d(const SlabTable& tab, const AttGeom& g, const void* q, const RopeEntry* rt,
+template <typename T, int D, int P>
+static hipError_t launch_partial_p(const SlabTable& tab, const AttGeom& g, const void* q, const RopeEntry* rt,
                                    float* part_acc, float* part_ml, hipStream_t st)
 {
     dim3 grid((unsigned)(g.units * g.n_split), (unsigned)(g.G / g.GT));
     dim3 block(kWaves * 64);
     switch (g.GT) {
-        case 4: hipLaunchKernelGGL((k_attend_partial<T, D, 4>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
-        case 2: hipLaunchKernelGGL((k_attend_partial<T, D, 2>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
-        case 1: hipLaunchKernelGGL((k_attend_partial<T, D, 1>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
+        case 4: hipLaunchKernelGGL((k_attend_partial<T, D, 4, P>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
+        case 2: hipLaunchKernelGGL((k_attend_partial<T, D, 2, P>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
+        case 1: hipLaunchKernelGGL((k_attend_partial<T, D, 1, P>), grid, block, 0, st, tab, g, (const T*)q, rt, part_acc, part_ml); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -413,10 +443,11 @@ template <typename T>
 static hipError_t launch_partial_t(const SlabTable& tab, const AttGeom& g, const void* q, const RopeEntry* rt,
                                    float* part_acc, float* part_ml, hipStream_t st)
 {
+    if (g.P != attend_pairs_per_lane(g.d)) return hipErrorInvalidValue;
     switch (g.d) {
-        case 64:  return launch_partial_d<T, 64>(tab, g, q, rt, part_acc, part_ml, st);
-        case 128: return launch_partial_d<T, 128>(tab, g, q, rt, part_acc, part_ml, st);
-        case 256: return launch_partial_d<T, 256>(tab, g, q, rt, part_acc, part_ml, st);
+        case 64:  return launch_partial_p<T, 64, attend_pairs_per_lane(64)>(tab, g, q, rt, part_acc, part_ml, st);
+        case 128: return launch_partial_p<T, 128, attend_pairs_per_lane(128)>(tab, g, q, rt, part_acc, part_ml, st);
+        case 256: return launch_partial_p<T, 256, attend_pairs_per_lane(256)>(tab, g, q, rt, part_acc, part_ml, st);
         default:  return hipErrorInvalidValue;
     }
 }
@@ -428,6 +459,7 @@ hipError_t launch_attend_partial(const SlabTable& tab, const AttGeom& g, int ele
     if ((long long)(g.n_split - 1) * g.chunk >= g.cur_len) return hipErrorInvalidValue;   // no empty chunk
     if ((long long)g.n_split * g.chunk < g.cur_len) return hipErrorInvalidValue;          // chunks cover the cache
     if (g.G % g.GT) return hipErrorInvalidValue;
+    if (g.chunk % (kUnroll * attend_row_step(g.d))) return hipErrorInvalidValue;
     return elem_bytes == 2 ? launch_partial_t<uint16_t>(tab, g, q, rt, part_acc, part_ml, st)
                            : launch_partial_t<float>(tab, g, q, rt, part_acc, part_ml, st);
 }

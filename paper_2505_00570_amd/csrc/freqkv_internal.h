@@ -79,6 +79,7 @@ struct AttGeom {
     int units_per_layer;   // batch * n_kv
     int cur_len;           // cached rows, >= 1
     int q_pos;             // in-cache position of the query
+    int P;                 // rotary pairs per lane, attend_pairs_per_lane(d)
     int rope;              // 1: rotate query and keys at read time, 0: plain dot products
     int n_split;           // row chunks per unit
     int chunk;             // rows per chunk, a multiple of 2 * attend_row_step(d)
@@ -92,8 +93,12 @@ struct RopeEntry {
     float cd, sd;
 };
 
-// Rows between two consecutive rows handled by one lane group of the attention kernel.
-inline int attend_row_step(int d) { return 4096 / d; }
+// Rotary pairs (and twice as many channels) one lane of the attention kernel owns.
+constexpr int attend_pairs_per_lane(int d) { return d > 256 ? 8 : 4; }
+// Rows between two consecutive rows handled by one lane group: 4 waves x 64 lanes / (lanes per row).
+constexpr int attend_row_step(int d) { return 4 * 64 / (d / (2 * attend_pairs_per_lane(d))); }
+// Waves per SIMD the compiler must leave room for (bounds the registers of a lane).
+constexpr int attend_min_waves(int elem_bytes, int GT, int P) { return elem_bytes == 2 ? (P == 4 ? (GT == 4 ? 3 : 4) : 2) : (P == 4 ? 2 : 1); }
 
 hipError_t launch_rope_table(RopeEntry* rt, int d, double base, hipStream_t st);
 // tab.base[2*i] / [2*i+1]: K / V slab of the pass's i-th layer.  part_acc: [units*G][n_split][d] fp32,

@@ -187,3 +187,66 @@ def test_plan_dropping_variant_needs_no_workspace():
     assert (p.retained_len, p.new_len) == (4094, 4098)
     assert p.workspace_bytes == 0 and p.workspace_min_bytes == 0 and p.basis_bytes == 0 and p.flops_executed == 0
     assert p.bytes_algorithmic == pytest.approx(2 * 4094 * 128 * 2 * 512)
+
+
+# ---------------------------------------------------------------- attention plan (host arithmetic only)
+
+def test_attend_plan_llama3_shape():
+    L = _layout()                                     # 32 layers x 8 KV heads x 8192 rows x 128, bf16
+    rc, p = fk.attend_plan(L, 32, 8, 128, 8192)
+    assert rc == 0
+    assert p.heads_together == 4
+    assert p.n_split >= 1 and p.chunk_rows % 32 == 0
+    assert (p.n_split - 1) * p.chunk_rows < 8192 <= p.n_split * p.chunk_rows
+    units = 32 * 8
+    # K and V rows read once (bf16) plus the query read and the output written
+    assert p.bytes_algorithmic == units * (2.0 * 8192 * 128 * 2 + 2.0 * 4 * 128 * 2)
+    assert p.flops == units * 4 * 4.0 * 8192 * 128
+    need = units * 4 * p.n_split * (128 + 2) * 4
+    assert need <= p.workspace_bytes <= need + 256
+
+
+@pytest.mark.parametrize("hq,hkv,gt", [(32, 32, 1), (8, 4, 2), (12, 4, 1), (24, 4, 2), (64, 8, 4)])
+def test_attend_plan_head_grouping(hq, hkv, gt):
+    L = _layout(n_heads=hkv, n_layers=2, cap=1024)
+    _, p = fk.attend_plan(L, hq, hkv, 128, 1000)
+    assert p.heads_together == gt
+    assert (p.n_split - 1) * p.chunk_rows < 1000 <= p.n_split * p.chunk_rows
+
+
+@pytest.mark.parametrize("cur", [1, 2, 15, 16, 17, 255, 256, 257, 8191])
+def test_attend_plan_chunks_cover_any_length(cur):
+    L = _layout(n_layers=1, n_heads=1, cap=8192)
+    for d in (64, 128, 256):
+        L.stride_token = d
+        _, p = fk.attend_plan(L, 4, 1, d, cur)
+        assert p.n_split >= 1
+        assert (p.n_split - 1) * p.chunk_rows < cur <= p.n_split * p.chunk_rows
+
+
+def test_attend_plan_invalid_arguments():
+    L = _layout(n_layers=1, n_heads=2, cap=128)
+    out = binding.AttendPlan()
+    lib = fk.load()
+    call = lambda *a: lib.freqkv_attend_plan(C.byref(L), *a, C.byref(out))
+    assert call(4, 2, 128, 100) == 0
+    assert call(5, 2, 128, 100) == -1           # query heads not a multiple of KV heads
+    assert call(4, 0, 128, 100) == -1
+    assert call(4, 2, 128, 0) == -1             # empty cache
+    assert call(4, 2, 128, 129) == -1           # beyond the capacity
+    assert call(4, 2, 96, 100) == -2            # head_dim not 64/128/256
+    assert call(4, 2, 4, 100) == -1
+    assert lib.freqkv_attend_plan(None, 4, 2, 128, 100, C.byref(out)) == -1
+    assert lib.freqkv_attend_plan(C.byref(L), 4, 2, 128, 100, None) == -1
+
+
+def test_attend_decode_validates_without_gpu():
+    """Argument errors are reported before any device call."""
+    L = _layout(n_layers=1, n_heads=2, cap=128)
+    lib = fk.load()
+    f = lib.freqkv_attend_decode
+    assert f(None, None, None, None, None, C.byref(L), 4, 2, 128, 100, -1, 10000.0, None) == -1
+    assert f(16, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -2, 10000.0, None) == -1       # q_pos
+    assert f(16, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, -5.0, None) == -1          # rotary base
+    assert f(16, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, 10000.0, None) == -3       # no workspace
+    assert f(24, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, 10000.0, None) == -1       # q misaligned
