@@ -25,6 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes (read + write) of one contraction launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # what the same counters read for the library's plain copy kernel (profiles/contract_llama3_8b_128k_pmc.txt).
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
+# the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
+ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
 
 
 def cpu_baseline(wl, k_cache, cores):
@@ -125,8 +127,8 @@ def bench_attend(args, wl, dev):
         "ms_partial_kernel": ms_kernel,
         "measured_copy_gbs": copy_gbs,
         "roofline": {"bound": "hbm", "kernel": "k_attend_partial", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "ms_per_launch": ms_kernel,
-                     "bytes_per_launch": bytes_launch, "measured_copy_gbs": copy_gbs,
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": ATTEND_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                     "ms_per_launch": ms_kernel, "bytes_per_launch": bytes_launch, "measured_copy_gbs": copy_gbs,
                      "frac_of_measured_copy": gbs / copy_gbs},
         "cpu_baseline": cpu,
     }
