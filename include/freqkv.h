@@ -198,6 +198,21 @@ FREQKV_API freqkv_status_t freqkv_attend_decode(const void* q, const void* k, co
                                      int n_kv_heads, int head_dim, int cur_len, int q_pos,
                                      double rope_base, void* stream);
 
+/*
+ * The same attention for a batch whose sequences hold different numbers of cached rows (a serving batch:
+ * Sec. 3.4's cache of each sequence fills and compacts on its own schedule).
+ *   cur_lens     DEVICE array [layout.batch] of int32: cached rows of each sequence, shared by all layers;
+ *                each value is clamped to [1, max_cur_len] on the device; the query of sequence b sits at
+ *                its last row, cur_lens[b] - 1
+ *   max_cur_len  host upper bound of the values in cur_lens, 1 <= max_cur_len <= layout.token_capacity;
+ *                sizes the launch (use it with freqkv_attend_plan for the workspace)
+ * Everything else as freqkv_attend_decode.  Rows at and beyond a sequence's cur_lens[b] are never read.
+ */
+FREQKV_API freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void* k, const void* v, void* out,
+                                            float* lse, const freqkv_layout_t* layout, int n_q_heads,
+                                            int n_kv_heads, int head_dim, const int32_t* cur_lens,
+                                            int max_cur_len, double rope_base, void* stream);
+
 /* Human-readable name of a status code (static string, host). */
 FREQKV_API const char* freqkv_status_string(freqkv_status_t status);
 

@@ -90,6 +90,10 @@ def load() -> C.CDLL:
         lib.freqkv_attend_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_attend_decode.restype = C.c_int
+        lib.freqkv_attend_decode_ragged.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
+                                                    C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_double,
+                                                    C.c_void_p]
+        lib.freqkv_attend_decode_ragged.restype = C.c_int
         lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_prepare.restype = C.c_int
         lib.freqkv_status_string.argtypes = [C.c_int]
@@ -175,6 +179,15 @@ def attend_decode(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads:
     rc = load().freqkv_attend_decode(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(out), _dev_ptr(lse),
                                      C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_pos,
                                      float(rope_base), _stream_ptr(stream))
+    return _check(rc) if check else rc
+
+
+def attend_decode_ragged(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                         cur_lens, max_cur_len: int, rope_base: float = 10000.0, stream=None, check: bool = True) -> int:
+    """freqkv_attend_decode_ragged.  cur_lens: int32 device tensor [batch]."""
+    rc = load().freqkv_attend_decode_ragged(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(out), _dev_ptr(lse),
+                                            C.byref(layout), n_q_heads, n_kv_heads, head_dim, _dev_ptr(cur_lens),
+                                            max_cur_len, float(rope_base), _stream_ptr(stream))
     return _check(rc) if check else rc
 
 

@@ -496,9 +496,10 @@ freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads,
     return FREQKV_OK;
 }
 
-freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v, void* out, float* lse,
-                                     const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
-                                     int cur_len, int q_pos, double rope_base, void* stream)
+namespace {
+freqkv_status_t attend_impl(const void* q, const void* k, const void* v, void* out, float* lse,
+                            const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
+                            int cur_len, int q_pos, const int32_t* cur_lens, double rope_base, void* stream)
 {
     g_last_error[0] = 0;
     AttShape a;
@@ -543,7 +544,7 @@ freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v
         memset(&g, 0, sizeof(g));
         g.d = a.d; g.G = a.G; g.GT = a.GT; g.n_kv = a.n_kv; g.P = attend_pairs_per_lane(a.d);
         g.units = layers * upl; g.units_per_layer = upl;
-        g.cur_len = cur_len; g.q_pos = q_pos; g.rope = rope;
+        g.cur_len = cur_len; g.q_pos = q_pos; g.cur_lens = cur_lens; g.rope = rope;
         g.n_split = a.n_split; g.chunk = a.chunk;
         g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
         g.qscale = (float)(1.4426950408889634 / std::sqrt((double)a.d));
@@ -559,6 +560,25 @@ freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v
         HIP_TRY(launch_attend_merge(g, a.elem, pa, pm, op, lse ? lse + head0 : nullptr, st));
     }
     return FREQKV_OK;
+}
+}  // namespace
+
+freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v, void* out, float* lse,
+                                     const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
+                                     int cur_len, int q_pos, double rope_base, void* stream)
+{
+    return attend_impl(q, k, v, out, lse, layout, n_q_heads, n_kv_heads, head_dim, cur_len, q_pos, nullptr,
+                       rope_base, stream);
+}
+
+freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void* k, const void* v, void* out, float* lse,
+                                            const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
+                                            int head_dim, const int32_t* cur_lens, int max_cur_len,
+                                            double rope_base, void* stream)
+{
+    if (!cur_lens || ((uintptr_t)cur_lens & 3)) return FREQKV_E_INVALID;
+    return attend_impl(q, k, v, out, lse, layout, n_q_heads, n_kv_heads, head_dim, max_cur_len, -1, cur_lens,
+                       rope_base, stream);
 }
 
 void freqkv_shutdown(void)

@@ -188,8 +188,15 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     const T* kbase = (const T*)tab.base[2 * layer] + head_off;
     const T* vbase = (const T*)tab.base[2 * layer + 1] + head_off;
 
+    // Cached rows and query position of this sequence: common to the batch, or per sequence (clamped to
+    // [1, g.cur_len] so that every address stays inside the cache whatever the device array holds).
+    int cur_len = g.cur_len, q_pos = g.q_pos;
+    if (g.cur_lens) {
+        cur_len = max(1, min(g.cur_lens[b], g.cur_len));
+        q_pos = cur_len - 1;
+    }
     const int row0 = split * g.chunk;
-    const int row_end = min(row0 + g.chunk, g.cur_len);
+    const int row_end = min(row0 + g.chunk, cur_len);   // <= row0 for a chunk beyond a short sequence: no rows
     const int p0 = row0 + wave * RPW + slot;           // first row of this lane group
 
     // ---- rotary state of the P pairs this lane owns: pair j couples channels P*l+j and D/2+P*l+j.
@@ -214,7 +221,7 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
         float qc[P], qs[P];
         static_for<P>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
-            CosSin q0 = seed_sincos(g.rope ? rt[P * l + j].theta : 0.0, g.q_pos);
+            CosSin q0 = seed_sincos(g.rope ? rt[P * l + j].theta : 0.0, q_pos);
             qc[j] = q0.c; qs[j] = q0.s;
         });
         static_for<GT>([&](auto gg) {
@@ -243,8 +250,8 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     });
 
     // ---- main loop over the rows of this lane group: p0, p0+STEP, p0+2*STEP, ...
-    const int nit = (row_end - row0 + STEP * U - 1) / (STEP * U);
-    const int last = g.cur_len - 1;
+    const int nit = row_end > row0 ? (row_end - row0 + STEP * U - 1) / (STEP * U) : 0;
+    const int last = cur_len - 1;
     RawT kl[U], kh[U], vl[U], vh[U];
     auto issue = [&](int it, RawT (&a)[U], RawT (&bq)[U], RawT (&cv)[U], RawT (&dv)[U]) {
         static_for<U>([&](auto uu) {
@@ -456,7 +463,7 @@ hipError_t launch_attend_partial(const SlabTable& tab, const AttGeom& g, int ele
                                  const RopeEntry* rt, float* part_acc, float* part_ml, hipStream_t st)
 {
     if (g.units < 1 || g.n_split < 1 || g.chunk < 1 || g.cur_len < 1) return hipErrorInvalidValue;
-    if ((long long)(g.n_split - 1) * g.chunk >= g.cur_len) return hipErrorInvalidValue;   // no empty chunk
+    if ((long long)(g.n_split - 1) * g.chunk >= g.cur_len) return hipErrorInvalidValue;   // no chunk beyond the longest cache
     if ((long long)g.n_split * g.chunk < g.cur_len) return hipErrorInvalidValue;          // chunks cover the cache
     if (g.G % g.GT) return hipErrorInvalidValue;
     if (g.chunk % (kUnroll * attend_row_step(g.d))) return hipErrorInvalidValue;

@@ -77,8 +77,9 @@ struct AttGeom {
     int n_kv;              // KV heads
     int units;             // layers in this pass * batch * n_kv
     int units_per_layer;   // batch * n_kv
-    int cur_len;           // cached rows, >= 1
-    int q_pos;             // in-cache position of the query
+    int cur_len;           // cached rows, >= 1 (with cur_lens: the longest sequence's, an upper bound)
+    int q_pos;             // in-cache position of the query (with cur_lens: each sequence's last row)
+    const int* cur_lens;   // optional device array [batch] of per-sequence cached rows, or null
     int P;                 // rotary pairs per lane, attend_pairs_per_lane(d)
     int rope;              // 1: rotate query and keys at read time, 0: plain dot products
     int n_split;           // row chunks per unit

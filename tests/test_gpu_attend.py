@@ -227,3 +227,83 @@ def test_compress_then_attend():
         worst = max(worst, float(np.abs(got - ref).max()) / rms)
     _say(f"compress->attend vs all-fp64 path: max err / rms = {worst:.3e}")
     assert worst < 5e-2
+
+
+# ---------------------------------------------------------------- batches of unequal cache lengths
+
+def _run_ragged(q, k, v, wl, lens, max_len=None):
+    L = binding.layout_for(k)
+    max_len = max_len or max(lens)
+    _, p = fk.attend_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, max_len)
+    ws = torch.empty(max(p.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full(q.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    cl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    fk.attend_decode_ragged(q, k, v, out, lse, L, wl.q_heads, wl.n_heads, wl.head_dim, cl, max_len, wl.rope_base)
+    torch.cuda.synchronize()
+    return out, lse, p
+
+
+@pytest.mark.parametrize("lens", [[1, 37, 300, 512], [512, 512, 512, 512], [64, 1, 2, 33], [500, 17, 499, 256]])
+def test_ragged_batch(lens):
+    wl = _wl(hkv=2, hq=8, layers=2, batch=4, cap=512)
+    _say(f"attend ragged lens={lens}")
+    k, v = synth.empty_cache(wl, DEV, 512)
+    synth.KVSource(wl, 31, DEV).fill(k, v, 0, 512)
+    for b, n in enumerate(lens):                   # rows a sequence does not hold must not matter
+        k[:, b, :, n:] = float("nan")
+        v[:, b, :, n:] = float("nan")
+    q = synth.queries(wl, 31, DEV)
+    out, lse, p = _run_ragged(q, k, v, wl, lens)
+    for b, n in enumerate(lens):
+        sub = synth.small(wl, batch=1)
+        _check(q[:, b:b + 1], k[:, b:b + 1], v[:, b:b + 1], out[:, b:b + 1], lse[:, b:b + 1], sub, n)
+    if len(set(lens)) == 1:                        # equal lengths: the same bits as the uniform entry point
+        k2, v2 = k.clone(), v.clone()
+        ref, rlse, _ = _run(q, k2, v2, wl, lens[0])
+        assert torch.equal(ref, out) and torch.equal(rlse, lse)
+
+
+def test_ragged_long_and_short_with_many_chunks():
+    wl = _wl(hkv=2, hq=8, layers=1, batch=3, cap=4096, base=500000.0)
+    lens = [4096, 5, 1700]
+    k, v = synth.empty_cache(wl, DEV, 4096)
+    synth.KVSource(wl, 41, DEV).fill(k, v, 0, 4096)
+    for b, n in enumerate(lens):
+        k[:, b, :, n:] = float("nan")
+        v[:, b, :, n:] = float("nan")
+    q = synth.queries(wl, 41, DEV)
+    out, lse, p = _run_ragged(q, k, v, wl, lens)
+    assert p.n_split > 1                           # the short sequences leave whole chunks empty
+    for b, n in enumerate(lens):
+        sub = synth.small(wl, batch=1)
+        _check(q[:, b:b + 1], k[:, b:b + 1], v[:, b:b + 1], out[:, b:b + 1], lse[:, b:b + 1], sub, n)
+
+
+def test_ragged_lengths_are_clamped_on_the_device():
+    """Values outside [1, max_cur_len] in the device array cannot make the kernel leave the cache."""
+    wl = _wl(hkv=1, hq=4, layers=1, batch=3, cap=128)
+    k, v = synth.empty_cache(wl, DEV, 128)
+    synth.KVSource(wl, 43, DEV).fill(k, v, 0, 128)
+    q = synth.queries(wl, 43, DEV)
+    out, lse, _ = _run_ragged(q, k, v, wl, [0, -7, 10 ** 6], max_len=100)
+    ref, rlse, _ = _run_ragged(q, k, v, wl, [1, 1, 100], max_len=100)
+    assert torch.equal(out, ref) and torch.equal(lse, rlse)
+
+
+def test_ragged_errors():
+    wl = _wl(hkv=1, hq=4, layers=1, batch=2, cap=128)
+    q, k, v = _mk(wl, 128, seed=2)
+    L = binding.layout_for(k)
+    _, p = fk.attend_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, 128)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    out = torch.full_like(q, 5.0)
+    cl = torch.tensor([3, 4], dtype=torch.int32, device=DEV)
+    f = fk.attend_decode_ragged
+    assert f(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, None, 128, check=False) == -1
+    assert f(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, cl, 0, check=False) == -1
+    assert f(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, cl, 129, check=False) == -1
+    torch.cuda.synchronize()
+    assert bool((out == 5.0).all())
