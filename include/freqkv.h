@@ -158,6 +158,22 @@ FREQKV_API freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout
                                 double retain_ratio, void* stream);
 
 /*
+ * The same trigger for a batch whose sequences hold different numbers of tokens (each sequence's cache
+ * fills and compacts on its own schedule, Sec. 3.4): sequence b is compressed iff cur_lens[b] >= window,
+ * exactly as freqkv_compress would with cur_len = cur_lens[b]; the others are not touched.
+ *   cur_lens  HOST array [layout.batch] of int32, each 0 <= cur_lens[b] <= layout.token_capacity
+ *   new_lens  optional HOST array [layout.batch] (may be NULL, may alias cur_lens): cache length of every
+ *             sequence after the call
+ * Neighbouring sequences with equal cur_lens share one launch sequence; layout.tap_f32 is ignored.
+ * Returns FREQKV_OK if any sequence was compressed, FREQKV_NOOP if none, or a negative status (checked
+ * for every sequence before anything is enqueued: no device memory written).
+ */
+FREQKV_API freqkv_status_t freqkv_compress_ragged(void* k, void* v, const freqkv_layout_t* layout,
+                                       int n_heads, int head_dim, const int32_t* cur_lens /* host */,
+                                       int32_t* new_lens /* host */, int window, int n_sink,
+                                       double retain_ratio, void* stream);
+
+/*
  * Build and cache the basis table for (window - n_sink, retain_ratio, dtype, flags) on the current
  * device ahead of the first trigger (Appendix A cosine bases fused into one operator).  Optional.
  */

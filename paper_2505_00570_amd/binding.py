@@ -94,6 +94,9 @@ def load() -> C.CDLL:
                                                     C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_double,
                                                     C.c_void_p]
         lib.freqkv_attend_decode_ragged.restype = C.c_int
+        lib.freqkv_compress_ragged.argtypes = [C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.POINTER(C.c_int32),
+                                               C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_double, C.c_void_p]
+        lib.freqkv_compress_ragged.restype = C.c_int
         lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_prepare.restype = C.c_int
         lib.freqkv_status_string.argtypes = [C.c_int]
@@ -189,6 +192,19 @@ def attend_decode_ragged(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv
                                             C.byref(layout), n_q_heads, n_kv_heads, head_dim, _dev_ptr(cur_lens),
                                             max_cur_len, float(rope_base), _stream_ptr(stream))
     return _check(rc) if check else rc
+
+
+def compress_ragged(k, v, layout: Layout, n_heads: int, head_dim: int, cur_lens, window: int, n_sink: int,
+                    retain_ratio: float, stream=None, check: bool = True):
+    """freqkv_compress_ragged.  cur_lens: sequence of ints (host).  Returns (status, new_lens list)."""
+    n = len(cur_lens)
+    cl = (C.c_int32 * n)(*[int(c) for c in cur_lens])
+    nl = (C.c_int32 * n)()
+    rc = load().freqkv_compress_ragged(_dev_ptr(k), _dev_ptr(v), C.byref(layout), n_heads, head_dim, cl, nl,
+                                       window, n_sink, float(retain_ratio), _stream_ptr(stream))
+    if check:
+        _check(rc)
+    return rc, list(nl)
 
 
 def profile_enable(on: bool) -> None:

@@ -375,31 +375,32 @@ freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink
     return get_basis(sh, g, !(flags & FREQKV_FLAG_NO_RESCALE), (hipStream_t)stream, &basis);
 }
 
-freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
-                                int cur_len, int window, int n_sink, double retain_ratio, void* stream)
-{
-    g_last_error[0] = 0;
-    Shape sh;
-    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, cur_len, window, n_sink, retain_ratio, &sh);
-    if (rc < 0) return rc;
-    if (!k || !v) return FREQKV_E_INVALID;
-    const freqkv_layout_t& L = *layout;
+namespace {
 
-    // per-slab base pointers in the caller's [K|V][layer] order
-    std::vector<char*> bases((size_t)sh.nslabs);
+// Base pointers of every (K|V, layer) slab in [K|V][layer] order, each moved forward by `batch0` sequences.
+freqkv_status_t resolve_bases(void* k, void* v, const freqkv_layout_t& L, const Shape& sh, int batch0,
+                              std::vector<char*>* out)
+{
+    out->assign((size_t)sh.nslabs, nullptr);
     for (int kv = 0; kv < 2; ++kv) {
         void* root = kv ? v : k;
         for (int l = 0; l < sh.n_layers; ++l) {
             char* p = L.pointer_table ? (char*)((void* const*)root)[l]
                                       : (char*)root + (long long)l * L.stride_layer * sh.elem;
             if (!p || ((uintptr_t)p & 15)) return FREQKV_E_INVALID;
-            bases[(size_t)kv * sh.n_layers + l] = p;
+            (*out)[(size_t)kv * sh.n_layers + l] = p + (long long)batch0 * L.stride_batch * sh.elem;
         }
     }
-    if (cur_len < window) return FREQKV_NOOP;
+    return FREQKV_OK;
+}
+
+// One trigger over sh.batch sequences that share cur_len; `bases` already point at the first of them.
+freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_layout_t& L, const Shape& sh,
+                                  float* tap, hipStream_t st)
+{
+    if (sh.cur_len < sh.W) return FREQKV_NOOP;
     if (sh.variant == kNone) return FREQKV_OK;                // retain_ratio == 1: identity
 
-    hipStream_t st = (hipStream_t)stream;
     if (sh.variant == kDrop) {
         // Dropping: rows [W-Lc, W) -> [S, S+Lc), then the tail -> [S+Lc, ...); both in chunks of at most
         // (n - Lc) rows, the distance of the move, so that no chunk overlaps its own source.
@@ -435,7 +436,7 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
     void* basis = nullptr;
     {
         Geom g0 = make_geom(sh, L, per_pass, 0);
-        rc = get_basis(sh, g0, rescale, st, &basis);
+        freqkv_status_t rc = get_basis(sh, g0, rescale, st, &basis);
         if (rc < 0) return rc;
     }
     if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
@@ -467,7 +468,6 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
         }
 
         // 3. contraction, written straight into rows [S, S+Lc)
-        float* tap = L.tap_f32;
         HIP_TRY(prof_begin(st, 1, &sp));
         if (sh.variant == kF32)
             HIP_TRY(launch_contract_f32(tab, g, (const float*)basis, (const float*)L.workspace, tap, st));
@@ -476,6 +476,73 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
         HIP_TRY(prof_end(st, &sp));
     }
     return FREQKV_OK;
+}
+
+}  // namespace
+
+freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
+                                int cur_len, int window, int n_sink, double retain_ratio, void* stream)
+{
+    g_last_error[0] = 0;
+    Shape sh;
+    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, cur_len, window, n_sink, retain_ratio, &sh);
+    if (rc < 0) return rc;
+    if (!k || !v) return FREQKV_E_INVALID;
+    std::vector<char*> bases;
+    rc = resolve_bases(k, v, *layout, sh, 0, &bases);
+    if (rc < 0) return rc;
+    return compress_resolved(bases, *layout, sh, layout->tap_f32, (hipStream_t)stream);
+}
+
+freqkv_status_t freqkv_compress_ragged(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
+                                       const int32_t* cur_lens, int32_t* new_lens, int window, int n_sink,
+                                       double retain_ratio, void* stream)
+{
+    g_last_error[0] = 0;
+    if (!layout || !cur_lens || !k || !v) return FREQKV_E_INVALID;
+    const int batch = layout->batch;
+    if (batch < 1) return FREQKV_E_INVALID;
+    // validate every sequence before anything is enqueued
+    bool any = false;
+    for (int b = 0; b < batch; ++b) {
+        Shape sh;
+        freqkv_status_t rc = check_shape(layout, n_heads, head_dim, cur_lens[b], window, n_sink, retain_ratio, &sh);
+        if (rc < 0) return rc;
+        if (cur_lens[b] >= window && sh.variant != kNone) {
+            any = true;
+            size_t min_ws = sh.variant == kDrop ? 0 : pass_workspace(sh, 1);
+            if (min_ws && (!layout->workspace || ((uintptr_t)layout->workspace & 255) || layout->workspace_bytes < min_ws))
+                return FREQKV_E_WORKSPACE;
+        }
+    }
+    {   // base pointers must be valid whatever the lengths are
+        Shape sh;
+        check_shape(layout, n_heads, head_dim, 0, window, n_sink, retain_ratio, &sh);
+        std::vector<char*> probe;
+        freqkv_status_t rc = resolve_bases(k, v, *layout, sh, 0, &probe);
+        if (rc < 0) return rc;
+    }
+    // maximal runs of neighbouring sequences that share cur_len >= window: one trigger per run
+    for (int b0 = 0; b0 < batch;) {
+        int b1 = b0 + 1;
+        while (b1 < batch && cur_lens[b1] == cur_lens[b0]) ++b1;
+        freqkv_layout_t Lrun = *layout;
+        Lrun.batch = b1 - b0;
+        Shape sh;
+        check_shape(&Lrun, n_heads, head_dim, cur_lens[b0], window, n_sink, retain_ratio, &sh);
+        if (cur_lens[b0] >= window) {
+            std::vector<char*> bases;
+            freqkv_status_t rc = resolve_bases(k, v, *layout, sh, b0, &bases);
+            if (rc < 0) return rc;
+            rc = compress_resolved(bases, Lrun, sh, nullptr, (hipStream_t)stream);
+            if (rc < 0) return rc;
+        }
+        if (new_lens)
+            for (int b = b0; b < b1; ++b)
+                new_lens[b] = cur_lens[b] >= window ? sh.S + sh.Lc + sh.tail : cur_lens[b];
+        b0 = b1;
+    }
+    return any ? FREQKV_OK : FREQKV_NOOP;
 }
 
 freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,

@@ -250,3 +250,20 @@ def test_attend_decode_validates_without_gpu():
     assert f(16, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, -5.0, None) == -1          # rotary base
     assert f(16, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, 10000.0, None) == -3       # no workspace
     assert f(24, 16, 16, 16, None, C.byref(L), 4, 2, 128, 100, -1, 10000.0, None) == -1       # q misaligned
+
+
+def test_compress_ragged_validates_without_gpu():
+    L = _layout(n_layers=1, batch=3, n_heads=2, cap=128)
+    lib = fk.load()
+    f = lib.freqkv_compress_ragged
+    lens = (C.c_int32 * 3)(10, 20, 30)
+    out = (C.c_int32 * 3)()
+    assert f(16, 16, C.byref(L), 2, 128, None, out, 64, 4, 0.5, None) == -1
+    assert f(None, 16, C.byref(L), 2, 128, lens, out, 64, 4, 0.5, None) == -1
+    assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 0.5, None) == 1          # nobody reached the window
+    assert list(out) == [10, 20, 30]
+    lens[1] = 129                                                                     # beyond the capacity
+    assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 0.5, None) == -1
+    lens[1] = 64                                                                      # triggers, but no workspace
+    assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 0.5, None) == -3
+    assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 1.5, None) == -1          # ratio

@@ -368,3 +368,93 @@ def test_dropping_variant(window, sink, ratio, extra, dtype):
                 ref = orc.drop_head(f64(before[l, 0, h]), cur, window, sink, ratio)
                 assert np.array_equal(f64(after[l, 0, h, :p.new_len]), ref)
                 assert torch.equal(after[l, 0, h, cur:], before[l, 0, h, cur:])
+
+
+# ------------------------------------------------------------------------------------------
+# batches whose sequences hold different numbers of tokens
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("lens,flags", [([300, 290, 307, 300], 0), ([300, 300, 301, 301], 0), ([10, 299, 0, 42], 0),
+                                        ([300, 290, 307, 300], fk.FLAG_DROPPING), ([340, 300, 300, 340], 0)])
+def test_ragged_batch(lens, flags):
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, batch=4, n_heads=2, window=300)
+    cap = 360
+    _say(f"ragged compress lens={lens} flags={flags}")
+    k, v = _mk(wl, seed=77, capacity=cap, cur_len=cap)
+    k0, v0 = k.clone(), v.clone()
+    L = binding.layout_for(k, flags=flags)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    ws = torch.empty(max(p.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    rc, new_lens = fk.compress_ragged(k, v, L, wl.n_heads, wl.head_dim, lens, wl.window, wl.n_sink, wl.retain_ratio)
+    torch.cuda.synchronize()
+    assert rc == (0 if any(n >= wl.window for n in lens) else 1)
+    for b, n in enumerate(lens):
+        assert new_lens[b] == (n if n < wl.window else orc.new_len(n, wl.window, wl.n_sink, wl.retain_ratio))
+        if n < wl.window:                                   # not triggered: untouched, bit for bit
+            assert torch.equal(k[:, b], k0[:, b]) and torch.equal(v[:, b], v0[:, b])
+            continue
+        # the same bits as the uniform entry point run on this sequence alone ...
+        kb, vb = k0[:, b:b + 1].clone(), v0[:, b:b + 1].clone()
+        sub = synth.small(wl, batch=1)
+        Lb = binding.layout_for(kb, flags=flags)
+        Lb.workspace, Lb.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+        fk.compress(kb, vb, Lb, wl.n_heads, wl.head_dim, n, wl.window, wl.n_sink, wl.retain_ratio)
+        torch.cuda.synchronize()
+        assert torch.equal(k[:, b, :, :new_lens[b]], kb[:, 0, :, :new_lens[b]])
+        assert torch.equal(v[:, b, :, :new_lens[b]], vb[:, 0, :, :new_lens[b]])
+        assert torch.equal(k[:, b, :, n:], k0[:, b, :, n:])  # rows beyond the old length: untouched
+        # ... and, on one head, the oracle directly
+        x = f64(k0[1, b, 1, :n].cpu())
+        if flags & fk.FLAG_DROPPING:
+            ref = orc.drop_head(x, n, wl.window, wl.n_sink, wl.retain_ratio)
+            assert np.array_equal(f64(k[1, b, 1, :new_lens[b]].cpu()), ref)
+        else:
+            ref = orc.compress_head(x, n, wl.window, wl.n_sink, wl.retain_ratio)
+            got = f64(k[1, b, 1, :new_lens[b]].cpu())
+            S, lc = wl.n_sink, p.retained_len
+            rms = math.sqrt(float((ref[S:S + lc] ** 2).mean()))
+            excess = np.abs(got[S:S + lc] - ref[S:S + lc]) - 0.5 * bf16_ulp(ref[S:S + lc])
+            assert float(excess.max()) / rms <= TOL_BF16
+            assert np.array_equal(got[:S], ref[:S]) and np.array_equal(got[S + lc:], ref[S + lc:])
+
+
+def test_ragged_batch_errors_and_pointer_table():
+    import ctypes as C
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, batch=3, n_heads=1, window=200)
+    k, v = _mk(wl, seed=5, capacity=220, cur_len=220)
+    k0 = k.clone()
+    L = binding.layout_for(k)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    # a length beyond the capacity anywhere in the batch: nothing is enqueued
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    rc, _ = fk.compress_ragged(k, v, L, wl.n_heads, wl.head_dim, [200, 200, 221], wl.window, wl.n_sink,
+                               wl.retain_ratio, check=False)
+    assert rc == -1
+    L.workspace_bytes = 0
+    rc, _ = fk.compress_ragged(k, v, L, wl.n_heads, wl.head_dim, [200, 10, 10], wl.window, wl.n_sink,
+                               wl.retain_ratio, check=False)
+    assert rc == -3
+    rc, nl = fk.compress_ragged(k, v, L, wl.n_heads, wl.head_dim, [199, 10, 10], wl.window, wl.n_sink,
+                                wl.retain_ratio, check=False)
+    assert rc == 1 and nl == [199, 10, 10]                   # nothing to do needs no workspace
+    torch.cuda.synchronize()
+    assert torch.equal(k, k0)
+    # per-layer pointer table: the runs are addressed through the table
+    L.workspace_bytes = p.workspace_bytes
+    ref_k, ref_v = k.clone(), v.clone()
+    fk.compress_ragged(ref_k, ref_v, binding.layout_for(ref_k, workspace=ws), wl.n_heads, wl.head_dim, [10, 205, 200],
+                       wl.window, wl.n_sink, wl.retain_ratio)
+    ks = [k[l].clone() for l in range(wl.n_layers)]
+    vs = [v[l].clone() for l in range(wl.n_layers)]
+    L.pointer_table = 1
+    kp = (C.c_void_p * wl.n_layers)(*[t.data_ptr() for t in ks])
+    vp = (C.c_void_p * wl.n_layers)(*[t.data_ptr() for t in vs])
+    rc, nl = fk.compress_ragged(kp, vp, L, wl.n_heads, wl.head_dim, [10, 205, 200], wl.window, wl.n_sink, wl.retain_ratio)
+    torch.cuda.synchronize()
+    assert rc == 0
+    for l in range(wl.n_layers):
+        for b in range(3):
+            assert torch.equal(ks[l][b, :, :nl[b]], ref_k[l, b, :, :nl[b]])
+            assert torch.equal(vs[l][b, :, :nl[b]], ref_v[l, b, :, :nl[b]])
