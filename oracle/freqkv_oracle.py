@@ -153,6 +153,30 @@ def compress_head(cache, cur_len: int, window: int, n_sink: int, retain_ratio: f
     return out
 
 
+def compress_span_high(x, lc: int, rescale: bool = True, return_coeffs: bool = False):
+    """The high-frequency variant of the ablation tables (Sec. 3.2 summarisation table, appendix table on
+    retaining high frequencies): the Lc HIGHEST coefficients of the n-point DCT are kept instead of the
+    lowest.  The paper does not say how the kept band becomes Lc cached rows; the reading taken is the
+    only one that reuses its inverse unchanged: the kept band, in order, is the input of the Lc-point
+    inverse DCT, with the same sqrt(Lc/n) factor:  y = sqrt(Lc/n) * IDCT_Lc(DCT_n(x)[n-Lc:n])."""
+    a = _as2d(x)
+    n = a.shape[0]
+    z = dct2(a)[n - lc:]
+    y = idct2(z)
+    if rescale:
+        y = y * math.sqrt(lc / n)
+    return (y, z) if return_coeffs else y
+
+
+def compress_head_high(cache, cur_len: int, window: int, n_sink: int, retain_ratio: float,
+                       rescale: bool = True) -> np.ndarray:
+    """compress_head with the high band retained: same sinks, retained size and tail rule (Sec. 3.4)."""
+    a = _as2d(cache)[:cur_len]
+    lc = retained_len(window - n_sink, retain_ratio)
+    y = compress_span_high(a[n_sink:window], lc, rescale)
+    return np.concatenate([a[:n_sink], y, a[window:cur_len]], axis=0)
+
+
 def drop_head(cache, cur_len: int, window: int, n_sink: int, retain_ratio: float) -> np.ndarray:
     """The "Dropping" variant (appendix on the compression overhead): no transform, the span keeps
     its Lc most recent rows; same sinks, retained size and tail rule as compress_head."""

@@ -240,3 +240,68 @@ def test_dropping_literal_example():
     assert out[:, 0].tolist() == [0, 1, 5, 6, 7, 8, 9]
     assert out[:, 1].tolist() == [0, 10, 50, 60, 70, 80, 90]
     assert out.shape[0] == orc.new_len(10, 8, 2, 0.5)
+
+
+# -- high-frequency retention (ablation tables): same transforms, the other end of the spectrum --------
+
+@pytest.mark.parametrize("n,lc,d", [(8, 4, 3), (9, 4, 2), (13, 5, 4), (64, 32, 5), (30, 7, 2), (16, 15, 1)])
+def test_high_band_bruteforce_matrices(n, lc, d):
+    x = _rng(n * 7 + lc).standard_normal((n, d))
+    Cn, Cl = _dct_matrix(n), _dct_matrix(lc)
+    z_ref = (Cn @ x)[n - lc:]
+    y, z = orc.compress_span_high(x, lc, return_coeffs=True)
+    assert np.allclose(z, z_ref, atol=1e-13)
+    assert np.allclose(y, math.sqrt(lc / n) * (Cl.T @ z_ref), atol=1e-13)
+    assert np.allclose(orc.compress_span_high(x, lc, rescale=False), Cl.T @ z_ref, atol=1e-13)
+
+
+@pytest.mark.parametrize("n,lc", [(508, 254), (120, 45)])
+def test_high_band_pure_cosine_and_parseval(n, lc):
+    j = np.arange(n)
+    m = np.arange(lc)
+    for t0 in (0, 1, n - lc - 1, n - lc, n - lc + 1, n - 2, n - 1):
+        x = np.cos(math.pi * t0 * (2 * j + 1) / (2 * n))
+        y = orc.compress_span_high(x, lc)[:, 0]
+        if t0 >= n - lc:
+            # basis function t0 of the n-point transform lands on index t0-(n-lc) of the Lc-point inverse;
+            # index 0 of the inverse has the smaller normalisation, hence the factor sqrt(1/2) there
+            s = t0 - (n - lc)
+            expect = np.cos(math.pi * s * (2 * m + 1) / (2 * lc)) * (math.sqrt(0.5) if s == 0 else 1.0)
+        else:
+            expect = np.zeros(lc)
+        assert np.max(np.abs(y - expect)) < 1e-11, t0
+    x = _rng(5).standard_normal((n, 3))
+    z_all = orc.dct2(x)
+    y = orc.compress_span_high(x, lc)
+    assert np.allclose((y ** 2).sum(0), (lc / n) * (z_all[n - lc:] ** 2).sum(0), rtol=1e-12)
+    # the two bands of a half/half split carry the whole energy between them (Parseval)
+    if n == 2 * lc:
+        ylow = orc.compress_span(x, lc)
+        assert np.allclose((y ** 2).sum(0) + (ylow ** 2).sum(0), 0.5 * (x ** 2).sum(0), rtol=1e-12)
+
+
+def test_high_band_operator_properties_and_scipy():
+    n, lc = 96, 40
+    M = orc.compress_span_high(np.eye(n), lc)
+    assert np.allclose(M @ M.T, (lc / n) * np.eye(lc), atol=1e-12)
+    assert np.allclose(M[::-1, ::-1], (-1) ** (n - lc) * M, atol=1e-12)     # reversal symmetry up to a sign
+    n, lc = 95, 40
+    M = orc.compress_span_high(np.eye(n), lc)
+    assert np.allclose(M[::-1, ::-1], -M, atol=1e-12)
+    x = _rng(12).standard_normal((500, 4)) * 2.0
+    z = scipy.fft.dct(x, type=2, norm="ortho", axis=0)
+    ref = math.sqrt(200 / 500) * scipy.fft.idct(z[300:], type=2, norm="ortho", axis=0)
+    assert np.max(np.abs(orc.compress_span_high(x, 200) - ref)) < 1e-11
+    # a smooth sequence keeps almost nothing in the high band, an alternating one almost everything
+    smooth = np.cos(np.linspace(0, 1, 400))[:, None]
+    assert (orc.compress_span_high(smooth, 200) ** 2).sum() < 1e-6 * (smooth ** 2).sum()
+    alt = ((-1.0) ** np.arange(400))[:, None]
+    assert (orc.compress_span_high(alt, 200) ** 2).sum() > 0.49 * (alt ** 2).sum()
+
+
+def test_high_band_cache_bookkeeping():
+    cache = _rng(3).standard_normal((90, 6))
+    out = orc.compress_head_high(cache, 80, 64, 4, 0.5)
+    assert out.shape == (4 + 30 + 16, 6)
+    assert np.array_equal(out[:4], cache[:4]) and np.array_equal(out[34:], cache[64:80])
+    assert np.allclose(out[4:34], orc.compress_span_high(cache[4:64], 30), atol=0)
