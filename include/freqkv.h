@@ -54,6 +54,11 @@ typedef enum {
                                          the Lc most recent rows of the span, [window-Lc, window), move to [n_sink, n_sink+Lc);
                                          same sinks, same retained size, same tail rule; needs no workspace and no basis */
 
+#define FREQKV_FLAG_RETAIN_HIGH 0x4u  /* the high-frequency variant of the ablation tables (Sec. 3.2 summarisation
+                                         table; appendix table on retaining high frequencies): the Lc HIGHEST
+                                         coefficients of the n-point DCT are kept and handed, in order, to the
+                                         Lc-point inverse; everything else as the default.  Not with DROPPING */
+
 /*
  * Memory description of the cache ("layout"): everything the scalar arguments of
  * freqkv_compress do not say.  One head-tensor is the [token][dim] matrix of one

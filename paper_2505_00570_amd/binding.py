@@ -16,6 +16,7 @@ _lib = None
 BF16, F32 = 0, 1
 FLAG_NO_RESCALE = 0x1
 FLAG_DROPPING = 0x2
+FLAG_RETAIN_HIGH = 0x4
 
 OK, NOOP = 0, 1
 E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_HIP, E_ALLOC = -1, -2, -3, -4, -5

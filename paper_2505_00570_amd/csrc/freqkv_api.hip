@@ -45,6 +45,7 @@ int retained_len(int n, double ratio)
 struct Shape {
     int n, Lc, S, W, d, n_heads, batch, n_layers, cur_len, tail;
     int variant;
+    int high;                 // 1: FREQKV_FLAG_RETAIN_HIGH
     int elem;                 // bytes per cache element
     long long hts_per_slab;   // batch * n_heads
     int nslabs;               // 2 * n_layers
@@ -61,6 +62,7 @@ Geom make_geom(const Shape& sh, const freqkv_layout_t& L, int slabs, int slab0)
     g.ncols = (int)((long long)slabs * sh.hts_per_slab * sh.d);
     g.ncoltiles = (g.ncols + kColTile - 1) / kColTile;
     g.fold = sh.variant == kFoldF16;
+    g.high = sh.high;
     if (sh.variant == kFoldF16) {
         g.Kh = sh.n / 2; g.Mh = sh.Lc / 2;
         g.Mpad = (int)round_up(g.Mh, kRowsFold);
@@ -110,7 +112,8 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     if (cur_len < 0 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
     if (!(ratio > 0.0) || !(ratio <= 1.0)) return FREQKV_E_INVALID;      // also rejects NaN
     if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
-    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING)) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH)) return FREQKV_E_INVALID;
+    if ((L->flags & FREQKV_FLAG_DROPPING) && (L->flags & FREQKV_FLAG_RETAIN_HIGH)) return FREQKV_E_INVALID;
     if (L->stride_token < head_dim) return FREQKV_E_INVALID;
     if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
     if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;
@@ -129,6 +132,7 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     sh.elem = L->dtype == FREQKV_BF16 ? 2 : 4;
     sh.hts_per_slab = hts;
     sh.nslabs = 2 * L->n_layers;
+    sh.high = (L->flags & FREQKV_FLAG_RETAIN_HIGH) ? 1 : 0;
     if (sh.Lc == sh.n) sh.variant = kNone;
     else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
@@ -139,10 +143,11 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
 
 // ---------------------------------------------------------------- basis cache
 struct BasisKey {
-    int device, n, Lc, variant, rescale;
+    int device, n, Lc, variant, rescale, high;
     bool operator<(const BasisKey& o) const
     {
-        return std::tie(device, n, Lc, variant, rescale) < std::tie(o.device, o.n, o.Lc, o.variant, o.rescale);
+        return std::tie(device, n, Lc, variant, rescale, high) <
+               std::tie(o.device, o.n, o.Lc, o.variant, o.rescale, o.high);
     }
 };
 struct BasisEntry {
@@ -158,7 +163,7 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
 {
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
-    BasisKey key{dev, sh.n, sh.Lc, sh.variant, rescale};
+    BasisKey key{dev, sh.n, sh.Lc, sh.variant, rescale, sh.high};
     std::lock_guard<std::mutex> lock(g_mu);
     auto it = g_basis.find(key);
     if (it == g_basis.end()) {
@@ -170,7 +175,7 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
             (void)hipGetLastError();
             return FREQKV_E_ALLOC;
         }
-        if (sh.variant == kF32) err = launch_basis_f32((float*)e.ptr, sh.n, sh.Lc, rescale, st);
+        if (sh.variant == kF32) err = launch_basis_f32((float*)e.ptr, sh.n, sh.Lc, rescale, sh.high, st);
         else                    err = launch_basis_f16((_Float16*)e.ptr, g, rescale, st);
         if (err == hipSuccess) err = hipEventCreateWithFlags(&e.ready, hipEventDisableTiming);
         if (err == hipSuccess) err = hipEventRecord(e.ready, st);
@@ -208,7 +213,7 @@ freqkv_status_t check_attend(const freqkv_layout_t* L, int n_q, int n_kv, int d,
     if (d != 64 && d != 128 && d != 256) return FREQKV_E_UNSUPPORTED;
     if (cur_len < 1 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
     if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
-    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING)) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH)) return FREQKV_E_INVALID;
     if (L->stride_token < d) return FREQKV_E_INVALID;
     if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
     if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;

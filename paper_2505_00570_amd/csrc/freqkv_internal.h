@@ -31,6 +31,7 @@ struct Geom {
     int ncols;           // virtual columns in this pass = slabs * hts_per_slab * d
     int ncoltiles;       // ceil(ncols / kColTile)
     int fold;            // 1: even/odd folded operator, 0: plain
+    int high;            // 1: the Lc highest coefficients are kept (ablation variant), 0: the lowest
     int Kh;              // contraction length: n/2 (fold) or n
     int Kpad;            // Kh rounded up to kKStage
     int nkstages;        // Kpad / kKStage
@@ -48,7 +49,7 @@ enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4 };
 // G: [Kpad/8][Grows][8] fp16.  Folded: rows [0,Mpad) even part, rows [Mpad,2Mpad) odd part.
 hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t st);
 // Mf: [Lc][n] fp32 row-major.
-hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, hipStream_t st);
+hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hipStream_t st);
 
 // ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);

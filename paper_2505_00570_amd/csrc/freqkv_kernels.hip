@@ -80,13 +80,34 @@ __device__ double dirichlet_q(long long q, long long Q, long long twoLm1)
     return s_num / s_den;
 }
 
-__device__ double operator_entry(int m, int j, long long n, long long Lc, double scale)
+// sin(L*theta/2) * cos((L-1)*theta/2 + phi) / sin(theta/2) = sum_{s<L} cos(theta*s + phi), for
+// theta = pi*q/(2*n*L) and phi = pi*p2/Q with Q = 4*n*L; |q| < Q, 0 <= p2 < 2Q.
+__device__ double shifted_cos_sum(long long q, long long p2, long long Q, long long L)
+{
+    if (q == 0) return (double)L * cospi((double)p2 / (double)Q);
+    long long qq  = ((q % (2 * Q)) + 2 * Q) % (2 * Q);
+    long long num = (L * qq) % (2 * Q);
+    long long arg = ((L - 1) * qq + p2) % (2 * Q);
+    return sinpi((double)num / (double)Q) * cospi((double)arg / (double)Q) / sinpi((double)q / (double)Q);
+}
+
+// Entry (m, j) of the fused operator.  band 0: the Lc lowest coefficients are kept (Sec. 3.3).
+// band 1: the Lc highest are kept and handed, in order, to the Lc-point inverse (the high-frequency
+// ablation): M[m][j] = (2/n) * sum_{s<Lc} w_s cos(a_m s) cos(b_j (s + n - Lc)), w_0 = 1/sqrt(2), else 1.
+__device__ double operator_entry(int m, int j, long long n, long long Lc, double scale, int band)
 {
     long long Q  = 4 * n * Lc;
     long long am = (2LL * m + 1) * n;
     long long bj = (2LL * j + 1) * Lc;
-    double v = dirichlet_q(am - bj, Q, 2 * Lc - 1) + dirichlet_q(am + bj, Q, 2 * Lc - 1);
-    return v * scale / (2.0 * (double)n);
+    if (band == 0) {
+        double v = dirichlet_q(am - bj, Q, 2 * Lc - 1) + dirichlet_q(am + bj, Q, 2 * Lc - 1);
+        return v * scale / (2.0 * (double)n);
+    }
+    // phi = b_j * (n - Lc) = pi * 2*bj*(n-Lc) / Q, reduced mod 2*pi in integers
+    long long p2 = (2 * ((bj % Q) * ((n - Lc) % Q) % Q)) % (2 * Q);
+    double v = shifted_cos_sum(bj + am, p2, Q, Lc) + shifted_cos_sum(bj - am, p2, Q, Lc);
+    v -= (2.0 - 1.4142135623730951) * cospi((double)p2 / (double)Q);
+    return v * scale / (double)n;
 }
 
 // G[kg][row][8]: one thread fills one 16-byte group of 8 consecutive k.
@@ -104,9 +125,9 @@ __global__ void k_basis_f16(_Float16* __restrict__ G, Geom g, double scale)
         int j = kg * 8 + i;
         double v = 0.0;
         if (m < g.Mh && j < g.Kh) {
-            double a = operator_entry(m, j, g.n, g.Lc, scale);
+            double a = operator_entry(m, j, g.n, g.Lc, scale, g.high);
             if (g.fold) {
-                double b = operator_entry(g.Lc - 1 - m, j, g.n, g.Lc, scale);
+                double b = operator_entry(g.Lc - 1 - m, j, g.n, g.Lc, scale, g.high);
                 v = parity ? 0.5 * (a - b) : 0.5 * (a + b);
             } else {
                 v = a;
@@ -117,12 +138,12 @@ __global__ void k_basis_f16(_Float16* __restrict__ G, Geom g, double scale)
     *(half8*)(G + idx * 8) = out;
 }
 
-__global__ void k_basis_f32(float* __restrict__ Mf, int n, int Lc, double scale)
+__global__ void k_basis_f32(float* __restrict__ Mf, int n, int Lc, double scale, int band)
 {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long long)n * Lc) return;
     int m = (int)(idx / n), j = (int)(idx - (long long)m * n);
-    Mf[idx] = (float)operator_entry(m, j, n, Lc, scale);
+    Mf[idx] = (float)operator_entry(m, j, n, Lc, scale, band);
 }
 
 hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t st)
@@ -134,12 +155,12 @@ hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, hipStream_t st)
+hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hipStream_t st)
 {
     double scale = rescale ? 1.0 : sqrt((double)n / (double)Lc);
     long long total = (long long)n * Lc;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(k_basis_f32, dim3(blocks), dim3(256), 0, st, Mf, n, Lc, scale);
+    hipLaunchKernelGGL(k_basis_f32, dim3(blocks), dim3(256), 0, st, Mf, n, Lc, scale, band);
     return hipGetLastError();
 }
 

@@ -458,3 +458,65 @@ def test_ragged_batch_errors_and_pointer_table():
         for b in range(3):
             assert torch.equal(ks[l][b, :, :nl[b]], ref_k[l, b, :, :nl[b]])
             assert torch.equal(vs[l][b, :, :nl[b]], ref_v[l, b, :, :nl[b]])
+
+
+# ------------------------------------------------------------------------------------------
+# high-frequency retention (ablation variant): a different operator through the same kernels
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("window,sink,ratio,extra,dtype", [
+    (516, 4, 0.5, 0, torch.bfloat16),      # folded operator (even span, even retained length)
+    (1300, 4, 0.5, 9, torch.bfloat16),     # two row tiles, a tail
+    (701, 4, 0.5, 0, torch.bfloat16),      # odd span: plain operator, antisymmetric under reversal
+    (600, 8, 0.75, 0, torch.bfloat16),
+    (600, 2, 0.01, 0, torch.bfloat16),     # five highest coefficients
+    (512, 4, 0.5, 0, torch.float32),
+])
+def test_retain_high_variant(window, sink, ratio, extra, dtype):
+    base = synth.WORKLOADS["tiny"] if dtype == torch.float32 else synth.WORKLOADS["llama2_7b_layer"]
+    wl = synth.small(base, n_layers=1, batch=1, n_heads=2, window=window, n_sink=sink, retain_ratio=ratio)
+    cur = window + extra
+    _say(f"retain-high window={window} sink={sink} ratio={ratio} extra={extra} {dtype}")
+    k, v = _mk(wl, seed=window, capacity=cur + 3, cur_len=cur)
+    if dtype == torch.bfloat16:
+        # give the high band something to hold: the synthetic states are low-frequency dominated
+        k += (torch.randn(k.shape, device=DEV) * 2.0).to(k.dtype)
+        v += (torch.randn(v.shape, device=DEV) * 2.0).to(v.dtype)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, cur, flags=fk.FLAG_RETAIN_HIGH)
+    assert rc == 0
+    S, lc = sink, p.retained_len
+    worst = 0.0
+    for before, after, kv in ((k0, k.cpu(), 0), (v0, v.cpu(), 1)):
+        for h in range(wl.n_heads):
+            ref = orc.compress_head_high(f64(before[0, 0, h, :cur]), cur, window, sink, ratio)
+            got = after[0, 0, h]
+            assert torch.equal(got[:S], before[0, 0, h, :S])
+            assert torch.equal(got[S + lc:p.new_len], before[0, 0, h, window:cur])
+            assert torch.equal(got[cur:], before[0, 0, h, cur:])
+            yref = ref[S:S + lc]
+            yt = f64(tap[kv, 0, 0, h].cpu())
+            worst = max(worst, rel_err(yt, yref))
+            if dtype == torch.bfloat16:
+                assert np.array_equal(f64(got[S:S + lc]), bf16_round(yt))
+            else:
+                assert np.array_equal(f64(got[S:S + lc]), yt)
+    _say(f"  worst fp32-tap err/rms {worst:.3e}")
+    assert worst <= (TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
+    # the flag is part of the basis cache key: the default operator still gives its own result afterwards
+    k2, v2 = k0.to(DEV), v0.to(DEV)
+    _, _, tap_low = _run(k2, v2, wl, cur)
+    ref_low = orc.compress_head(f64(k0[0, 0, 0, :cur]), cur, window, sink, ratio)[S:S + lc]
+    assert rel_err(f64(tap_low[0, 0, 0, 0].cpu()), ref_low) <= (TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
+
+
+def test_retain_high_rejects_dropping():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=1, n_heads=1, window=100)
+    k, v = _mk(wl, seed=1)
+    k0 = k.clone()
+    L = binding.layout_for(k, flags=fk.FLAG_RETAIN_HIGH | fk.FLAG_DROPPING)
+    rc, _ = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, check=False)
+    assert rc == -1
+    rc = fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, check=False)
+    torch.cuda.synchronize()
+    assert rc == -1 and torch.equal(k, k0)
