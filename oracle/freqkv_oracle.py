@@ -177,6 +177,21 @@ def compress_head_high(cache, cur_len: int, window: int, n_sink: int, retain_rat
     return np.concatenate([a[:n_sink], y, a[window:cur_len]], axis=0)
 
 
+def power_spectrum(x) -> np.ndarray:
+    """Average power spectrum of key or value states (Sec. 3.1 and its figure; appendix on the head-wise
+    analysis): x [samples, tokens, channels] (or [tokens, channels]) is taken to the frequency domain by the
+    orthonormal DCT-II along the token axis, and the squared coefficients are averaged over samples and
+    channels.  Returns P[t], t = 0 .. tokens-1."""
+    a = np.asarray(x, dtype=np.float64)
+    if a.ndim == 2:
+        a = a[None]
+    acc = np.zeros(a.shape[1])
+    for sample in a:
+        z = dct2(sample)
+        acc += (z ** 2).sum(axis=1)
+    return acc / (a.shape[0] * a.shape[2])
+
+
 def drop_head(cache, cur_len: int, window: int, n_sink: int, retain_ratio: float) -> np.ndarray:
     """The "Dropping" variant (appendix on the compression overhead): no transform, the span keeps
     its Lc most recent rows; same sinks, retained size and tail rule as compress_head."""

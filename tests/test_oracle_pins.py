@@ -305,3 +305,51 @@ def test_high_band_cache_bookkeeping():
     assert out.shape == (4 + 30 + 16, 6)
     assert np.array_equal(out[:4], cache[:4]) and np.array_equal(out[34:], cache[64:80])
     assert np.allclose(out[4:34], orc.compress_span_high(cache[4:64], 30), atol=0)
+
+
+# -- power spectrum diagnostic (Sec. 3.1 figure; appendix on the head-wise analysis) ---------------------
+
+def test_power_spectrum_closed_forms():
+    n, d = 96, 5
+    x = _rng(1).standard_normal((3, n, d))
+    P = orc.power_spectrum(x)
+    assert P.shape == (n,)
+    # Parseval: the spectrum sums to the mean energy of a channel
+    assert math.isclose(P.sum(), (x ** 2).sum() / (3 * d), rel_tol=1e-12)
+    # explicit matrix
+    Cn = _dct_matrix(n)
+    ref = np.mean([((Cn @ x[b]) ** 2).mean(axis=1) for b in range(3)], axis=0)
+    assert np.allclose(P, ref, rtol=1e-12, atol=1e-15)
+    # a constant has only the DC line, n c^2; basis function t0 has a single line n/2 (n for t0 = 0)
+    c = np.full((n, 2), 1.5)
+    Pc = orc.power_spectrum(c)
+    assert math.isclose(Pc[0], n * 1.5 ** 2, rel_tol=1e-12) and Pc[1:].max() < 1e-20
+    j = np.arange(n)
+    for t0 in (1, 7, n - 1):
+        Pt = orc.power_spectrum(np.cos(math.pi * t0 * (2 * j + 1) / (2 * n))[:, None])
+        assert math.isclose(Pt[t0], n / 2, rel_tol=1e-12)
+        assert np.delete(Pt, t0).max() < 1e-20
+    # scipy's transform
+    assert np.allclose(P, (scipy.fft.dct(x, type=2, norm="ortho", axis=1) ** 2).mean(axis=(0, 2)), rtol=1e-11)
+
+
+def test_power_spectrum_of_white_and_ar1_sequences():
+    """White noise is flat at the variance; a stationary AR(1) sequence follows
+    sigma_e^2 / (1 - 2 rho cos(w) + rho^2), w = pi t / n (low frequencies dominate, as Sec. 3.1 reports
+    for KV states): statistical checks over many channels."""
+    rng = _rng(9)
+    n, d = 512, 2048
+    P = orc.power_spectrum(rng.standard_normal((n, d)))
+    assert abs(P.mean() - 1.0) < 0.01 and np.max(np.abs(P - 1.0)) < 0.2
+    rho = 0.9
+    e = rng.standard_normal((n, d))
+    a = np.zeros_like(e)
+    a[0] = e[0] / math.sqrt(1 - rho ** 2)
+    for t in range(1, n):
+        a[t] = rho * a[t - 1] + e[t]
+    P = orc.power_spectrum(a)
+    w = math.pi * np.arange(n) / n
+    theory = 1.0 / (1 - 2 * rho * np.cos(w) + rho ** 2)
+    rel = np.abs(P[4:] / theory[4:] - 1.0)            # the lowest few lines feel the finite length
+    assert rel.max() < 0.2 and rel.mean() < 0.04
+    assert P[: n // 2].sum() / P.sum() > 0.95          # energy kept by the lower half of the spectrum
