@@ -135,6 +135,69 @@ def bench_attend(args, wl, dev):
     print(json.dumps(out_json))
 
 
+def bench_spectrum(args, wl, dev):
+    """A step = one power-spectrum call over every layer's K and V, all `window` cached rows."""
+    import torch
+    import paper_2505_00570_amd as fk
+    from paper_2505_00570_amd import binding, synth
+
+    k, v = synth.empty_cache(wl, dev)
+    synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
+    n = wl.window
+    L = binding.layout_for(k)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, n, n, 0, 0.5)
+    ws = torch.empty(p.workspace_bytes + (1 << 20), dtype=torch.uint8, device=dev)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), ws.numel()
+    out = torch.empty(2, wl.n_layers, wl.n_heads, n, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fk.power_spectrum(k, v, out, L, wl.n_heads, wl.head_dim, 0, n, stream)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import freqkv_oracle as orc
+        x = k[0, :, 0].cpu().float().double().numpy()
+        t0 = time.perf_counter()
+        orc.power_spectrum(x)
+        dtc = time.perf_counter() - t0
+        cpu = {"value": x.size * 2 / dtc / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"one (layer, head) of K, {x.shape[0]} sample(s) x {n} rows x {wl.head_dim}, {dtc:.1f} s on 1 thread"}
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fk.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = fk.profile_read()
+    fk.profile_enable(False)
+    mfma_tflops = fk.calibrate_mfma(20000, stream)
+    hts = 2 * wl.n_layers * wl.batch * wl.n_heads
+    fold = n % 2 == 0
+    flops = hts * wl.head_dim * (float(n) * n if fold else 2.0 * n * n)     # executed: the fold halves 2 n^2 d
+    launches = max(int(prof.launches_contract), 1)
+    ms_contract = prof.ms_contract / launches
+    achieved = flops * args.steps / launches / (ms_contract * 1e-3) / 1e12
+    bytes_in = hts * n * wl.head_dim * 2
+    print(json.dumps({
+        "metric": "power-spectrum throughput (GB/s KV in)", "value": bytes_in / (dt / args.steps) / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "dtype_note": "bf16 cache; fp16 MFMA operands, fp32 accumulation and squares", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: power spectrum of K and V, {hts} head-tensors x {n} rows x {wl.head_dim}",
+                   "operator": "power_spectrum"},
+        "ms_prepare_kernel": prof.ms_prepare / max(int(prof.launches_prepare), 1), "ms_contract_kernel": ms_contract,
+        "roofline": {"bound": "mfma", "kernel": "k_contract_f16<spectrum>", "achieved": achieved,
+                     "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": None, "ms_per_launch": ms_contract, "flops_per_launch": flops * args.steps / launches,
+                     "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,6 +207,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend", action="store_true",
                     help="time decode attention over the full cache (rotary embedding at read time) instead of compression")
+    ap.add_argument("--spectrum", action="store_true",
+                    help="time the power-spectrum diagnostic over the full window instead of compression")
     ap.add_argument("--dropping", action="store_true",
                     help="time the Dropping variant (row moves only): the memcpy-roofline reference of the write-back step")
     args = ap.parse_args()
@@ -164,6 +229,8 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.attend:
         return bench_attend(args, wl, dev)
+    if args.spectrum:
+        return bench_spectrum(args, wl, dev)
 
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)

@@ -234,6 +234,23 @@ FREQKV_API freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void
                                             int n_kv_heads, int head_dim, const int32_t* cur_lens,
                                             int max_cur_len, double rope_base, void* stream);
 
+/*
+ * Average power spectrum of the cached key and value states (Sec. 3.1 and its figure; appendix on the
+ * head-wise analysis): rows [row0, row0 + n_rows) of every head-tensor go through the orthonormal
+ * n_rows-point DCT-II along the token axis (Appendix A), and the squared coefficients are averaged over
+ * the batch ("samples") and the head_dim channels.  A diagnostic: the cache is only read.
+ *   out   DEVICE array [2 (K,V)][n_layers][n_heads][n_rows] fp32, 16-byte aligned; overwritten
+ *   layout.workspace   as for a trigger with window - n_sink = n_rows (freqkv_plan reports it for
+ *                      n_sink = row0, window = row0 + n_rows, any retain_ratio < 1)
+ * bf16 caches only (FREQKV_E_UNSUPPORTED otherwise); n_rows >= 2.  fp16 operands put a noise floor of
+ * about 2e-7 of the average line under every line.  The sums are accumulated with fp32 atomics, so the
+ * last bits can differ from call to call.  The first call for a new (device, n_rows) builds and caches the
+ * transform matrix (one allocation of about n_rows^2 bytes).
+ */
+FREQKV_API freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, float* out,
+                                      const freqkv_layout_t* layout, int n_heads, int head_dim,
+                                      int row0, int n_rows, void* stream);
+
 /* Human-readable name of a status code (static string, host). */
 FREQKV_API const char* freqkv_status_string(freqkv_status_t status);
 

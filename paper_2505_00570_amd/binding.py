@@ -98,6 +98,9 @@ def load() -> C.CDLL:
         lib.freqkv_compress_ragged.argtypes = [C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.POINTER(C.c_int32),
                                                C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_compress_ragged.restype = C.c_int
+        lib.freqkv_power_spectrum.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.c_int,
+                                              C.c_int, C.c_void_p]
+        lib.freqkv_power_spectrum.restype = C.c_int
         lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_prepare.restype = C.c_int
         lib.freqkv_status_string.argtypes = [C.c_int]
@@ -206,6 +209,14 @@ def compress_ragged(k, v, layout: Layout, n_heads: int, head_dim: int, cur_lens,
     if check:
         _check(rc)
     return rc, list(nl)
+
+
+def power_spectrum(k, v, out, layout: Layout, n_heads: int, head_dim: int, row0: int, n_rows: int, stream=None,
+                   check: bool = True) -> int:
+    """freqkv_power_spectrum.  out: fp32 device tensor [2, layers, heads, n_rows]."""
+    rc = load().freqkv_power_spectrum(_dev_ptr(k), _dev_ptr(v), _dev_ptr(out), C.byref(layout), n_heads, head_dim,
+                                      row0, n_rows, _stream_ptr(stream))
+    return _check(rc) if check else rc
 
 
 def profile_enable(on: bool) -> None:

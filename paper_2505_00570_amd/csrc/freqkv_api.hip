@@ -477,7 +477,7 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
         if (sh.variant == kF32)
             HIP_TRY(launch_contract_f32(tab, g, (const float*)basis, (const float*)L.workspace, tap, st));
         else
-            HIP_TRY(launch_contract_f16(tab, g, (const _Float16*)basis, (const _Float16*)L.workspace, tap, st));
+            HIP_TRY(launch_contract_f16(tab, g, (const _Float16*)basis, (const _Float16*)L.workspace, tap, 0, st));
         HIP_TRY(prof_end(st, &sp));
     }
     return FREQKV_OK;
@@ -651,6 +651,56 @@ freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void* k, const 
     if (!cur_lens || ((uintptr_t)cur_lens & 3)) return FREQKV_E_INVALID;
     return attend_impl(q, k, v, out, lse, layout, n_q_heads, n_kv_heads, head_dim, max_cur_len, -1, cur_lens,
                        rope_base, stream);
+}
+
+freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, float* out, const freqkv_layout_t* layout,
+                                      int n_heads, int head_dim, int row0, int n_rows, void* stream)
+{
+    g_last_error[0] = 0;
+    if (!layout || !k || !v || !out) return FREQKV_E_INVALID;
+    if (row0 < 0 || n_rows < 2) return FREQKV_E_INVALID;
+    if ((long long)row0 + n_rows > layout->token_capacity) return FREQKV_E_INVALID;
+    if ((uintptr_t)out & 15) return FREQKV_E_INVALID;
+    // same shape rules as a trigger whose span is rows [row0, row0 + n_rows) and keeps every coefficient
+    Shape sh;
+    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, row0 + n_rows, row0 + n_rows, row0, 1.0, &sh);
+    if (rc < 0) return rc;
+    if (layout->dtype != FREQKV_BF16) return FREQKV_E_UNSUPPORTED;
+    sh.variant = (sh.n % 2 == 0) ? kFoldF16 : kPlainF16;
+    sh.high = 2;
+    const freqkv_layout_t& L = *layout;
+    std::vector<char*> bases;
+    rc = resolve_bases(const_cast<void*>(k), const_cast<void*>(v), L, sh, 0, &bases);
+    if (rc < 0) return rc;
+    size_t min_ws = pass_workspace(sh, 1);
+    if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < min_ws) return FREQKV_E_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    int per_pass = sh.nslabs < kMaxSlabs ? sh.nslabs : kMaxSlabs;
+    while (per_pass > 1 && pass_workspace(sh, per_pass) > L.workspace_bytes) --per_pass;
+    void* basis = nullptr;
+    {
+        Geom g0 = make_geom(sh, L, per_pass, 0);
+        rc = get_basis(sh, g0, 1, st, &basis);
+        if (rc < 0) return rc;
+    }
+    HIP_TRY(launch_fill_zero(out, (size_t)sh.nslabs * sh.n_heads * sh.n, st));
+    for (int s0 = 0; s0 < sh.nslabs; s0 += per_pass) {
+        int slabs = sh.nslabs - s0 < per_pass ? sh.nslabs - s0 : per_pass;
+        Geom g = make_geom(sh, L, slabs, s0);
+        g.spec_scale = (float)(1.0 / ((double)sh.batch * sh.d));
+        SlabTable tab;
+        memset(&tab, 0, sizeof(tab));
+        for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
+        ProfSpan sp;
+        HIP_TRY(prof_begin(st, 0, &sp));
+        HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st));
+        HIP_TRY(prof_end(st, &sp));
+        HIP_TRY(prof_begin(st, 1, &sp));
+        HIP_TRY(launch_contract_f16(tab, g, (const _Float16*)basis, (const _Float16*)L.workspace, out, 1, st));
+        HIP_TRY(prof_end(st, &sp));
+    }
+    return FREQKV_OK;
 }
 
 void freqkv_shutdown(void)

@@ -31,7 +31,9 @@ struct Geom {
     int ncols;           // virtual columns in this pass = slabs * hts_per_slab * d
     int ncoltiles;       // ceil(ncols / kColTile)
     int fold;            // 1: even/odd folded operator, 0: plain
-    int high;            // 1: the Lc highest coefficients are kept (ablation variant), 0: the lowest
+    int high;            // 0: the Lc lowest coefficients are kept, 1: the highest (ablation variant),
+                         // 2: forward transform only, all n coefficients (power spectrum)
+    float spec_scale;    // power spectrum: 1 / (batch * head_dim)
     int Kh;              // contraction length: n/2 (fold) or n
     int Kpad;            // Kh rounded up to kKStage
     int nkstages;        // Kpad / kKStage
@@ -53,8 +55,10 @@ hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hip
 
 // ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
+// spec != 0: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (accumulated with atomics)
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
-                               const _Float16* ws, float* tap, hipStream_t st);
+                               const _Float16* ws, float* tap, int spec, hipStream_t st);
+hipError_t launch_fill_zero(float* p, size_t count, hipStream_t st);
 
 // ---- fp32 cache ------------------------------------------------------------------------
 hipError_t launch_prepare_f32(const SlabTable& tab, const Geom& g, float* ws, hipStream_t st);

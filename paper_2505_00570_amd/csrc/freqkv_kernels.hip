@@ -91,6 +91,14 @@ __device__ double shifted_cos_sum(long long q, long long p2, long long Q, long l
     return sinpi((double)num / (double)Q) * cospi((double)arg / (double)Q) / sinpi((double)q / (double)Q);
 }
 
+// Entry (t, j) of the orthonormal n-point DCT-II matrix (Appendix A): alpha_t cos(pi t (2j+1) / 2n).
+__device__ double dct_entry(long long t, long long j, long long n)
+{
+    long long q = (t * (2 * j + 1)) % (4 * n);
+    double a = t == 0 ? sqrt(1.0 / (double)n) : sqrt(2.0 / (double)n);
+    return a * cospi((double)q / (double)(2 * n));
+}
+
 // Entry (m, j) of the fused operator.  band 0: the Lc lowest coefficients are kept (Sec. 3.3).
 // band 1: the Lc highest are kept and handed, in order, to the Lc-point inverse (the high-frequency
 // ablation): M[m][j] = (2/n) * sum_{s<Lc} w_s cos(a_m s) cos(b_j (s + n - Lc)), w_0 = 1/sqrt(2), else 1.
@@ -124,7 +132,11 @@ __global__ void k_basis_f16(_Float16* __restrict__ G, Geom g, double scale)
     for (int i = 0; i < 8; ++i) {
         int j = kg * 8 + i;
         double v = 0.0;
-        if (m < g.Mh && j < g.Kh) {
+        if (m < g.Mh && j < g.Kh && g.high == 2) {
+            // forward transform only (power spectrum): the even-indexed rows act on the symmetric part of
+            // the span and the odd-indexed rows on the antisymmetric part, so the fold needs no mixing
+            v = dct_entry(g.fold ? 2 * m + parity : m, j, g.n);
+        } else if (m < g.Mh && j < g.Kh) {
             double a = operator_entry(m, j, g.n, g.Lc, scale, g.high);
             if (g.fold) {
                 double b = operator_entry(g.Lc - 1 - m, j, g.n, g.Lc, scale, g.high);
@@ -249,7 +261,9 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool FOLD, int NW>
+// SPEC: instead of writing rows into the cache, add the squared results, summed over the 8 channels of an
+// item and scaled by g.spec_scale, to the spectrum line of the item's head: tap[(slab, head)][coefficient].
+template <bool FOLD, int NW, bool SPEC>
 __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom g,
                                                          const _Float16* __restrict__ G,
                                                          const _Float16* __restrict__ ws,
@@ -445,7 +459,13 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
         int ht;
         base = column_base(tab, g, vcol, 2, &ht);
         const int c = vcol - ht * g.d;
-        if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c;
+        if constexpr (SPEC) {
+            const int slab = ht / g.hts_per_slab;
+            const int h = (ht - slab * g.hts_per_slab) % g.n_heads;
+            tp = tap + ((g.tap_slab0 + slab) * (long long)g.n_heads + h) * g.Lc;
+        } else {
+            if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c;
+        }
     }
     static_for<MBN>([&](auto mbc) {
         constexpr int MB = decltype(mbc)::value;
@@ -460,6 +480,41 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
         for (int it = 0; it < ITEMS / NT; ++it) {
             const int item = threadIdx.x + it * NT;
             const int row = (item >> 4) & 31, w = item >> 9;
+            if constexpr (SPEC) {
+                // Power spectrum: squares of the item's 8 channels; E is coefficient 2*rh and O coefficient
+                // 2*rh+1 (folded), or the row itself (plain).  No lane leaves early, so the 16 lanes that
+                // hold one row can be summed with lane exchanges when they all belong to one head
+                // (head_dim a multiple of 128); otherwise every lane adds its own share.
+                const int rh = mt * (FOLD ? kRowsFold : kRowsPlain) + w * WROWS + MB * 32 + row;
+                const bool ok = col_ok && rh < g.Mh;
+                const float* e = T + (((FOLD ? 0 * WPP : 0) + w) * 32 + row) * 128 + cg * 8;
+                const float* o = T + ((1 * WPP + w) * 32 + row) * 128 + cg * 8;
+                float pe = 0.f, po = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    pe = fmaf(e[i], e[i], pe);
+                    if constexpr (FOLD) po = fmaf(o[i], o[i], po);
+                }
+                pe = ok ? pe * g.spec_scale : 0.f;
+                po = ok ? po * g.spec_scale : 0.f;
+                bool lead = true;
+                if (g.d % 128 == 0) {
+                    for (int sft = 1; sft < 16; sft <<= 1) {
+                        pe += __shfl_xor(pe, sft);
+                        if constexpr (FOLD) po += __shfl_xor(po, sft);
+                    }
+                    lead = cg == 0;
+                }
+                if (ok && lead) {
+                    if constexpr (FOLD) {
+                        atomicAdd(tp + 2 * rh, pe);
+                        atomicAdd(tp + 2 * rh + 1, po);
+                    } else {
+                        atomicAdd(tp + rh, pe);
+                    }
+                }
+                continue;
+            }
             if (!col_ok) continue;
             float va[8], vb[8];
             int row_a, row_b = -1;
@@ -504,15 +559,34 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     });
 }
 
+__global__ void k_fill_zero(float* __restrict__ p, size_t count)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+hipError_t launch_fill_zero(float* p, size_t count, hipStream_t st)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, p, count);
+    return hipGetLastError();
+}
+
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
-                               const _Float16* ws, float* tap, hipStream_t st)
+                               const _Float16* ws, float* tap, int spec, hipStream_t st)
 {
     dim3 grid((unsigned)g.ncoltiles * (unsigned)g.nmtiles);
     // Four waves (one per SIMD, 128x128 accumulators each).  Eight waves of 64x128 are correct too but
     // measured 2.99 ms against 2.16 ms on the 8188 -> 4094 trigger: twice the LDS fragment traffic.
     constexpr int NW = 4;
-    if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
-    else        hipLaunchKernelGGL((k_contract_f16<false, NW>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+    if (spec) {
+        if (!tap) return hipErrorInvalidValue;
+        if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, true>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+        else        hipLaunchKernelGGL((k_contract_f16<false, NW, true>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+    } else {
+        if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, false>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+        else        hipLaunchKernelGGL((k_contract_f16<false, NW, false>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+    }
     return hipGetLastError();
 }
 

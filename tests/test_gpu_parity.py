@@ -520,3 +520,64 @@ def test_retain_high_rejects_dropping():
     rc = fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, check=False)
     torch.cuda.synchronize()
     assert rc == -1 and torch.equal(k, k0)
+
+
+# ------------------------------------------------------------------------------------------
+# power-spectrum diagnostic
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("layers,batch,heads,d,row0,n", [
+    (1, 1, 1, 128, 0, 256),      # folded transform, one head per column tile
+    (2, 3, 2, 128, 4, 508),      # batch averaged into the same lines, sinks skipped
+    (1, 2, 3, 64, 0, 330),       # two heads per column tile
+    (1, 1, 2, 128, 0, 701),      # odd length: plain transform
+    (1, 2, 5, 96, 3, 260),       # column tiles straddle heads
+    (1, 1, 2, 128, 0, 2048),     # several row tiles
+])
+def test_power_spectrum(layers, batch, heads, d, row0, n):
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=layers, batch=batch, n_heads=heads, head_dim=d,
+                     window=row0 + n)
+    _say(f"power spectrum layers={layers} batch={batch} heads={heads} d={d} row0={row0} n={n}")
+    k, v = _mk(wl, seed=n, capacity=row0 + n + 2, cur_len=row0 + n)
+    k0, v0 = k.clone(), v.clone()
+    L = binding.layout_for(k)
+    _, p = fk.plan(L, heads, d, row0 + n, row0 + n, row0, 0.5)
+    ws = torch.empty(p.workspace_bytes + (1 << 16), dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), ws.numel()
+    out = torch.full((2, layers, heads, n), float("nan"), dtype=torch.float32, device=DEV)
+    fk.power_spectrum(k, v, out, L, heads, d, row0, n)
+    torch.cuda.synchronize()
+    assert torch.equal(k, k0) and torch.equal(v, v0)            # a diagnostic: the cache is only read
+    got = out.cpu().double().numpy()
+    worst = 0.0
+    for kv, t in enumerate((k0, v0)):
+        for l in range(layers):
+            for h in range(heads):
+                ref = orc.power_spectrum(f64(t[l, :, h, row0:row0 + n].cpu()))
+                # fp16 operands: each coefficient carries ~2^-11 relative error plus a floor set by the rounding
+                # of the whole span; squaring doubles the relative part
+                bound = 5e-3 * ref + 1e-5 * ref.mean()
+                err = np.abs(got[kv, l, h] - ref)
+                worst = max(worst, float((err / bound).max()))
+                # Parseval on the GPU result: the lines sum to the mean energy per channel
+                assert math.isclose(got[kv, l, h].sum(), ref.sum(), rel_tol=1e-3)
+    _say(f"  worst err/bound {worst:.3f}")
+    assert worst <= 1.0
+    # twice in a row: the output is overwritten, not accumulated
+    fk.power_spectrum(k, v, out, L, heads, d, row0, n)
+    torch.cuda.synchronize()
+    assert np.allclose(out.cpu().double().numpy(), got, rtol=1e-4, atol=0)
+
+
+def test_power_spectrum_errors():
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=1, n_heads=1, window=128)
+    k, v = _mk(wl, seed=1)
+    L = binding.layout_for(k)
+    out = torch.full((2, 1, 1, 128), 7.0, dtype=torch.float32, device=DEV)
+    f = lambda *a: fk.power_spectrum(k, v, out, L, 1, 128, *a, check=False)
+    assert f(0, 128) == -3                      # no workspace
+    assert f(0, 129) == -1 and f(-1, 10) == -1 and f(0, 1) == -1
+    kf = torch.zeros(1, 1, 1, 128, 128, device=DEV)
+    assert fk.power_spectrum(kf, kf, out, binding.layout_for(kf), 1, 128, 0, 128, check=False) == -2
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
