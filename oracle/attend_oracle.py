@@ -100,3 +100,23 @@ def attend_decode(q, k, v, cur_len: int, q_pos: int | None = None, base: float =
     for h in range(hq):
         out[h], lse[h] = attend_decode_head(q[h], k[h // group], v[h // group], cur_len, q_pos, base, rope)
     return out, lse
+
+
+def attend_prefill(q, k, v, cur_len: int, base: float = 10000.0, rope: bool = True):
+    """Chunk-wise attention of Sec. 3.4 (Eq. 5): the last q_len cached rows are the tokens of the incoming
+    chunk; query i sits at in-cache position p_i = cur_len - q_len + i and attends to rows [0, p_i]:
+    sinks, compressed rows, the earlier tokens of its own chunk and itself.
+    q [Hq, q_len, d]; k, v [Hkv, T, d] (pre-rotary keys).  Returns (out [Hq, q_len, d], lse [Hq, q_len])."""
+    q = np.asarray(q, dtype=np.float64)
+    hq, q_len, d = q.shape
+    hkv = k.shape[0]
+    if hq % hkv or q_len < 1 or q_len > cur_len:
+        raise ValueError("bad shapes")
+    group = hq // hkv
+    out = np.zeros((hq, q_len, d))
+    lse = np.zeros((hq, q_len))
+    for h in range(hq):
+        for i in range(q_len):
+            p = cur_len - q_len + i
+            out[h, i], lse[h, i] = attend_decode_head(q[h, i], k[h // group], v[h // group], p + 1, p, base, rope)
+    return out, lse

@@ -172,3 +172,49 @@ def test_explicit_query_position():
     c, _ = att.attend_decode(q, k, v, 50, q_pos=48)
     assert np.array_equal(a, b)
     assert np.max(np.abs(a - c)) > 1e-3
+
+
+# -- chunk-wise (prefill) attention: causal inside the chunk, everything before it visible ------------
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_prefill_against_torch_causal_attention(rope):
+    hq, hkv, t, d, cur, qlen, base = 4, 2, 60, 16, 50, 20, 10000.0
+    r = _rng(21)
+    q = r.standard_normal((hq, qlen, d)) * 2.0
+    k = r.standard_normal((hkv, t, d))
+    v = r.standard_normal((hkv, t, d))
+    out, lse = att.attend_prefill(q, k, v, cur, base=base, rope=rope)
+    tq = torch.from_numpy(q)
+    tk = torch.from_numpy(k[:, :cur]).repeat_interleave(hq // hkv, dim=0)
+    tv = torch.from_numpy(v[:, :cur]).repeat_interleave(hq // hkv, dim=0)
+    if rope:
+        tq = _rotate_half_torch(tq, torch.arange(cur - qlen, cur), base)
+        tk = _rotate_half_torch(tk, torch.arange(cur), base)
+    # query i may see key j iff j <= cur - qlen + i
+    mask = torch.arange(cur)[None, :] <= (torch.arange(qlen)[:, None] + cur - qlen)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], attn_mask=mask)[0]
+    assert np.allclose(out, ref.numpy(), atol=1e-12)
+    s = (tq @ tk.transpose(1, 2)) / math.sqrt(d)
+    s = s.masked_fill(~mask, float("-inf"))
+    assert np.allclose(lse, torch.logsumexp(s, dim=-1).numpy(), atol=1e-12)
+
+
+def test_prefill_special_cases():
+    hq, hkv, t, d = 2, 1, 40, 8
+    r = _rng(22)
+    q = r.standard_normal((hq, 7, d))
+    k = r.standard_normal((hkv, t, d))
+    v = r.standard_normal((hkv, t, d))
+    out, lse = att.attend_prefill(q, k, v, 30)
+    # the last query of the chunk is the decode case
+    dout, dlse = att.attend_decode(q[:, -1], k, v, 30)
+    assert np.array_equal(out[:, -1], dout) and np.array_equal(lse[:, -1], dlse)
+    # a chunk that is the whole cache: the first query sees only itself
+    out2, _ = att.attend_prefill(q, k, v, 7)
+    assert np.allclose(out2[:, 0], v[0, 0], atol=0)
+    # later rows of the chunk never influence earlier queries
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 27:] = 9.0
+    v2[:, 27:] = -9.0
+    out3, _ = att.attend_prefill(q, k2, v2, 30)
+    assert np.array_equal(out3[:, :4], out[:, :4]) and not np.allclose(out3[:, 4:], out[:, 4:])
