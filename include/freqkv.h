@@ -251,6 +251,37 @@ FREQKV_API freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, f
                                       const freqkv_layout_t* layout, int n_heads, int head_dim,
                                       int row0, int n_rows, void* stream);
 
+/* Result of the chunk-attention buffer-plan query (host arithmetic only). */
+typedef struct freqkv_prefill_plan {
+    size_t  workspace_bytes;    /* rotary table, rotated keys, transposed values, rotated queries (fp16)      */
+    int32_t key_tiles;          /* ceil(cur_len / 32)                                                         */
+    int32_t query_blocks;       /* ceil(q_len / 64)                                                           */
+    double  flops;              /* 4 * head_dim per (query, visible row), summed                              */
+    double  bytes_algorithmic;  /* K and V rows [0, cur_len) once, q read, out written                        */
+} freqkv_prefill_plan_t;
+
+FREQKV_API freqkv_status_t freqkv_attend_prefill_plan(const freqkv_layout_t* layout, int n_q_heads,
+                                           int n_kv_heads, int head_dim, int cur_len, int q_len,
+                                           freqkv_prefill_plan_t* out);
+
+/*
+ * Chunk-wise attention of training and prefilling (Sec. 3.4 Eq. 5): the q_len tokens of the incoming chunk
+ * are the LAST q_len cached rows (their keys and values must already be in the cache); query i sits at
+ * in-cache position cur_len - q_len + i and attends to rows [0, that position]: sinks, compressed rows,
+ * the earlier tokens of its chunk and itself.  Rotary embedding, head grouping and scaling exactly as in
+ * freqkv_attend_decode (its last query is this call's last query).
+ *   q, out   [n_layers][batch][n_q_heads][q_len][head_dim], dense, bfloat16
+ *   lse      optional [n_layers][batch][n_q_heads][q_len] fp32
+ *   layout.workspace  at least freqkv_attend_prefill_plan(...).workspace_bytes, 256-byte aligned
+ * head_dim 128 and bfloat16 caches only (FREQKV_E_UNSUPPORTED otherwise).  Operands of the matrix cores are
+ * fp16 (cache values are exact in fp16; rotated keys and queries keep 11 significant bits), accumulation,
+ * softmax and the running sums are fp32.  The call only enqueues work on `stream`.
+ */
+FREQKV_API freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, const void* v, void* out,
+                                      float* lse, const freqkv_layout_t* layout, int n_q_heads,
+                                      int n_kv_heads, int head_dim, int cur_len, int q_len,
+                                      double rope_base, void* stream);
+
 /* Human-readable name of a status code (static string, host). */
 FREQKV_API const char* freqkv_status_string(freqkv_status_t status);
 

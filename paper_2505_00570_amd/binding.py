@@ -61,6 +61,14 @@ class Profile(C.Structure):
     ]
 
 
+class PrefillPlan(C.Structure):
+    """struct freqkv_prefill_plan (include/freqkv.h)."""
+    _fields_ = [
+        ("workspace_bytes", C.c_size_t), ("key_tiles", C.c_int32), ("query_blocks", C.c_int32),
+        ("flops", C.c_double), ("bytes_algorithmic", C.c_double),
+    ]
+
+
 class AttendPlan(C.Structure):
     """struct freqkv_attend_plan (include/freqkv.h)."""
     _fields_ = [
@@ -101,6 +109,11 @@ def load() -> C.CDLL:
         lib.freqkv_power_spectrum.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, LP, C.c_int, C.c_int, C.c_int,
                                               C.c_int, C.c_void_p]
         lib.freqkv_power_spectrum.restype = C.c_int
+        lib.freqkv_attend_prefill_plan.argtypes = [LP, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(PrefillPlan)]
+        lib.freqkv_attend_prefill_plan.restype = C.c_int
+        lib.freqkv_attend_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
+                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_void_p]
+        lib.freqkv_attend_prefill.restype = C.c_int
         lib.freqkv_prepare.argtypes = [C.c_int, C.c_uint32, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_prepare.restype = C.c_int
         lib.freqkv_status_string.argtypes = [C.c_int]
@@ -216,6 +229,26 @@ def power_spectrum(k, v, out, layout: Layout, n_heads: int, head_dim: int, row0:
     """freqkv_power_spectrum.  out: fp32 device tensor [2, layers, heads, n_rows]."""
     rc = load().freqkv_power_spectrum(_dev_ptr(k), _dev_ptr(v), _dev_ptr(out), C.byref(layout), n_heads, head_dim,
                                       row0, n_rows, _stream_ptr(stream))
+    return _check(rc) if check else rc
+
+
+def attend_prefill_plan(layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int, cur_len: int, q_len: int,
+                        check: bool = True):
+    """freqkv_attend_prefill_plan: returns (status, PrefillPlan).  Host arithmetic only."""
+    out = PrefillPlan()
+    rc = load().freqkv_attend_prefill_plan(C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_len,
+                                           C.byref(out))
+    if check:
+        _check(rc)
+    return rc, out
+
+
+def attend_prefill(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                   cur_len: int, q_len: int, rope_base: float = 10000.0, stream=None, check: bool = True) -> int:
+    """freqkv_attend_prefill.  q, out: dense [layer, batch, q_head, q_len, dim] bf16 device tensors."""
+    rc = load().freqkv_attend_prefill(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(out), _dev_ptr(lse),
+                                      C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_len,
+                                      float(rope_base), _stream_ptr(stream))
     return _check(rc) if check else rc
 
 

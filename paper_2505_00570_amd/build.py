@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 LIB = os.path.join(LIB_DIR, "libfreqkv.so")
-SOURCES = ["freqkv_kernels.hip", "freqkv_attend.hip", "freqkv_api.hip"]
+SOURCES = ["freqkv_kernels.hip", "freqkv_attend.hip", "freqkv_prefill.hip", "freqkv_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops off: the compiler must not form v_pk_*_f32 from scalar float code.

@@ -703,6 +703,117 @@ freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, float* out, 
     return FREQKV_OK;
 }
 
+namespace {
+struct PrefillShape {
+    AttShape a;
+    int q_len, q_pad, key_tiles, layers_per_pass;
+    size_t off_kr, off_vt, off_qr, workspace_bytes;
+};
+
+freqkv_status_t check_prefill(const freqkv_layout_t* L, int n_q, int n_kv, int d, int cur_len, int q_len,
+                              PrefillShape* out)
+{
+    PrefillShape p;
+    freqkv_status_t rc = check_attend(L, n_q, n_kv, d, cur_len, &p.a);
+    if (rc < 0) return rc;
+    if (q_len < 1 || q_len > cur_len) return FREQKV_E_INVALID;
+    if (d != 128 || L->dtype != FREQKV_BF16) return FREQKV_E_UNSUPPORTED;
+    p.q_len = q_len;
+    p.q_pad = (int)round_up(q_len, 64);
+    p.key_tiles = (cur_len + 31) / 32;
+    p.layers_per_pass = p.a.n_layers < kMaxSlabs / 2 ? p.a.n_layers : kMaxSlabs / 2;
+    const long long units = (long long)p.layers_per_pass * p.a.batch * n_kv;
+    if (units * p.a.G * (p.q_pad / 64) > (1LL << 30)) return FREQKV_E_UNSUPPORTED;
+    size_t cs_bytes = (size_t)round_up((long long)cur_len * (d / 2) * 8, 256);
+    size_t kv_bytes = (size_t)units * p.key_tiles * 32 * d * 2;
+    size_t q_bytes = (size_t)units * p.a.G * p.q_pad * d * 2;
+    p.off_kr = cs_bytes;
+    p.off_vt = p.off_kr + kv_bytes;
+    p.off_qr = p.off_vt + kv_bytes;
+    p.workspace_bytes = p.off_qr + q_bytes;
+    *out = p;
+    return FREQKV_OK;
+}
+}  // namespace
+
+freqkv_status_t freqkv_attend_prefill_plan(const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
+                                           int head_dim, int cur_len, int q_len, freqkv_prefill_plan_t* out)
+{
+    if (!out) return FREQKV_E_INVALID;
+    PrefillShape p;
+    freqkv_status_t rc = check_prefill(layout, n_q_heads, n_kv_heads, head_dim, cur_len, q_len, &p);
+    if (rc < 0) return rc;
+    memset(out, 0, sizeof(*out));
+    out->workspace_bytes = p.workspace_bytes;
+    out->key_tiles = p.key_tiles;
+    out->query_blocks = p.q_pad / 64;
+    // query i sees cur_len - q_len + i + 1 rows; 4 d flops per (query, row): scores and weighted sum
+    const double rows_seen = (double)q_len * (cur_len - q_len) + 0.5 * (double)q_len * (q_len + 1);
+    const double heads = (double)p.a.units_all * p.a.G;
+    out->flops = heads * 4.0 * head_dim * rows_seen;
+    out->bytes_algorithmic = (double)p.a.units_all * 2.0 * cur_len * head_dim * 2 + heads * 2.0 * q_len * head_dim * 2;
+    return FREQKV_OK;
+}
+
+freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, const void* v, void* out, float* lse,
+                                      const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
+                                      int cur_len, int q_len, double rope_base, void* stream)
+{
+    g_last_error[0] = 0;
+    PrefillShape p;
+    freqkv_status_t rc = check_prefill(layout, n_q_heads, n_kv_heads, head_dim, cur_len, q_len, &p);
+    if (rc < 0) return rc;
+    if (!q || !k || !v || !out) return FREQKV_E_INVALID;
+    if (((uintptr_t)q | (uintptr_t)out | (uintptr_t)lse) & 15) return FREQKV_E_INVALID;
+    if (!(rope_base >= 0.0) || !(rope_base < 1e30)) return FREQKV_E_INVALID;
+    const freqkv_layout_t& L = *layout;
+    const AttShape& a = p.a;
+    std::vector<char*> bases((size_t)2 * a.n_layers);          // [layer][K|V]
+    for (int l = 0; l < a.n_layers; ++l) {
+        for (int kv = 0; kv < 2; ++kv) {
+            const void* root = kv ? v : k;
+            char* bp = L.pointer_table ? (char*)((void* const*)root)[l]
+                                       : (char*)root + (long long)l * L.stride_layer * a.elem;
+            if (!bp || ((uintptr_t)bp & 15)) return FREQKV_E_INVALID;
+            bases[(size_t)2 * l + kv] = bp;
+        }
+    }
+    if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < p.workspace_bytes)
+        return FREQKV_E_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)L.workspace;
+    const int upl = a.batch * a.n_kv;
+    for (int l0 = 0; l0 < a.n_layers; l0 += p.layers_per_pass) {
+        int layers = a.n_layers - l0 < p.layers_per_pass ? a.n_layers - l0 : p.layers_per_pass;
+        SlabTable tab;
+        memset(&tab, 0, sizeof(tab));
+        for (int i = 0; i < 2 * layers; ++i) tab.base[i] = bases[(size_t)2 * l0 + i];
+        PrefillGeom g;
+        memset(&g, 0, sizeof(g));
+        g.d = a.d; g.G = a.G; g.n_kv = a.n_kv;
+        g.units = layers * upl; g.units_per_layer = upl;
+        g.cur_len = cur_len; g.q_len = q_len; g.q_pad = p.q_pad; g.q_blocks = p.q_pad / 64;
+        g.key_tiles = p.key_tiles; g.rope = rope_base > 0.0;
+        g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
+        g.qscale = (float)(1.4426950408889634 / std::sqrt((double)a.d));
+        const long long head0 = (long long)l0 * upl * a.G;
+        const char* qp = (const char*)q + head0 * q_len * a.d * a.elem;
+        char* op = (char*)out + head0 * q_len * a.d * a.elem;
+        ProfSpan sp;
+        HIP_TRY(prof_begin(st, 0, &sp));
+        HIP_TRY(launch_prefill_prepare(tab, g, qp, rope_base > 0.0 ? rope_base : 1.0, (float2*)ws,
+                                       (_Float16*)(ws + p.off_kr), (_Float16*)(ws + p.off_vt),
+                                       (_Float16*)(ws + p.off_qr), st));
+        HIP_TRY(prof_end(st, &sp));
+        HIP_TRY(prof_begin(st, 3, &sp));
+        HIP_TRY(launch_attend_prefill(g, (const _Float16*)(ws + p.off_kr), (const _Float16*)(ws + p.off_vt),
+                                      (const _Float16*)(ws + p.off_qr), op, lse ? lse + head0 * q_len : nullptr, st));
+        HIP_TRY(prof_end(st, &sp));
+    }
+    return FREQKV_OK;
+}
+
 void freqkv_shutdown(void)
 {
     std::lock_guard<std::mutex> lock(g_mu);

@@ -114,4 +114,28 @@ hipError_t launch_attend_partial(const SlabTable& tab, const AttGeom& g, int ele
 hipError_t launch_attend_merge(const AttGeom& g, int elem_bytes, const float* part_acc, const float* part_ml,
                                void* out, float* lse, hipStream_t st);
 
+// ---- chunk-wise (prefill) attention over the compacted cache ------------------------------------------
+struct PrefillGeom {
+    int d;                 // head_dim (128)
+    int G;                 // query heads per KV head
+    int n_kv;
+    int units;             // layers in this pass * batch * n_kv
+    int units_per_layer;   // batch * n_kv
+    int cur_len;           // cached rows, the chunk's tokens included
+    int q_len;             // tokens of the chunk = queries per head; they are the last q_len cached rows
+    int q_pad;             // q_len rounded up to 64
+    int q_blocks;          // q_pad / 64
+    int key_tiles;         // ceil(cur_len / 32)
+    int rope;
+    long long stride_batch, stride_head, stride_token;   // elements
+    float qscale;          // log2(e) / sqrt(d)
+};
+
+// cs: [cur_len][d/2] (cos, sin); Kr, Vt: [units][key_tiles] tiles of 32 keys x d fp16 in fragment order;
+// Qr: [units*G][q_pad][d] fp16.  q: dense [units*G][q_len][d] bf16.
+hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, const void* q, double rope_base,
+                                  float2* cs, _Float16* Kr, _Float16* Vt, _Float16* Qr, hipStream_t st);
+hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const _Float16* Qr,
+                                 void* out, float* lse, hipStream_t st);
+
 }  // namespace freqkv

@@ -1,0 +1,425 @@
+// gfx950 kernels for chunk-wise (prefill) attention over the compacted cache.
+//
+// The tokens of an incoming chunk are the last q_len cached rows; query i sits at in-cache position
+// p_i = cur_len - q_len + i and attends to rows [0, p_i]: sinks, compressed rows, the earlier tokens of its
+// chunk and itself (Sec. 3.4 Eq. 5).  Keys are cached un-rotated and take the rotary embedding of their
+// row index when they are read; queries take the one of p_i (closing paragraph of Sec. 3.4).
+//
+// Unlike the one-token case this is a dense contraction (q_len x cur_len x d per head, twice), so it runs
+// on the matrix cores, as a streaming-softmax attention kernel.  Three small passes put the operands into
+// MFMA fragment order first (all fp16: a bf16 cache value is exact in fp16, and the rotated keys and
+// queries keep 11 significant bits instead of 8):
+//   k_prefill_cs      cos/sin of (row * theta_j) for every cached row, fp64 angle reduction, fp32 table
+//   k_prefill_prep_k  Kr = rotate(K) in tiles of 32 keys, [tile][group of 8 channels][key][8]
+//   k_prefill_prep_v  Vt = V transposed in tiles of 32 keys, [tile][channel block][k-step][half][channel][8 keys],
+//                     keys permuted so that a softmax tile, as the matrix core leaves it in registers, is
+//                     already the second operand of the weighted sum
+//   k_prefill_prep_q  Qr = rotate(q) * log2(e)/sqrt(d), row-major
+// and k_attend_prefill computes, per wave, S^T = Kr Qr^T for 32 keys x 64 queries, the running softmax per
+// query (a query is a column, so its maximum and sum are in-lane reductions plus one exchange between the
+// two half-waves), and O^T += Vt P^T.
+#include "freqkv_internal.h"
+
+namespace freqkv {
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int I> struct IC { static constexpr int value = I; };
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+constexpr int kD = 128;            // head_dim served by this kernel
+constexpr int kKeyTile = 32;       // keys per tile
+constexpr int kQPerWave = 64;      // queries per wave
+constexpr int kTileBytes = kKeyTile * kD * 2;   // one Kr or Vt tile, fp16
+constexpr float kMinusBig = -1.0e30f;
+constexpr float kSlack = 8.0f;     // log2 of the largest un-rescaled softmax weight
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint32_t pack_half2(float a, float b)
+{
+    half2v h = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// Position of the key that sits at storage index s (0..31) of a Vt tile: the matrix core leaves a
+// 32x32 result with register r of a lane in half-wave hw at row 8*(r/4) + 4*hw + r%4; k-step t of the
+// weighted sum takes registers 8t .. 8t+7, so storage index s = 16t + 8hw + e holds key
+// 16t + 8*(e/4) + 4*hw + e%4.
+__device__ __forceinline__ int vt_key(int s)
+{
+    int t = s >> 4, hw = (s >> 3) & 1, e = s & 7;
+    return 16 * t + 8 * (e >> 2) + 4 * hw + (e & 3);
+}
+
+}  // namespace
+
+// cs[p][j] = (cos, sin)(p * base^(-2j/d)), p < rows, j < d/2.
+__global__ void k_prefill_cs(float2* __restrict__ cs, int rows, int d, double base, int rope)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    int half = d / 2;
+    if (idx >= (long long)rows * half) return;
+    int p = (int)(idx / half), j = (int)(idx - (long long)p * half);
+    float2 o = {1.f, 0.f};
+    if (rope) {
+        double theta = pow(base, -2.0 * (double)j / (double)d);
+        double x = (double)p * theta;
+        double k = rint(x * 0.15915494309189535);
+        double r = fma(-k, 6.283185307179586, x);
+        r = fma(-k, 2.4492935982947064e-16, r);
+        double s, c;
+        sincos(r, &s, &c);
+        o.x = (float)c;
+        o.y = (float)s;
+    }
+    cs[idx] = o;
+}
+
+// One thread per (unit, key row, group of 8 channels): rotate and store in fragment order.
+// Kr tile layout (fp16): [group of 8 channels g8 = 0..15][key 0..31][8].
+__global__ void k_prefill_prep_k(const SlabTable tab, const PrefillGeom g, const float2* __restrict__ cs,
+                                 _Float16* __restrict__ Kr)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int g8n = kD / 8;
+    long long total = (long long)g.units * g.key_tiles * kKeyTile * g8n;
+    if (idx >= total) return;
+    int g8 = (int)(idx % g8n);
+    long long rest = idx / g8n;
+    int p = (int)(rest % ((long long)g.key_tiles * kKeyTile));
+    int unit = (int)(rest / ((long long)g.key_tiles * kKeyTile));
+    half8 out;
+    for (int i = 0; i < 8; ++i) out[i] = (_Float16)0.f;
+    if (p < g.cur_len) {
+        int layer = unit / g.units_per_layer;
+        int rem = unit - layer * g.units_per_layer;
+        int b = rem / g.n_kv, kvh = rem - b * g.n_kv;
+        const uint16_t* row = (const uint16_t*)tab.base[2 * layer] + (long long)b * g.stride_batch +
+                              (long long)kvh * g.stride_head + (long long)p * g.stride_token;
+        const int half = kD / 2;
+        const bool upper = g8 * 8 >= half;
+        const int j0 = upper ? g8 * 8 - half : g8 * 8;         // first rotary pair of this group
+        u32x4 own = *(const u32x4*)(row + g8 * 8);
+        u32x4 oth = *(const u32x4*)(row + (upper ? j0 : j0 + half));
+        const float2* c = cs + (long long)p * half + j0;
+        for (int i = 0; i < 4; ++i) {
+            float a0 = bf16_lo(own[i]), a1 = bf16_hi(own[i]);
+            float b0 = bf16_lo(oth[i]), b1 = bf16_hi(oth[i]);
+            float2 c0 = c[2 * i], c1 = c[2 * i + 1];
+            // lower half: x_j cos - x_{j+d/2} sin;  upper half: x_{j+d/2} cos + x_j sin
+            float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
+            float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
+            out[2 * i] = (_Float16)r0;
+            out[2 * i + 1] = (_Float16)r1;
+        }
+    }
+    int tile = p / kKeyTile, key = p % kKeyTile;
+    _Float16* dst = Kr + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) + ((long long)g8 * kKeyTile + key) * 8;
+    *(half8*)dst = out;
+}
+
+// One thread per (unit, tile, 16-byte group of a Vt tile).
+// Vt tile layout (fp16): [channel block db = 0..3][k-step t = 0..1][half-wave hw = 0..1][channel 0..31][8 keys].
+__global__ void k_prefill_prep_v(const SlabTable tab, const PrefillGeom g, _Float16* __restrict__ Vt)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int groups = kKeyTile * kD / 8;                     // 16-byte groups per tile
+    long long total = (long long)g.units * g.key_tiles * groups;
+    if (idx >= total) return;
+    int grp = (int)(idx % groups);
+    long long rest = idx / groups;
+    int tile = (int)(rest % g.key_tiles);
+    int unit = (int)(rest / g.key_tiles);
+    int dl = grp & 31, hw = (grp >> 5) & 1, t = (grp >> 6) & 1, db = grp >> 7;
+    int layer = unit / g.units_per_layer;
+    int rem = unit - layer * g.units_per_layer;
+    int b = rem / g.n_kv, kvh = rem - b * g.n_kv;
+    const uint16_t* head = (const uint16_t*)tab.base[2 * layer + 1] + (long long)b * g.stride_batch +
+                           (long long)kvh * g.stride_head;
+    const int ch = db * 32 + dl;
+    half8 out;
+    for (int e = 0; e < 8; ++e) {
+        int key = tile * kKeyTile + vt_key(16 * t + 8 * hw + e);
+        float x = 0.f;
+        if (key < g.cur_len) x = __uint_as_float((uint32_t)head[(long long)key * g.stride_token + ch] << 16);
+        out[e] = (_Float16)x;
+    }
+    *(half8*)(Vt + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) + (long long)grp * 8) = out;
+}
+
+// One thread per (query head, query row, group of 8 channels): rotate at the query's in-cache position,
+// scale, store row-major [head][q_pad][d]; rows beyond q_len are zero.
+__global__ void k_prefill_prep_q(const uint16_t* __restrict__ q, const PrefillGeom g,
+                                 const float2* __restrict__ cs, _Float16* __restrict__ Qr)
+{
+    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int g8n = kD / 8;
+    long long total = (long long)g.units * g.G * g.q_pad * g8n;
+    if (idx >= total) return;
+    int g8 = (int)(idx % g8n);
+    long long rest = idx / g8n;
+    int i = (int)(rest % g.q_pad);
+    long long head = rest / g.q_pad;
+    half8 out;
+    for (int e = 0; e < 8; ++e) out[e] = (_Float16)0.f;
+    if (i < g.q_len) {
+        const uint16_t* row = q + (head * g.q_len + i) * kD;
+        const int half = kD / 2;
+        const bool upper = g8 * 8 >= half;
+        const int j0 = upper ? g8 * 8 - half : g8 * 8;
+        u32x4 own = *(const u32x4*)(row + g8 * 8);
+        u32x4 oth = *(const u32x4*)(row + (upper ? j0 : j0 + half));
+        const int pos = g.cur_len - g.q_len + i;
+        const float2* c = cs + (long long)pos * half + j0;
+        for (int e = 0; e < 4; ++e) {
+            float a0 = bf16_lo(own[e]), a1 = bf16_hi(own[e]);
+            float b0 = bf16_lo(oth[e]), b1 = bf16_hi(oth[e]);
+            float2 c0 = c[2 * e], c1 = c[2 * e + 1];
+            float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
+            float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
+            out[2 * e] = (_Float16)(r0 * g.qscale);
+            out[2 * e + 1] = (_Float16)(r1 * g.qscale);
+        }
+    }
+    *(half8*)(Qr + (head * g.q_pad + i) * kD + g8 * 8) = out;
+}
+
+// Workgroup = 4 waves = 4 tasks of one KV unit; a task is (query head of the KV group, block of 64 queries),
+// heads fastest, so that with 4 query heads per KV head the four waves walk the same keys.
+__global__ __launch_bounds__(256, 1)
+void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, const _Float16* __restrict__ Vt,
+                      const _Float16* __restrict__ Qr, uint16_t* __restrict__ out, float* __restrict__ lse)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[2][2 * kTileBytes];   // [slot][Kr tile | Vt tile]
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int l32 = lane & 31, hw = lane >> 5;
+    const int tasks_per_unit = g.G * g.q_blocks;
+    const int wgs_per_unit = (tasks_per_unit + 3) / 4;
+    const int unit = blockIdx.x / wgs_per_unit;
+    // later query blocks see more keys: hand them out first so that the long workgroups start early
+    const int wg_in_unit = wgs_per_unit - 1 - (blockIdx.x - unit * wgs_per_unit);
+    const int task = wg_in_unit * 4 + wave;
+    const bool active = task < tasks_per_unit;
+    const int qb = active ? task / g.G : 0;
+    const int gh = active ? task - qb * g.G : 0;
+    const long long head = (long long)unit * g.G + gh;             // dense query-head index
+    const int q0 = qb * kQPerWave;                                 // first query row of this wave
+    const int pos0 = g.cur_len - g.q_len + q0;                     // its in-cache position
+
+    // keys this wave needs: [0, pos0 + 63] cut at cur_len; the workgroup loads up to its largest need
+    const int my_last = active ? min(pos0 + kQPerWave - 1, g.cur_len - 1) : -1;
+    const int my_tiles = (my_last + kKeyTile) / kKeyTile;
+    int wg_tiles;
+    {
+        const int last_task = min(wg_in_unit * 4 + 3, tasks_per_unit - 1);
+        const int last_qb = last_task / g.G;
+        const int wg_last = min(g.cur_len - g.q_len + last_qb * kQPerWave + kQPerWave - 1, g.cur_len - 1);
+        wg_tiles = (wg_last + kKeyTile) / kKeyTile;
+    }
+
+    // ---- queries of this wave: second operand of S^T = Kr Qr^T, lane = query column, 8 channels per k-step half
+    half8 qf[2][8];
+    {
+        const _Float16* qrow = Qr + (head * g.q_pad + q0) * kD;
+        static_for<2>([&](auto qs) {
+            static_for<8>([&](auto s) {
+                const _Float16* p = qrow + (qs.value * 32 + l32) * kD + s.value * 16 + hw * 8;
+                qf[qs.value][s.value] = active ? *(const half8*)p : half8{};
+            });
+        });
+    }
+
+    f32x16 acc[4][2];           // O^T: [channel block][query sub-block], 32 channels x 32 queries each
+    static_for<4>([&](auto db) {
+        static_for<2>([&](auto qs) {
+            static_for<16>([&](auto r) { acc[db.value][qs.value][r.value] = 0.f; });
+        });
+    });
+    float m[2] = {kMinusBig, kMinusBig}, lsum[2] = {0.f, 0.f};     // per query column (lane), both half-waves agree
+
+    const char* ksrc = (const char*)(Kr + (long long)unit * g.key_tiles * (kKeyTile * kD));
+    const char* vsrc = (const char*)(Vt + (long long)unit * g.key_tiles * (kKeyTile * kD));
+    const int tid16 = threadIdx.x * 16;
+
+    // stage a tile pair through registers into an LDS slot: 16 KiB = 4 x 16 bytes per thread
+    u32x4 stage[4];
+    auto load_tile = [&](int tile) {
+        const char* ks = ksrc + (long long)tile * kTileBytes + tid16;
+        const char* vs = vsrc + (long long)tile * kTileBytes + tid16;
+        stage[0] = *(const u32x4*)ks;
+        stage[1] = *(const u32x4*)(ks + 4096);
+        stage[2] = *(const u32x4*)vs;
+        stage[3] = *(const u32x4*)(vs + 4096);
+    };
+    auto store_tile = [&](int slot) {
+        char* d = smem[slot] + tid16;
+        *(u32x4*)d = stage[0];
+        *(u32x4*)(d + 4096) = stage[1];
+        *(u32x4*)(d + kTileBytes) = stage[2];
+        *(u32x4*)(d + kTileBytes + 4096) = stage[3];
+    };
+
+    if (wg_tiles > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int tile = 0; tile < wg_tiles; ++tile) {
+        const int slot = tile & 1;
+        if (tile + 1 < wg_tiles) load_tile(tile + 1);
+
+        if (tile < my_tiles) {
+            const char* kt = smem[slot];
+            const char* vt = smem[slot] + kTileBytes;
+            // ---- S^T = Kr Qr^T : 32 keys x 64 queries, contraction over the 128 channels
+            f32x16 st[2];
+            static_for<2>([&](auto qs) { static_for<16>([&](auto r) { st[qs.value][r.value] = 0.f; }); });
+            static_for<8>([&](auto s) {
+                half8 kf = *(const half8*)(kt + ((s.value * 2 + hw) * kKeyTile + l32) * 16);
+                static_for<2>([&](auto qs) {
+                    st[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s.value], st[qs.value], 0, 0, 0);
+                });
+            });
+            // ---- causal mask (only tiles that reach past the first query of the wave), running softmax
+            const int key_base = tile * kKeyTile;
+            const bool diag = key_base + kKeyTile - 1 > pos0;
+            half8 pf[2][2];         // P^T as second operand of the weighted sum: [query sub-block][k-step]
+            static_for<2>([&](auto qs) {
+                constexpr int QS = decltype(qs)::value;
+                const int qpos = pos0 + QS * 32 + l32;
+                if (diag) {
+                    static_for<16>([&](auto r) {
+                        constexpr int R = decltype(r)::value;
+                        const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
+                        if (key > qpos) st[QS][R] = -INFINITY;
+                    });
+                }
+                float mx = st[QS][0];
+                static_for<16>([&](auto r) { mx = fmaxf(mx, st[QS][r.value]); });
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // the reference point moves only when a score exceeds it by more than 2^kSlack
+                const bool grow = mx > m[QS] + kSlack;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                    const float mn = grow ? mx : m[QS];
+                    const float f = exp2_fast(m[QS] - mn);
+                    m[QS] = mn;
+                    lsum[QS] *= f;
+                    static_for<4>([&](auto db) {
+                        static_for<16>([&](auto r) { acc[db.value][QS][r.value] *= f; });
+                    });
+                }
+                float ps = 0.f;
+                float pv[16];
+                static_for<16>([&](auto r) {
+                    pv[r.value] = exp2_fast(st[QS][r.value] - m[QS]);
+                    ps += pv[r.value];
+                });
+                ps += __shfl_xor(ps, 32);
+                lsum[QS] += ps;
+                static_for<2>([&](auto t) {
+                    u32x4 w;
+                    static_for<4>([&](auto e) {
+                        w[e.value] = pack_half2(pv[8 * t.value + 2 * e.value], pv[8 * t.value + 2 * e.value + 1]);
+                    });
+                    pf[QS][t.value] = __builtin_bit_cast(half8, w);
+                });
+            });
+            // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys
+            static_for<4>([&](auto db) {
+                static_for<2>([&](auto t) {
+                    half8 vf = *(const half8*)(vt + (((db.value * 2 + t.value) * 2 + hw) * 32 + l32) * 16);
+                    static_for<2>([&](auto qs) {
+                        acc[db.value][qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            vf, pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
+                    });
+                });
+            });
+        }
+
+        if (tile + 1 < wg_tiles) store_tile(slot ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: lane = query, registers = channels 8*(r/4) + 4*hw + r%4 of each block
+    if (active) {
+        static_for<2>([&](auto qs) {
+            constexpr int QS = decltype(qs)::value;
+            const int qi = q0 + QS * 32 + l32;
+            if (qi < g.q_len) {
+                const float inv = 1.0f / lsum[QS];
+                uint16_t* orow = out + (head * g.q_len + qi) * kD;
+                static_for<4>([&](auto db) {
+                    static_for<4>([&](auto r4) {
+                        constexpr int R = 4 * decltype(r4)::value;
+                        f32x2 a = {acc[db.value][QS][R] * inv, acc[db.value][QS][R + 1] * inv};
+                        f32x2 b = {acc[db.value][QS][R + 2] * inv, acc[db.value][QS][R + 3] * inv};
+                        u32x2 w;
+                        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+                        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+                        *(u32x2*)(orow + db.value * 32 + 8 * r4.value + 4 * hw) = w;
+                    });
+                });
+                if (lse && hw == 0) lse[head * g.q_len + qi] = 0.6931471805599453f * (m[QS] + log2f(lsum[QS]));
+            }
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+
+hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, const void* q, double rope_base,
+                                  float2* cs, _Float16* Kr, _Float16* Vt, _Float16* Qr, hipStream_t st)
+{
+    if (g.d != kD || g.cur_len < 1 || g.q_len < 1 || g.q_len > g.cur_len) return hipErrorInvalidValue;
+    if (g.key_tiles * kKeyTile < g.cur_len || g.q_pad < g.q_len || g.q_pad % kQPerWave) return hipErrorInvalidValue;
+    {
+        long long total = (long long)g.cur_len * (kD / 2);
+        hipLaunchKernelGGL(k_prefill_cs, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, cs, g.cur_len, kD,
+                           rope_base, g.rope);
+    }
+    {
+        long long total = (long long)g.units * g.key_tiles * kKeyTile * (kD / 8);
+        hipLaunchKernelGGL(k_prefill_prep_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, cs, Kr);
+        hipLaunchKernelGGL(k_prefill_prep_v, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, Vt);
+    }
+    {
+        long long total = (long long)g.units * g.G * g.q_pad * (kD / 8);
+        hipLaunchKernelGGL(k_prefill_prep_q, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t*)q, g, cs, Qr);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const _Float16* Qr,
+                                 void* out, float* lse, hipStream_t st)
+{
+    if (g.d != kD || g.q_blocks * kQPerWave != g.q_pad) return hipErrorInvalidValue;
+    const int wgs_per_unit = (g.G * g.q_blocks + 3) / 4;
+    hipLaunchKernelGGL(k_attend_prefill, dim3((unsigned)((long long)g.units * wgs_per_unit)), dim3(256), 0, st, g, Kr,
+                       Vt, Qr, (uint16_t*)out, lse);
+    return hipGetLastError();
+}
+
+}  // namespace freqkv
