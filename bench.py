@@ -135,6 +135,85 @@ def bench_attend(args, wl, dev):
     print(json.dumps(out_json))
 
 
+def bench_prefill(args, wl, dev):
+    """A step = chunk-wise attention of every layer: the chunk that refills the cache after a trigger
+    (window - n_sink - Lc tokens) attends to the full cache (cur_len = window)."""
+    import torch
+    import paper_2505_00570_amd as fk
+    from paper_2505_00570_amd import binding, synth
+
+    k, v = synth.empty_cache(wl, dev)
+    synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
+    L = binding.layout_for(k)
+    _, cp = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    q_len = wl.window - cp.new_len
+    g = torch.Generator(device="cpu").manual_seed(1)
+    q = torch.empty(wl.n_layers, wl.batch, wl.q_heads, q_len, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    for l in range(wl.n_layers):
+        q[l] = (torch.randn(wl.batch, wl.q_heads, q_len, wl.head_dim, generator=g) * 0.5).to(torch.bfloat16).to(dev)
+    out = torch.empty_like(q)
+    _, p = fk.attend_prefill_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, wl.window, q_len)
+    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=dev)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
+    stream = torch.cuda.current_stream()
+
+    def step():
+        fk.attend_prefill(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, wl.window, q_len, wl.rope_base, stream)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import attend_oracle as att
+        cores = min(16, os.cpu_count() or 1)
+        rows = [int(i) for i in __import__("numpy").linspace(0, q_len - 1, 4 * cores)]
+        kk = k[0, 0, 0].cpu().float().double().numpy()
+        vv = v[0, 0, 0].cpu().float().double().numpy()
+        qq = q[0, 0, 0].cpu().float().double().numpy()
+
+        def one(i):
+            pos = wl.window - q_len + i
+            att.attend_decode_head(qq[i], kk, vv, pos + 1, pos, wl.rope_base)
+            return 4.0 * wl.head_dim * (pos + 1)
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            fl = sum(ex.map(one, rows))
+        dtc = time.perf_counter() - t0
+        cpu = {"value": fl / dtc / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+               "sample": f"{len(rows)} query rows of one head of layer 0, {dtc:.1f} s on {cores} threads"}
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fk.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = fk.profile_read()
+    fk.profile_enable(False)
+    mfma_tflops = fk.calibrate_mfma(20000, stream)
+    launches = max(int(prof.launches_attend), 1)
+    ms_kernel = prof.ms_attend / launches
+    flops_launch = p.flops * args.steps / launches
+    achieved = flops_launch / (ms_kernel * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "chunk-wise attention throughput (TFLOP/s, causal flops only)", "value": p.flops / (dt / args.steps) / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "dtype_note": "bf16 cache, queries and output; fp16 MFMA operands, fp32 accumulation and softmax", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: chunk-wise attention, {wl.n_layers} layers x {wl.batch} x {wl.q_heads} query heads / "
+                               f"{wl.n_heads} KV heads x head_dim {wl.head_dim}, {q_len} chunk tokens over {wl.window} cached rows, "
+                               f"rotary base {wl.rope_base:g}", "operator": "attend_prefill"},
+        "ms_prepare_kernels": prof.ms_prepare / max(int(prof.launches_prepare), 1), "ms_attend_kernel": ms_kernel,
+        "roofline": {"bound": "mfma", "kernel": "k_attend_prefill", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None, "ms_per_launch": ms_kernel,
+                     "flops_per_launch": flops_launch, "measured_mfma_loop_tflops": mfma_tflops,
+                     "frac_of_measured_mfma_loop": achieved / mfma_tflops},
+        "cpu_baseline": cpu}))
+
+
 def bench_spectrum(args, wl, dev):
     """A step = one power-spectrum call over every layer's K and V, all `window` cached rows."""
     import torch
@@ -207,6 +286,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attend", action="store_true",
                     help="time decode attention over the full cache (rotary embedding at read time) instead of compression")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time chunk-wise attention: a chunk of window - n_sink - Lc queries over the full cache")
     ap.add_argument("--spectrum", action="store_true",
                     help="time the power-spectrum diagnostic over the full window instead of compression")
     ap.add_argument("--dropping", action="store_true",
@@ -231,6 +312,8 @@ def main():
         return bench_attend(args, wl, dev)
     if args.spectrum:
         return bench_spectrum(args, wl, dev)
+    if args.prefill:
+        return bench_prefill(args, wl, dev)
 
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)

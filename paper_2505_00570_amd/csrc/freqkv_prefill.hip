@@ -47,7 +47,7 @@ constexpr int kKeyTile = 32;       // keys per tile
 constexpr int kQPerWave = 64;      // queries per wave
 constexpr int kTileBytes = kKeyTile * kD * 2;   // one Kr or Vt tile, fp16
 constexpr float kMinusBig = -1.0e30f;
-constexpr float kSlack = 8.0f;     // log2 of the largest un-rescaled softmax weight
+constexpr float kSlack = 14.0f;    // log2 of the largest un-rescaled softmax weight (an fp16 operand: < 2^16)
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -208,7 +208,8 @@ __global__ __launch_bounds__(256, 1)
 void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, const _Float16* __restrict__ Vt,
                       const _Float16* __restrict__ Qr, uint16_t* __restrict__ out, float* __restrict__ lse)
 {
-    __shared__ __attribute__((aligned(1024))) char smem[2][2 * kTileBytes];   // [slot][Kr tile | Vt tile]
+    __shared__ __attribute__((aligned(1024))) char ksm[2][kTileBytes];   // Kr tiles t+1, t+2 (one step ahead)
+    __shared__ __attribute__((aligned(1024))) char vsm[2][kTileBytes];   // Vt tiles t, t+1
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, hw = lane >> 5;
@@ -260,7 +261,11 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     const char* vsrc = (const char*)(Vt + (long long)unit * g.key_tiles * (kKeyTile * kD));
     const int tid16 = threadIdx.x * 16;
 
-    // stage a tile pair through registers into an LDS slot: 16 KiB = 4 x 16 bytes per thread
+    // Tiles travel global -> registers -> LDS, two tiles ahead of the weighted sum and one ahead of the scores:
+    //   step t:  issue loads of tile t+2;  S(t+1) = Kr(t+1) Qr^T;  softmax of S(t);  O^T += Vt(t) P(t)^T;
+    //            Kr(t+2) -> K slot t%2 (its tile t was consumed a step ago);  barrier;  Vt(t+2) -> V slot t%2.
+    // The scores of the next tile are independent of the softmax of this one, so the matrix cores have work
+    // while the vector units do the exponentials.
     u32x4 stage[4];
     auto load_tile = [&](int tile) {
         const char* ks = ksrc + (long long)tile * kTileBytes + tid16;
@@ -270,94 +275,132 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
         stage[2] = *(const u32x4*)vs;
         stage[3] = *(const u32x4*)(vs + 4096);
     };
-    auto store_tile = [&](int slot) {
-        char* d = smem[slot] + tid16;
-        *(u32x4*)d = stage[0];
-        *(u32x4*)(d + 4096) = stage[1];
-        *(u32x4*)(d + kTileBytes) = stage[2];
-        *(u32x4*)(d + kTileBytes + 4096) = stage[3];
+    auto store_k = [&](int slot) {
+        *(u32x4*)(ksm[slot] + tid16) = stage[0];
+        *(u32x4*)(ksm[slot] + tid16 + 4096) = stage[1];
+    };
+    auto store_v = [&](int slot) {
+        *(u32x4*)(vsm[slot] + tid16) = stage[2];
+        *(u32x4*)(vsm[slot] + tid16 + 4096) = stage[3];
+    };
+    auto scores = [&](int slot, f32x16 (&st)[2]) {
+        const char* kt = ksm[slot];
+        static_for<2>([&](auto qs) { static_for<16>([&](auto r) { st[qs.value][r.value] = 0.f; }); });
+        static_for<8>([&](auto s8) {
+            half8 kf = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16);
+            static_for<2>([&](auto qs) {
+                st[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s8.value], st[qs.value], 0, 0, 0);
+            });
+        });
     };
 
-    if (wg_tiles > 0) {
-        load_tile(0);
-        store_tile(0);
+    load_tile(0);
+    store_k(0);
+    store_v(0);
+    if (wg_tiles > 1) {
+        load_tile(1);
+        store_k(1);
+        store_v(1);
     }
     __syncthreads();
 
-    for (int tile = 0; tile < wg_tiles; ++tile) {
-        const int slot = tile & 1;
-        if (tile + 1 < wg_tiles) load_tile(tile + 1);
-
-        if (tile < my_tiles) {
-            const char* kt = smem[slot];
-            const char* vt = smem[slot] + kTileBytes;
-            // ---- S^T = Kr Qr^T : 32 keys x 64 queries, contraction over the 128 channels
-            f32x16 st[2];
-            static_for<2>([&](auto qs) { static_for<16>([&](auto r) { st[qs.value][r.value] = 0.f; }); });
-            static_for<8>([&](auto s) {
-                half8 kf = *(const half8*)(kt + ((s.value * 2 + hw) * kKeyTile + l32) * 16);
-                static_for<2>([&](auto qs) {
-                    st[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s.value], st[qs.value], 0, 0, 0);
+    // Causal mask (tiles that reach past the first query of the wave) and the largest score of each query.
+    auto mask_and_max = [&](int tile, f32x16 (&cur)[2], float (&mx)[2]) {
+        const int key_base = tile * kKeyTile;
+        const bool diag = key_base + kKeyTile - 1 > pos0;
+        static_for<2>([&](auto qs) {
+            constexpr int QS = decltype(qs)::value;
+            const int qpos = pos0 + QS * 32 + l32;
+            if (diag) {
+                static_for<16>([&](auto r) {
+                    constexpr int R = decltype(r)::value;
+                    const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
+                    if (key > qpos) cur[QS][R] = -INFINITY;
                 });
-            });
-            // ---- causal mask (only tiles that reach past the first query of the wave), running softmax
-            const int key_base = tile * kKeyTile;
-            const bool diag = key_base + kKeyTile - 1 > pos0;
-            half8 pf[2][2];         // P^T as second operand of the weighted sum: [query sub-block][k-step]
+            }
+            float v = cur[QS][0];
+            static_for<16>([&](auto r) { v = fmaxf(v, cur[QS][r.value]); });
+            mx[QS] = fmaxf(v, __shfl_xor(v, 32));
+        });
+    };
+
+    f32x16 cur[2], nxt[2];
+    if (my_tiles > 0) scores(0, cur);
+    __syncthreads();          // K slot 0 is overwritten with tile 2 in step 0: every wave must have read tile 0
+
+    // The reference point m of a query's running softmax moves only when a score exceeds it by more than
+    // 2^kSlack (weights up to 2^kSlack are accumulated as they are; any reference point gives the same
+    // quotient).  Moving it rescales the accumulators with vector instructions, which would drag them out of
+    // the accumulation registers of the matrix cores; so the tile loop is split: the inner loop below never
+    // touches the accumulators with vector instructions and leaves, before consuming a tile, when some query
+    // of the wave needs a new reference point; the outer loop moves the reference points and re-enters.
+    int tile = 0;
+    while (tile < wg_tiles) {
+        if (tile < my_tiles) {
+            float mx[2];
+            mask_and_max(tile, cur, mx);
             static_for<2>([&](auto qs) {
                 constexpr int QS = decltype(qs)::value;
-                const int qpos = pos0 + QS * 32 + l32;
-                if (diag) {
-                    static_for<16>([&](auto r) {
-                        constexpr int R = decltype(r)::value;
-                        const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
-                        if (key > qpos) st[QS][R] = -INFINITY;
-                    });
-                }
-                float mx = st[QS][0];
-                static_for<16>([&](auto r) { mx = fmaxf(mx, st[QS][r.value]); });
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // the reference point moves only when a score exceeds it by more than 2^kSlack
-                const bool grow = mx > m[QS] + kSlack;
-                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                    const float mn = grow ? mx : m[QS];
-                    const float f = exp2_fast(m[QS] - mn);
-                    m[QS] = mn;
-                    lsum[QS] *= f;
-                    static_for<4>([&](auto db) {
-                        static_for<16>([&](auto r) { acc[db.value][QS][r.value] *= f; });
-                    });
-                }
-                float ps = 0.f;
-                float pv[16];
-                static_for<16>([&](auto r) {
-                    pv[r.value] = exp2_fast(st[QS][r.value] - m[QS]);
-                    ps += pv[r.value];
-                });
-                ps += __shfl_xor(ps, 32);
-                lsum[QS] += ps;
-                static_for<2>([&](auto t) {
-                    u32x4 w;
-                    static_for<4>([&](auto e) {
-                        w[e.value] = pack_half2(pv[8 * t.value + 2 * e.value], pv[8 * t.value + 2 * e.value + 1]);
-                    });
-                    pf[QS][t.value] = __builtin_bit_cast(half8, w);
-                });
-            });
-            // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys
-            static_for<4>([&](auto db) {
-                static_for<2>([&](auto t) {
-                    half8 vf = *(const half8*)(vt + (((db.value * 2 + t.value) * 2 + hw) * 32 + l32) * 16);
-                    static_for<2>([&](auto qs) {
-                        acc[db.value][qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            vf, pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
-                    });
+                const bool grow = mx[QS] > m[QS] + kSlack;
+                const float mn = grow ? mx[QS] : m[QS];
+                const float f = exp2_fast(m[QS] - mn);
+                m[QS] = mn;
+                lsum[QS] *= f;
+                static_for<4>([&](auto db) {
+                    static_for<16>([&](auto r) { acc[db.value][QS][r.value] *= f; });
                 });
             });
         }
-
-        if (tile + 1 < wg_tiles) store_tile(slot ^ 1);
-        __syncthreads();
+        while (tile < wg_tiles) {
+            const bool mine = tile < my_tiles;
+            if (mine) {
+                float mx[2];
+                mask_and_max(tile, cur, mx);
+                const bool grow = mx[0] > m[0] + kSlack || mx[1] > m[1] + kSlack;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) break;
+            }
+            const int slot = tile & 1;
+            if (tile + 2 < wg_tiles) load_tile(tile + 2);
+            if (mine) {
+                const char* vt = vsm[slot];
+                // ---- scores of the next tile (matrix cores) alongside the exponentials of this one (vector units)
+                if (tile + 1 < my_tiles) scores(slot ^ 1, nxt);
+                half8 pf[2][2];         // P^T as second operand of the weighted sum: [query sub-block][k-step]
+                static_for<2>([&](auto qs) {
+                    constexpr int QS = decltype(qs)::value;
+                    float ps = 0.f;
+                    float pv[16];
+                    static_for<16>([&](auto r) {
+                        pv[r.value] = exp2_fast(cur[QS][r.value] - m[QS]);
+                        ps += pv[r.value];
+                    });
+                    ps += __shfl_xor(ps, 32);
+                    lsum[QS] += ps;
+                    static_for<2>([&](auto t) {
+                        u32x4 w;
+                        static_for<4>([&](auto e) {
+                            w[e.value] = pack_half2(pv[8 * t.value + 2 * e.value], pv[8 * t.value + 2 * e.value + 1]);
+                        });
+                        pf[QS][t.value] = __builtin_bit_cast(half8, w);
+                    });
+                });
+                // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys
+                static_for<4>([&](auto db) {
+                    static_for<2>([&](auto t) {
+                        half8 vf = *(const half8*)(vt + (((db.value * 2 + t.value) * 2 + hw) * 32 + l32) * 16);
+                        static_for<2>([&](auto qs) {
+                            acc[db.value][qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                                vf, pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
+                        });
+                    });
+                });
+                static_for<2>([&](auto qs) { cur[qs.value] = nxt[qs.value]; });
+            }
+            if (tile + 2 < wg_tiles) store_k(slot);
+            __syncthreads();
+            if (tile + 2 < wg_tiles) store_v(slot);
+            ++tile;
+        }
     }
 
     // ---- normalise and store: lane = query, registers = channels 8*(r/4) + 4*hw + r%4 of each block
