@@ -55,7 +55,8 @@ __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_ex
 
 __device__ __forceinline__ uint32_t pack_half2(float a, float b)
 {
-    half2v h = {(_Float16)a, (_Float16)b};
+    f32x2 v = {a, b};
+    half2v h = __builtin_convertvector(v, half2v);      // round to nearest even, one packed conversion
     return __builtin_bit_cast(uint32_t, h);
 }
 
@@ -255,7 +256,7 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
             static_for<16>([&](auto r) { acc[db.value][qs.value][r.value] = 0.f; });
         });
     });
-    float m[2] = {kMinusBig, kMinusBig}, lsum[2] = {0.f, 0.f};     // per query column (lane), both half-waves agree
+    float m[2] = {0.f, 0.f}, lsum[2] = {0.f, 0.f};     // per query column (lane), both half-waves agree
 
     const char* ksrc = (const char*)(Kr + (long long)unit * g.key_tiles * (kKeyTile * kD));
     const char* vsrc = (const char*)(Vt + (long long)unit * g.key_tiles * (kKeyTile * kD));
@@ -283,17 +284,6 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
         *(u32x4*)(vsm[slot] + tid16) = stage[2];
         *(u32x4*)(vsm[slot] + tid16 + 4096) = stage[3];
     };
-    auto scores = [&](int slot, f32x16 (&st)[2]) {
-        const char* kt = ksm[slot];
-        static_for<2>([&](auto qs) { static_for<16>([&](auto r) { st[qs.value][r.value] = 0.f; }); });
-        static_for<8>([&](auto s8) {
-            half8 kf = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16);
-            static_for<2>([&](auto qs) {
-                st[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s8.value], st[qs.value], 0, 0, 0);
-            });
-        });
-    };
-
     load_tile(0);
     store_k(0);
     store_v(0);
@@ -304,97 +294,137 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     }
     __syncthreads();
 
-    // Causal mask (tiles that reach past the first query of the wave) and the largest score of each query.
-    auto mask_and_max = [&](int tile, f32x16 (&cur)[2], float (&mx)[2]) {
+    // Causal mask: tiles that reach past the first query of the wave.
+    auto mask_tile = [&](int tile, f32x16 (&cur)[2]) {
         const int key_base = tile * kKeyTile;
-        const bool diag = key_base + kKeyTile - 1 > pos0;
+        if (key_base + kKeyTile - 1 <= pos0) return;
         static_for<2>([&](auto qs) {
             constexpr int QS = decltype(qs)::value;
             const int qpos = pos0 + QS * 32 + l32;
-            if (diag) {
-                static_for<16>([&](auto r) {
-                    constexpr int R = decltype(r)::value;
-                    const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
-                    if (key > qpos) cur[QS][R] = -INFINITY;
-                });
-            }
-            float v = cur[QS][0];
-            static_for<16>([&](auto r) { v = fmaxf(v, cur[QS][r.value]); });
-            mx[QS] = fmaxf(v, __shfl_xor(v, 32));
+            static_for<16>([&](auto r) {
+                constexpr int R = decltype(r)::value;
+                const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
+                if (key > qpos) cur[QS][R] = -INFINITY;
+            });
         });
     };
 
+    // cur holds S(t) - m: the accumulators of the scores start at minus the query's reference point, so the
+    // exponent needs no subtraction; nxt receives S(t+1) - m during step t.
     f32x16 cur[2], nxt[2];
-    if (my_tiles > 0) scores(0, cur);
+    if (my_tiles > 0) {
+        const char* kt = ksm[0];
+        static_for<2>([&](auto qs) { static_for<16>([&](auto r) { cur[qs.value][r.value] = 0.f; }); });
+        static_for<8>([&](auto s8) {
+            half8 kf = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16);
+            static_for<2>([&](auto qs) {
+                cur[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s8.value], cur[qs.value], 0, 0, 0);
+            });
+        });
+    }
     __syncthreads();          // K slot 0 is overwritten with tile 2 in step 0: every wave must have read tile 0
 
     // The reference point m of a query's running softmax moves only when a score exceeds it by more than
     // 2^kSlack (weights up to 2^kSlack are accumulated as they are; any reference point gives the same
     // quotient).  Moving it rescales the accumulators with vector instructions, which would drag them out of
-    // the accumulation registers of the matrix cores; so the tile loop is split: the inner loop below never
-    // touches the accumulators with vector instructions and leaves, before consuming a tile, when some query
-    // of the wave needs a new reference point; the outer loop moves the reference points and re-enters.
+    // the accumulation registers of the matrix cores; so the tile loop is split: the inner loop never touches
+    // the accumulators with vector instructions and leaves, before consuming a tile, when some query of the
+    // wave needs a new reference point; the outer loop moves the reference points and re-enters.
     int tile = 0;
+    bool first = true;        // the first tile sets the reference points whatever the scores are
     while (tile < wg_tiles) {
         if (tile < my_tiles) {
-            float mx[2];
-            mask_and_max(tile, cur, mx);
+            mask_tile(tile, cur);
             static_for<2>([&](auto qs) {
                 constexpr int QS = decltype(qs)::value;
-                const bool grow = mx[QS] > m[QS] + kSlack;
-                const float mn = grow ? mx[QS] : m[QS];
-                const float f = exp2_fast(m[QS] - mn);
-                m[QS] = mn;
+                float v = cur[QS][0];
+                static_for<16>([&](auto r) { v = fmaxf(v, cur[QS][r.value]); });
+                const float mx = fmaxf(v, __shfl_xor(v, 32));
+                const bool grow = first || mx > kSlack;
+                const float delta = grow ? mx : 0.f;              // the reference point moves up by delta
+                const float f = exp2_fast(-delta);
+                m[QS] += delta;
                 lsum[QS] *= f;
                 static_for<4>([&](auto db) {
                     static_for<16>([&](auto r) { acc[db.value][QS][r.value] *= f; });
                 });
+                static_for<16>([&](auto r) { cur[QS][r.value] -= delta; });   // the pending tile follows
             });
         }
+        first = false;
         while (tile < wg_tiles) {
             const bool mine = tile < my_tiles;
             if (mine) {
-                float mx[2];
-                mask_and_max(tile, cur, mx);
-                const bool grow = mx[0] > m[0] + kSlack || mx[1] > m[1] + kSlack;
-                if (__builtin_amdgcn_ballot_w64(grow) != 0) break;
+                // does any score of this tile exceed its query's reference point by more than the slack?  (the
+                // lanes' own 16 scores suffice for the vote; exact maxima are only needed when it is yes)
+                mask_tile(tile, cur);
+                float v0 = cur[0][0], v1 = cur[1][0];
+                static_for<16>([&](auto r) {
+                    v0 = fmaxf(v0, cur[0][r.value]);
+                    v1 = fmaxf(v1, cur[1][r.value]);
+                });
+                if (__builtin_amdgcn_ballot_w64(fmaxf(v0, v1) > kSlack) != 0) break;
             }
             const int slot = tile & 1;
             if (tile + 2 < wg_tiles) load_tile(tile + 2);
             if (mine) {
+                // Fragments come from LDS a few matrix instructions ahead of their use: Kr(t+1) for the next
+                // scores (past the wave's last tile this is a stale slot; the result is never used), then Vt(t).
+                half8 kf[8], vf[8];
+                const char* kt = ksm[slot ^ 1];
                 const char* vt = vsm[slot];
-                // ---- scores of the next tile (matrix cores) alongside the exponentials of this one (vector units)
-                if (tile + 1 < my_tiles) scores(slot ^ 1, nxt);
-                half8 pf[2][2];         // P^T as second operand of the weighted sum: [query sub-block][k-step]
+                auto read_k = [&](auto s8) { kf[s8.value] = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16); };
+                auto read_v = [&](auto i) { vf[i.value] = *(const half8*)(vt + ((i.value * 2 + hw) * 32 + l32) * 16); };
+                static_for<2>([&](auto s8) { read_k(s8); });
+                // ---- scores of the next tile on the matrix cores, dealt out between the exponentials of this
+                // tile on the vector units: per 16-channel step two matrix instructions and four weights,
+                // packed to fp16 as they are produced
+                static_for<2>([&](auto qs) { static_for<16>([&](auto r) { nxt[qs.value][r.value] = -m[qs.value]; }); });
+                float ps[2] = {0.f, 0.f};
+                u32x4 pw[2][2];         // P^T, the second operand of the weighted sum: [query sub-block][k-step]
+                static_for<8>([&](auto s8) {
+                    constexpr int S8 = decltype(s8)::value;
+                    if constexpr (S8 < 6) {
+                        read_k(IC<S8 + 2>{});
+                    } else {                                   // first k-step of the weighted sum: vf[2*db]
+                        read_v(IC<(S8 - 6) * 4>{});
+                        read_v(IC<(S8 - 6) * 4 + 2>{});
+                    }
+                    static_for<2>([&](auto qs) {
+                        nxt[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[S8], qf[qs.value][S8], nxt[qs.value], 0, 0, 0);
+                    });
+                    static_for<2>([&](auto e) {
+                        constexpr int I = S8 * 4 + 2 * decltype(e)::value;  // (query sub-block, register pair)
+                        constexpr int QS = I / 16, R = I % 16;
+                        const float p0 = exp2_fast(cur[QS][R]), p1 = exp2_fast(cur[QS][R + 1]);
+                        ps[QS] += p0 + p1;
+                        pw[QS][R / 8][(R % 8) / 2] = pack_half2(p0, p1);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                half8 pf[2][2];
                 static_for<2>([&](auto qs) {
                     constexpr int QS = decltype(qs)::value;
-                    float ps = 0.f;
-                    float pv[16];
-                    static_for<16>([&](auto r) {
-                        pv[r.value] = exp2_fast(cur[QS][r.value] - m[QS]);
-                        ps += pv[r.value];
-                    });
-                    ps += __shfl_xor(ps, 32);
-                    lsum[QS] += ps;
-                    static_for<2>([&](auto t) {
-                        u32x4 w;
-                        static_for<4>([&](auto e) {
-                            w[e.value] = pack_half2(pv[8 * t.value + 2 * e.value], pv[8 * t.value + 2 * e.value + 1]);
-                        });
-                        pf[QS][t.value] = __builtin_bit_cast(half8, w);
-                    });
+                    lsum[QS] += ps[QS] + __shfl_xor(ps[QS], 32);
+                    static_for<2>([&](auto t) { pf[QS][t.value] = __builtin_bit_cast(half8, pw[QS][t.value]); });
                 });
-                // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys
-                static_for<4>([&](auto db) {
-                    static_for<2>([&](auto t) {
-                        half8 vf = *(const half8*)(vt + (((db.value * 2 + t.value) * 2 + hw) * 32 + l32) * 16);
+                // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys; k-step outermost so
+                // that dependent accumulations are eight instructions apart
+                static_for<2>([&](auto t) {
+                    static_for<4>([&](auto db) {
+                        if constexpr (decltype(t)::value == 0) read_v(IC<decltype(db)::value * 2 + 1>{});   // second k-step
                         static_for<2>([&](auto qs) {
                             acc[db.value][qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                                vf, pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
+                                vf[db.value * 2 + t.value], pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
                         });
+                        __builtin_amdgcn_sched_barrier(0);
                     });
                 });
                 static_for<2>([&](auto qs) { cur[qs.value] = nxt[qs.value]; });
+                // keep the output accumulators in the accumulation registers across the loop edge: only the
+                // rare reference-point move above may copy them to vector registers
+                asm volatile("" : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[1][0]), "+a"(acc[1][1]),
+                                  "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[3][0]), "+a"(acc[3][1]));
             }
             if (tile + 2 < wg_tiles) store_k(slot);
             __syncthreads();
