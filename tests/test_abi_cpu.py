@@ -267,3 +267,23 @@ def test_compress_ragged_validates_without_gpu():
     lens[1] = 64                                                                      # triggers, but no workspace
     assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 0.5, None) == -3
     assert f(16, 16, C.byref(L), 2, 128, lens, out, 64, 4, 1.5, None) == -1          # ratio
+
+
+def test_prefill_plan():
+    L = _layout()                                     # 32 layers x 8 KV heads x 8192 rows x 128, bf16
+    out = binding.PrefillPlan()
+    rc, p = fk.attend_prefill_plan(L, 32, 8, 128, 8192, 4094)
+    assert rc == 0 and p.key_tiles == 256 and p.query_blocks == 64
+    # causal flops: query i sees cur_len - q_len + i + 1 rows
+    rows = sum(8192 - 4094 + i + 1 for i in range(4094))
+    assert p.flops == 32 * 32 * 4.0 * 128 * rows
+    units = 32 * 8
+    need = 8192 * 64 * 8 + 2 * units * 256 * 32 * 128 * 2 + units * 4 * 4096 * 128 * 2
+    assert need <= p.workspace_bytes <= need + 1024
+    lib = fk.load()
+    call = lambda *a: lib.freqkv_attend_prefill_plan(C.byref(L), *a, C.byref(out))
+    assert call(32, 8, 128, 8192, 0) == -1 and call(32, 8, 128, 8192, 8193) == -1
+    assert call(32, 8, 64, 8192, 100) == -2           # head_dim 128 only
+    assert call(33, 8, 128, 8192, 100) == -1
+    L.dtype = fk.F32
+    assert call(32, 8, 128, 8192, 100) == -2          # bf16 only
