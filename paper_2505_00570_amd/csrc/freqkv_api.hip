@@ -3,6 +3,7 @@
 #include "freqkv.h"
 #include "freqkv_internal.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -289,7 +290,7 @@ freqkv_status_t get_rope_table(int d, double base, hipStream_t st, RopeEntry** o
 
 // ---------------------------------------------------------------- profiling
 struct ProfSpan { hipEvent_t a, b; int kind; };
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
 std::vector<ProfSpan> g_prof_spans;
 freqkv_profile_t g_prof_acc;
 
@@ -300,6 +301,11 @@ hipError_t prof_begin(hipStream_t st, int kind, ProfSpan* sp)
     hipError_t e = hipEventCreate(&sp->a);
     if (e == hipSuccess) e = hipEventCreate(&sp->b);
     if (e == hipSuccess) e = hipEventRecord(sp->a, st);
+    if (e != hipSuccess) {                       // nothing half-made is left behind
+        if (sp->a) (void)hipEventDestroy(sp->a);
+        if (sp->b) (void)hipEventDestroy(sp->b);
+        sp->a = sp->b = nullptr;
+    }
     return e;
 }
 hipError_t prof_end(hipStream_t st, ProfSpan* sp)
@@ -310,6 +316,22 @@ hipError_t prof_end(hipStream_t st, ProfSpan* sp)
     g_prof_spans.push_back(*sp);
     return e;
 }
+
+// Two timing events, destroyed on every path out of the calibration calls.
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create()
+    {
+        hipError_t e = hipEventCreate(&a);
+        if (e == hipSuccess) e = hipEventCreate(&b);
+        return e;
+    }
+    ~EventPair()
+    {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
 
 }  // namespace
 
@@ -849,18 +871,15 @@ freqkv_status_t freqkv_calibrate_copy(void* dst, const void* src, size_t bytes, 
     if (!dst || !src || !gbs_out || bytes < 16 || (bytes & 15) || repeats < 1) return FREQKV_E_INVALID;
     if (((uintptr_t)dst | (uintptr_t)src) & 15) return FREQKV_E_INVALID;
     hipStream_t st = (hipStream_t)stream;
-    hipEvent_t a, b;
-    HIP_TRY(hipEventCreate(&a));
-    HIP_TRY(hipEventCreate(&b));
+    EventPair ev;
+    HIP_TRY(ev.create());
     HIP_TRY(launch_calib_copy(dst, src, bytes, st));             // warm-up
-    HIP_TRY(hipEventRecord(a, st));
+    HIP_TRY(hipEventRecord(ev.a, st));
     for (int i = 0; i < repeats; ++i) HIP_TRY(launch_calib_copy(dst, src, bytes, st));
-    HIP_TRY(hipEventRecord(b, st));
-    HIP_TRY(hipEventSynchronize(b));
+    HIP_TRY(hipEventRecord(ev.b, st));
+    HIP_TRY(hipEventSynchronize(ev.b));
     float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, a, b));
-    (void)hipEventDestroy(a);
-    (void)hipEventDestroy(b);
+    HIP_TRY(hipEventElapsedTime(&ms, ev.a, ev.b));
     *gbs_out = 2.0 * (double)bytes * repeats / (ms * 1e-3) / 1e9;     // read + write
     return FREQKV_OK;
 }
@@ -874,20 +893,17 @@ freqkv_status_t freqkv_calibrate_mfma(int iters, void* stream, double* tflops_ou
     HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     float* out = nullptr;
     HIP_TRY(hipMalloc(&out, (size_t)cus * 256 * sizeof(float)));
-    hipEvent_t a, b;
-    hipError_t e = hipEventCreate(&a);
-    if (e == hipSuccess) e = hipEventCreate(&b);
+    EventPair ev;
+    hipError_t e = ev.create();
     if (e == hipSuccess) e = launch_calib_mfma(out, cus, iters / 10 + 1, st);
-    if (e == hipSuccess) e = hipEventRecord(a, st);
+    if (e == hipSuccess) e = hipEventRecord(ev.a, st);
     if (e == hipSuccess) e = launch_calib_mfma(out, cus, iters, st);
-    if (e == hipSuccess) e = hipEventRecord(b, st);
-    if (e == hipSuccess) e = hipEventSynchronize(b);
+    if (e == hipSuccess) e = hipEventRecord(ev.b, st);
+    if (e == hipSuccess) e = hipEventSynchronize(ev.b);
     float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
     (void)hipFree(out);
     if (e != hipSuccess) { set_error("calibrate_mfma", e); return FREQKV_E_HIP; }
-    (void)hipEventDestroy(a);
-    (void)hipEventDestroy(b);
     // one workgroup per CU, 4 waves, 16 MFMAs of 32*32*16 MACs per iteration
     *tflops_out = (double)cus * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e-3) / 1e12;
     return FREQKV_OK;
