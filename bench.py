@@ -214,6 +214,78 @@ def bench_prefill(args, wl, dev):
         "cpu_baseline": cpu}))
 
 
+def bench_e2e(args, wl, dev):
+    """A step = the whole iterative prefill of Sec. 3.4 on the KV side: the first window of tokens attends
+    causally, then, until total_tokens have streamed through, one compression trigger, the next chunk appended
+    behind the compacted rows (a device copy of pre-generated synthetic K/V), chunk-wise attention."""
+    import torch
+    import paper_2505_00570_amd as fk
+    from paper_2505_00570_amd import binding, synth
+
+    k, v = synth.empty_cache(wl, dev)
+    src = synth.KVSource(wl, seed=0, device=dev)
+    src.fill(k, v, 0, wl.window)
+    L = binding.layout_for(k)
+    _, cp = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    chunk = wl.window - cp.new_len
+    ck, cv = k[:, :, :, cp.new_len:].clone(), v[:, :, :, cp.new_len:].clone()       # the chunk that is re-appended
+    q = (torch.randn(wl.n_layers, wl.batch, wl.q_heads, wl.window, wl.head_dim, device=dev) * 0.5).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    _, pp = fk.attend_prefill_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, wl.window, wl.window)
+    ws = torch.empty(max(pp.workspace_bytes, cp.workspace_bytes), dtype=torch.uint8, device=dev)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), ws.numel()
+    stream = torch.cuda.current_stream()
+    H, d, W = wl.n_heads, wl.head_dim, wl.window
+
+    def step():
+        triggers = chunks = 0
+        flops = 0.0
+        fk.attend_prefill(q, k, v, out, None, L, wl.q_heads, H, d, W, W, wl.rope_base, stream)
+        flops += fk.attend_prefill_plan(L, wl.q_heads, H, d, W, W)[1].flops
+        done = W
+        while done < wl.total_tokens:
+            fk.compress(k, v, L, H, d, W, W, wl.n_sink, wl.retain_ratio, stream)
+            triggers += 1
+            n = min(chunk, wl.total_tokens - done)
+            k[:, :, :, cp.new_len:cp.new_len + n].copy_(ck[:, :, :, :n])
+            v[:, :, :, cp.new_len:cp.new_len + n].copy_(cv[:, :, :, :n])
+            qn = q[:, :, :, :n] if n == W else q.view(-1)[: wl.n_layers * wl.batch * wl.q_heads * n * d].view(
+                wl.n_layers, wl.batch, wl.q_heads, n, d)
+            on = out.view(-1)[: qn.numel()].view(qn.shape)
+            fk.attend_prefill(qn, k, v, on, None, L, wl.q_heads, H, d, cp.new_len + n, n, wl.rope_base, stream)
+            flops += fk.attend_prefill_plan(L, wl.q_heads, H, d, cp.new_len + n, n)[1].flops
+            chunks += 1
+            done += n
+        return triggers, chunks, flops
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fk.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        triggers, chunks, flops = step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    prof = fk.profile_read()
+    fk.profile_enable(False)
+    ms_compress = (prof.ms_contract + prof.ms_tail) / args.steps
+    ms_attend = prof.ms_attend / args.steps
+    ms_prepare = prof.ms_prepare / args.steps
+    print(json.dumps({
+        "metric": "iterative prefill, KV-side path (tokens/s)", "value": wl.total_tokens * wl.batch / dt, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.total_tokens} tokens through a window of {W} ({wl.n_layers} layers, "
+                               f"{wl.q_heads}/{H} heads, head_dim {d}): {triggers} compression triggers, "
+                               f"{chunks + 1} chunk attentions", "operator": "e2e"},
+        "ms_attention_kernels": ms_attend, "ms_contraction_and_tail_kernels": ms_compress,
+        "ms_prepare_kernels_both_paths": ms_prepare,
+        "compression_share_of_gpu_time": (ms_compress + 0.0) / max(ms_attend + ms_compress + ms_prepare, 1e-9),
+        "attention_tflops": flops / (ms_attend * 1e-3) / 1e12,
+        "roofline": None, "cpu_baseline": None}))
+
+
 def bench_spectrum(args, wl, dev):
     """A step = one power-spectrum call over every layer's K and V, all `window` cached rows."""
     import torch
@@ -288,6 +360,8 @@ def main():
                     help="time decode attention over the full cache (rotary embedding at read time) instead of compression")
     ap.add_argument("--prefill", action="store_true",
                     help="time chunk-wise attention: a chunk of window - n_sink - Lc queries over the full cache")
+    ap.add_argument("--e2e", action="store_true",
+                    help="stream the workload's total_tokens through the cache: chunk attention + compression triggers")
     ap.add_argument("--spectrum", action="store_true",
                     help="time the power-spectrum diagnostic over the full window instead of compression")
     ap.add_argument("--dropping", action="store_true",
@@ -314,6 +388,8 @@ def main():
         return bench_spectrum(args, wl, dev)
     if args.prefill:
         return bench_prefill(args, wl, dev)
+    if args.e2e:
+        return bench_e2e(args, wl, dev)
 
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)
