@@ -356,6 +356,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the workload's layer count (0: keep)")
     ap.add_argument("--attend", action="store_true",
                     help="time decode attention over the full cache (rotary embedding at read time) instead of compression")
     ap.add_argument("--prefill", action="store_true",
@@ -382,6 +383,8 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
+    if args.layers > 0:
+        wl = synth.small(wl, n_layers=args.layers)
     if args.attend:
         return bench_attend(args, wl, dev)
     if args.spectrum:

@@ -581,3 +581,51 @@ def test_power_spectrum_errors():
     assert fk.power_spectrum(kf, kf, out, binding.layout_for(kf), 1, 128, 0, 128, check=False) == -2
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+# ------------------------------------------------------------------------------------------
+# HIP graph capture: the library only enqueues kernels on the caller's stream (no allocation, no
+# memset, no synchronisation once the basis and rotary tables exist), so a trigger followed by decode
+# attention can be captured once and replayed
+# ------------------------------------------------------------------------------------------
+
+def test_graph_capture_of_trigger_and_attention():
+    wl = synth.small(synth.WORKLOADS["llama3_8b_128k"], n_layers=2, n_heads=2, n_q_heads=8, window=516)
+    k0, v0 = _mk(wl, seed=17)
+    k, v = k0.clone(), v0.clone()
+    q = synth.queries(wl, 17, DEV)
+    L = binding.layout_for(k)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    _, ap = fk.attend_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len)
+    ws = torch.empty(max(p.workspace_bytes, ap.workspace_bytes), dtype=torch.uint8, device=DEV)
+    L.workspace, L.workspace_bytes = ws.data_ptr(), ws.numel()
+    out = torch.zeros_like(q)
+
+    def work(stream):
+        k.copy_(k0)
+        v.copy_(v0)
+        fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, stream)
+        fk.attend_decode(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len, -1, wl.rope_base, stream)
+
+    # eager reference (also builds the cached basis and rotary tables: the only allocations the library makes)
+    work(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    k_ref, v_ref, out_ref = k.clone(), v.clone(), out.clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        work(side)                                    # warm-up on the capturing stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            work(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(4):
+        k.zero_(); v.zero_(); out.zero_()             # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(k[:, :, :, :p.new_len], k_ref[:, :, :, :p.new_len]), i
+        assert torch.equal(v[:, :, :, :p.new_len], v_ref[:, :, :, :p.new_len]), i
+        assert torch.equal(out, out_ref), i
