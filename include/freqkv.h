@@ -59,6 +59,11 @@ typedef enum {
                                          coefficients of the n-point DCT are kept and handed, in order, to the
                                          Lc-point inverse; everything else as the default.  Not with DROPPING */
 
+#define FREQKV_FLAG_SINGLE_FOLD 0x8u  /* never use the two-level even/odd fold (default: spans of 6144 rows or more
+                                         that are a multiple of 4, with an even retained length) */
+#define FREQKV_FLAG_TWO_LEVEL_FOLD 0x10u /* use the two-level fold wherever it applies (span a multiple of 4, even
+                                         retained length), also below 6144 rows.  Not with SINGLE_FOLD */
+
 /*
  * Memory description of the cache ("layout"): everything the scalar arguments of
  * freqkv_compress do not say.  One head-tensor is the [token][dim] matrix of one
@@ -96,7 +101,8 @@ typedef struct freqkv_plan {
     int32_t retained_len;       /* Lc = clamp(floor(retain_ratio*n + 1e-9), 1, n)                */
     int32_t new_len;            /* cache length after the call: n_sink + Lc + (cur_len - window) */
     int32_t head_tensors;       /* 2 * n_layers * batch * n_heads                                */
-    int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA, 4 dropping (row moves only) */
+    int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA,
+                                   4 dropping (row moves only), 5 two-level folded fp16-MFMA */
     int32_t reserved;
     size_t  workspace_bytes;    /* scratch for all head-tensors in one pass (fastest)            */
     size_t  workspace_min_bytes;/* smallest scratch accepted (one (layer,K|V) slab per pass)     */

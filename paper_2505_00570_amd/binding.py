@@ -17,6 +17,8 @@ BF16, F32 = 0, 1
 FLAG_NO_RESCALE = 0x1
 FLAG_DROPPING = 0x2
 FLAG_RETAIN_HIGH = 0x4
+FLAG_SINGLE_FOLD = 0x8
+FLAG_TWO_LEVEL_FOLD = 0x10
 
 OK, NOOP = 0, 1
 E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_HIP, E_ALLOC = -1, -2, -3, -4, -5

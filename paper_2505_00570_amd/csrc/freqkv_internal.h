@@ -34,6 +34,11 @@ struct Geom {
     int high;            // 0: the Lc lowest coefficients are kept, 1: the highest (ablation variant),
                          // 2: forward transform only, all n coefficients (power spectrum)
     float spec_scale;    // power spectrum: 1 / (batch * head_dim)
+    // two-level fold (l2 != 0): this Geom describes one of its two launches
+    int l2;              // 0: not used, 1: even part (folded again, n = n0/2, Lc = Lc0/2), 2: odd part (plain)
+    int n0, Lc0;         // span and retained length of the full problem
+    int H;               // n0/4 rounded up to a pipeline stage: half the contraction length of the odd part
+    const float* ebuf;   // odd part: fp32 even part E[head-tensor][Lc0/2][d] written by the first launch
     int Kh;              // contraction length: n/2 (fold) or n
     int Kpad;            // Kh rounded up to kKStage
     int nkstages;        // Kpad / kKStage
@@ -45,7 +50,7 @@ struct Geom {
     long long tap_slab0; // index of this pass's first slab in the caller's [2][n_layers] order
 };
 
-enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4 };
+enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4, kFold2F16 = 5 };
 
 // ---- basis construction (fp64 closed form, rounded once) -------------------------
 // G: [Kpad/8][Grows][8] fp16.  Folded: rows [0,Mpad) even part, rows [Mpad,2Mpad) odd part.
@@ -55,9 +60,12 @@ hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hip
 
 // ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
-// spec != 0: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (accumulated with atomics)
+// mode 0: rows into the cache; 1: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (atomics);
+// 2: even part of the two-level fold, fp32 rows into tap only; 3: odd part, combined with g.ebuf into the cache
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
-                               const _Float16* ws, float* tap, int spec, hipStream_t st);
+                               const _Float16* ws, float* tap, int mode, hipStream_t st);
+// two-level fold: gA = geometry of the even-part launch; wsA folded layout (xee | xeo), wsB plain layout (xo)
+hipError_t launch_prepare_bf16_l2(const SlabTable& tab, const Geom& gA, _Float16* wsA, _Float16* wsB, hipStream_t st);
 hipError_t launch_fill_zero(float* p, size_t count, hipStream_t st);
 
 // ---- fp32 cache ------------------------------------------------------------------------

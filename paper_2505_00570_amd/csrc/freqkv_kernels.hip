@@ -11,7 +11,15 @@
 //     xe_j = x_j + x_{n-1-j},  xo_j = x_j - x_{n-1-j}           (j < n/2)
 //     E = Ge xe,  O = Go xo,   Ge/Go[m][j] = (M[m][j] +/- M[Lc-1-m][j]) / 2   (m < Lc/2)
 //     y_m = E_m + O_m,         y_{Lc-1-m} = E_m - O_m
-// which halves the multiply-adds.  The kernels below build Ge/Go (or M), fold and
+// which halves the multiply-adds.  Ge is, up to a factor, the same operator for the half-size problem
+// (the even-indexed coefficients of an n-point DCT are the n/2-point DCT of xe), hence centro-symmetric
+// itself: when n/2 is even the even part folds once more,
+//     xee_j = xe_j + xe_{n/2-1-j},  xeo_j = xe_j - xe_{n/2-1-j}     (j < n/4)
+//     EE = Gee xee,  EO = Geo xeo,  Gee/Geo[m][j] = (Ge[m][j] +/- Ge[Lc/2-1-m][j]) / 2
+//     E_m = EE_m + EO_m,  E_{Lc/2-1-m} = EE_m - EO_m                (m < ceil(Lc/4))
+// and the multiply-adds drop to 3/8 of the dense count ("two-level" variant: one launch for E into an
+// fp32 buffer, one for O that adds and subtracts E on its way into the cache).
+// The kernels below build Ge/Go (or M), fold and
 // convert the span into an MFMA-ready fp16 workspace, and contract on the matrix
 // cores with fp32 accumulation, writing the Lc rows straight into the cache.
 #include "freqkv_internal.h"
@@ -21,6 +29,7 @@ namespace freqkv {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
@@ -132,7 +141,33 @@ __global__ void k_basis_f16(_Float16* __restrict__ G, Geom g, double scale)
     for (int i = 0; i < 8; ++i) {
         int j = kg * 8 + i;
         double v = 0.0;
-        if (m < g.Mh && j < g.Kh && g.high == 2) {
+        if (g.l2 != 0) {
+            // two-level fold.  Ge/Go of the full problem (n0 -> Lc0): (M[m][j] +/- M[Lc0-1-m][j]) / 2.
+            const int band = g.high;
+            auto Ge = [&](int mm, int jj) {
+                return 0.5 * (operator_entry(mm, jj, g.n0, g.Lc0, scale, band) +
+                              operator_entry(g.Lc0 - 1 - mm, jj, g.n0, g.Lc0, scale, band));
+            };
+            auto Go = [&](int mm, int jj) {
+                return 0.5 * (operator_entry(mm, jj, g.n0, g.Lc0, scale, band) -
+                              operator_entry(g.Lc0 - 1 - mm, jj, g.n0, g.Lc0, scale, band));
+            };
+            const int L2 = g.Lc0 / 2, n2 = g.n0 / 2, n4 = g.n0 / 4;
+            if (g.l2 == 1) {            // even part, folded again: rows m < ceil(L2/2), columns j < n/4
+                if (m < g.Mh && j < n4) {
+                    double a = Ge(m, j), b = Ge(L2 - 1 - m, j);
+                    v = parity ? 0.5 * (a - b) : 0.5 * (a + b);
+                }
+            } else {                    // odd part, plain; columns in the order the span is laid out:
+                                        // positions [0, H) hold j, positions [H, 2H) hold n/2-1-j  (j < n/4)
+                if (m < L2) {
+                    int jo = -1;
+                    if (j < g.H) { if (j < n4) jo = j; }
+                    else if (j - g.H < n4) jo = n2 - 1 - (j - g.H);
+                    if (jo >= 0) v = Go(m, jo);
+                }
+            }
+        } else if (m < g.Mh && j < g.Kh && g.high == 2) {
             // forward transform only (power spectrum): the even-indexed rows act on the symmetric part of
             // the span and the odd-indexed rows on the antisymmetric part, so the fold needs no mixing
             v = dct_entry(g.fold ? 2 * m + parity : m, j, g.n);
@@ -231,6 +266,70 @@ __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Fl
     }
 }
 
+// Two-level fold: one thread takes 8 quarter positions j of 2 adjacent channels, reads the four rows
+// j, n/2-1-j, n/2+j, n-1-j and writes
+//   wsA (folded layout, stage ks): parity 0  xee_j = x_j + x_{n/2-1-j} + x_{n/2+j} + x_{n-1-j}
+//                                  parity 1  xeo_j = x_j - x_{n/2-1-j} - x_{n/2+j} + x_{n-1-j}
+//   wsB (plain layout): stage ks          xo_j         = x_j - x_{n-1-j}
+//                       stage nksA + ks   xo_{n/2-1-j} = x_{n/2-1-j} - x_{n/2+j}
+// g: the geometry of the even-part launch (Kh = n/4, nkstages = nksA).
+__global__ __launch_bounds__(256) void k_prepare_bf16_l2(SlabTable tab, Geom g, _Float16* __restrict__ wsA,
+                                                         _Float16* __restrict__ wsB)
+{
+    const int ct   = blockIdx.x;
+    const int ks   = blockIdx.y;
+    const int kg   = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int col  = lane * 2;
+    const int vcol = ct * kColTile + col;
+    const int j0   = (ks * 4 + kg) * 8;
+    const int n = g.n0, n2 = n / 2, n4 = n / 4;
+
+    const bool colok = vcol < g.ncols;
+    const char* base = colok ? column_base(tab, g, vcol, 2, nullptr) : nullptr;
+    const long long rowb = g.stride_token * 2;
+    half8 ee0, ee1, eo0, eo1, od0, od1, om0, om1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int j = j0 + i;
+        const bool ok = colok && j < n4;
+        uint32_t a = 0u, b = 0u, c = 0u, d = 0u;
+        if (ok) {
+            a = *(const uint32_t*)(base + (long long)(g.S + j) * rowb);
+            b = *(const uint32_t*)(base + (long long)(g.S + n2 - 1 - j) * rowb);
+            c = *(const uint32_t*)(base + (long long)(g.S + n2 + j) * rowb);
+            d = *(const uint32_t*)(base + (long long)(g.S + n - 1 - j) * rowb);
+        }
+        const float a0 = bf16_to_f32(a & 0xffffu), a1 = bf16_to_f32(a >> 16);
+        const float b0 = bf16_to_f32(b & 0xffffu), b1 = bf16_to_f32(b >> 16);
+        const float c0 = bf16_to_f32(c & 0xffffu), c1 = bf16_to_f32(c >> 16);
+        const float d0 = bf16_to_f32(d & 0xffffu), d1 = bf16_to_f32(d >> 16);
+        ee0[i] = (_Float16)((a0 + d0) + (b0 + c0)); ee1[i] = (_Float16)((a1 + d1) + (b1 + c1));
+        eo0[i] = (_Float16)((a0 + d0) - (b0 + c0)); eo1[i] = (_Float16)((a1 + d1) - (b1 + c1));
+        od0[i] = (_Float16)(a0 - d0);               od1[i] = (_Float16)(a1 - d1);
+        om0[i] = (_Float16)(b0 - c0);               om1[i] = (_Float16)(b1 - c1);
+    }
+    half8* wa = (half8*)wsA;
+    half8* wb = (half8*)wsB;
+    const size_t stA = ((size_t)ct * g.nkstages + ks) * 2;
+    const size_t ge = ((stA + 0) * 4 + kg) * kColTile + col;
+    const size_t go = ((stA + 1) * 4 + kg) * kColTile + col;
+    wa[ge] = ee0; wa[ge + 1] = ee1;
+    wa[go] = eo0; wa[go + 1] = eo1;
+    const size_t sd = (((size_t)ct * (2 * g.nkstages) + ks) * 4 + kg) * kColTile + col;
+    const size_t sm = (((size_t)ct * (2 * g.nkstages) + g.nkstages + ks) * 4 + kg) * kColTile + col;
+    wb[sd] = od0; wb[sd + 1] = od1;
+    wb[sm] = om0; wb[sm + 1] = om1;
+}
+
+hipError_t launch_prepare_bf16_l2(const SlabTable& tab, const Geom& gA, _Float16* wsA, _Float16* wsB, hipStream_t st)
+{
+    if (gA.l2 != 1 || !gA.fold || gA.n0 % 4) return hipErrorInvalidValue;
+    dim3 grid(gA.ncoltiles, gA.nkstages);
+    hipLaunchKernelGGL(k_prepare_bf16_l2, grid, dim3(256), 0, st, tab, gA, wsA, wsB);
+    return hipGetLastError();
+}
+
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st)
 {
     dim3 grid(g.ncoltiles, g.nkstages);
@@ -261,9 +360,14 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// SPEC: instead of writing rows into the cache, add the squared results, summed over the 8 channels of an
-// item and scaled by g.spec_scale, to the spectrum line of the item's head: tap[(slab, head)][coefficient].
-template <bool FOLD, int NW, bool SPEC>
+// MODE 0: rows into the cache (and the optional fp32 tap).
+// MODE 1 (spectrum): add the squared results, summed over the 8 channels of an item and scaled by
+//         g.spec_scale, to the spectrum line of the item's head: tap[(slab, head)][coefficient].
+// MODE 2 (even part of the two-level fold): results only into tap, which is then the fp32 buffer
+//         E[head-tensor][Lc][d] of this (half-size) problem; the cache is not written.
+// MODE 3 (odd part of the two-level fold, plain operator): row m of the result is O_m; with E_m from
+//         g.ebuf, cache row m gets E+O and row Lc0-1-m gets E-O (tap likewise, full-size layout).
+template <bool FOLD, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom g,
                                                          const _Float16* __restrict__ G,
                                                          const _Float16* __restrict__ ws,
@@ -455,14 +559,18 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     const bool col_ok = vcol < g.ncols;
     char* base = nullptr;
     float* tp = nullptr;
+    const float* ep = nullptr;      // MODE 3: the even part of this thread's columns
     if (col_ok) {
         int ht;
         base = column_base(tab, g, vcol, 2, &ht);
         const int c = vcol - ht * g.d;
-        if constexpr (SPEC) {
+        if constexpr (MODE == 1) {
             const int slab = ht / g.hts_per_slab;
             const int h = (ht - slab * g.hts_per_slab) % g.n_heads;
             tp = tap + ((g.tap_slab0 + slab) * (long long)g.n_heads + h) * g.Lc;
+        } else if constexpr (MODE == 3) {
+            if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc0) * g.d + c;
+            ep = g.ebuf + ((long long)ht * g.Lc) * g.d + c;          // the buffer belongs to this pass alone
         } else {
             if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c;
         }
@@ -480,7 +588,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
         for (int it = 0; it < ITEMS / NT; ++it) {
             const int item = threadIdx.x + it * NT;
             const int row = (item >> 4) & 31, w = item >> 9;
-            if constexpr (SPEC) {
+            if constexpr (MODE == 1) {
                 // Power spectrum: squares of the item's 8 channels; E is coefficient 2*rh and O coefficient
                 // 2*rh+1 (folded), or the row itself (plain).  No lane leaves early, so the 16 lanes that
                 // hold one row can be summed with lane exchanges when they all belong to one head
@@ -535,6 +643,28 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                 row_a = mt * kRowsPlain + w * WROWS + MB * 32 + row;
                 if (row_a >= g.Mh) continue;
             }
+            if constexpr (MODE == 2) {
+                // even part of the two-level fold: fp32 rows of E only
+#pragma unroll
+                for (int i = 0; i < 8; ++i) tp[(long long)row_a * g.d + i] = va[i];
+                if constexpr (FOLD) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) tp[(long long)row_b * g.d + i] = vb[i];
+                }
+                continue;
+            }
+            if constexpr (MODE == 3) {
+                // va = O_m; y_m = E_m + O_m, y_{Lc0-1-m} = E_m - O_m
+                row_b = g.Lc0 - 1 - row_a;
+                const f32x4 e0 = *(const f32x4*)(ep + (long long)row_a * g.d);
+                const f32x4 e1 = *(const f32x4*)(ep + (long long)row_a * g.d + 4);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float e = i < 4 ? e0[i & 3] : e1[i & 3];
+                    vb[i] = e - va[i];
+                    va[i] = e + va[i];
+                }
+            }
             u32x4 pk;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -544,7 +674,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
 #pragma unroll
                 for (int i = 0; i < 8; ++i) tp[(long long)row_a * g.d + i] = va[i];
             }
-            if (FOLD) {
+            if (FOLD || MODE == 3) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     pk[i] = pack_bf16x2(vb[2 * i], vb[2 * i + 1]);
@@ -573,19 +703,33 @@ hipError_t launch_fill_zero(float* p, size_t count, hipStream_t st)
 }
 
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
-                               const _Float16* ws, float* tap, int spec, hipStream_t st)
+                               const _Float16* ws, float* tap, int mode, hipStream_t st)
 {
     dim3 grid((unsigned)g.ncoltiles * (unsigned)g.nmtiles);
     // Four waves (one per SIMD, 128x128 accumulators each).  Eight waves of 64x128 are correct too but
     // measured 2.99 ms against 2.16 ms on the 8188 -> 4094 trigger: twice the LDS fragment traffic.
     constexpr int NW = 4;
-    if (spec) {
-        if (!tap) return hipErrorInvalidValue;
-        if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, true>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
-        else        hipLaunchKernelGGL((k_contract_f16<false, NW, true>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
-    } else {
-        if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, false>),  grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
-        else        hipLaunchKernelGGL((k_contract_f16<false, NW, false>), grid, dim3(NW * 64), 0, st, tab, g, G, ws, tap);
+    const dim3 block(NW * 64);
+    switch (mode) {
+        case 0:
+            if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, 0>),  grid, block, 0, st, tab, g, G, ws, tap);
+            else        hipLaunchKernelGGL((k_contract_f16<false, NW, 0>), grid, block, 0, st, tab, g, G, ws, tap);
+            break;
+        case 1:
+            if (!tap) return hipErrorInvalidValue;
+            if (g.fold) hipLaunchKernelGGL((k_contract_f16<true, NW, 1>),  grid, block, 0, st, tab, g, G, ws, tap);
+            else        hipLaunchKernelGGL((k_contract_f16<false, NW, 1>), grid, block, 0, st, tab, g, G, ws, tap);
+            break;
+        case 2:
+            if (!tap || !g.fold) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((k_contract_f16<true, NW, 2>), grid, block, 0, st, tab, g, G, ws, tap);
+            break;
+        case 3:
+            if (!g.ebuf || g.fold || (g.d % 8)) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((k_contract_f16<false, NW, 3>), grid, block, 0, st, tab, g, G, ws, tap);
+            break;
+        default:
+            return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }

@@ -79,12 +79,19 @@ def test_plan_matches_paper_integers():
     assert p.head_tensors == 2 * 32 * 32
     # LLaMA-3 window
     rc, p = fk.plan(_layout(), 8, 128, 8192, 8192, 4, 0.5)
-    assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 1)
+    assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 5)
     assert p.flops_dense == pytest.approx(2.0 * 4094 * 8188 * 128 * 512)
-    assert p.flops_executed == pytest.approx(p.flops_dense / 2)
+    assert p.flops_executed == pytest.approx(p.flops_dense * 3 / 8)       # two-level even/odd fold
     assert p.bytes_algorithmic == pytest.approx((8188 + 4094) * 128 * 2 * 512)
     assert p.workspace_min_bytes <= p.workspace_bytes
-    assert p.basis_bytes == 2 * 2048 * 4096 * 2
+    # even part: 2 x 1024 rows x 2048 columns, odd part: 2048 rows x 4096 columns, fp16
+    assert p.basis_bytes == 2 * 1024 * 2048 * 2 + 2048 * 4096 * 2
+    # the one-level fold on request
+    L1 = _layout()
+    L1.flags = fk.FLAG_SINGLE_FOLD
+    rc, p1 = fk.plan(L1, 8, 128, 8192, 8192, 4, 0.5)
+    assert p1.variant == 1 and p1.flops_executed == pytest.approx(p1.flops_dense / 2)
+    assert p1.basis_bytes == 2 * 2048 * 4096 * 2
 
 
 @pytest.mark.parametrize("window,sink,ratio,cur", [(4096, 4, 0.5, 4096), (4096, 0, 0.25, 5000), (512, 4, 0.5, 512),
@@ -98,6 +105,8 @@ def test_plan_agrees_with_oracle_rules(window, sink, ratio, cur):
     assert p.new_len == orc.new_len(cur, window, sink, ratio)
     if ratio == 1.0:
         assert p.variant == 0 and p.workspace_bytes == 0
+    elif (window - sink) % 4 == 0 and p.retained_len % 2 == 0 and window - sink >= 6144:
+        assert p.variant == 5
     elif (window - sink) % 2 == 0 and p.retained_len % 2 == 0:
         assert p.variant == 1
     else:

@@ -128,6 +128,31 @@ SMALL = [
     (1, 1, 2, 128, 600, 2, 0.01),    # ratio 0.01 -> Lc = 5 (odd -> plain)
 ]
 
+# the two-level fold (default only for long spans), forced on small shapes
+TWO_LEVEL = [
+    (1, 1, 2, 128, 512, 4, 0.5),     # an odd half: n = 508, Lc = 254, Lc/2 = 127 (a middle row)
+    (2, 1, 1, 128, 64, 4, 0.5),      # n = 60, Lc/2 = 15: one stage, almost empty tiles
+    (1, 1, 1, 128, 2052, 4, 0.75),   # n = 2048, Lc = 1536: rows of the odd part span two tiles
+    (1, 2, 3, 64, 516, 4, 0.5),      # head_dim 64
+    (1, 1, 5, 96, 260, 4, 0.5),      # head_dim 96: column tiles straddle heads
+    (2, 1, 3, 128, 700, 4, 0.5),     # n = 696, Lc/2 = 174
+    (1, 1, 2, 128, 1300, 4, 0.5),    # n = 1296: the even part spans two row tiles
+]
+
+
+@pytest.mark.parametrize("cfg", TWO_LEVEL, ids=[str(c) for c in TWO_LEVEL])
+def test_bf16_two_level_fold(cfg):
+    layers, batch, heads, d, window, sink, ratio = cfg
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=layers, batch=batch, n_heads=heads, head_dim=d,
+                     window=window, n_sink=sink, retain_ratio=ratio)
+    _say(f"bf16 two-level {cfg}")
+    k, v = _mk(wl, seed=window + d, capacity=window + 7, cur_len=window + 5)
+    k0, v0 = k.cpu().clone(), v.cpu().clone()
+    rc, p, tap = _run(k, v, wl, window + 5, flags=fk.FLAG_TWO_LEVEL_FOLD)
+    assert rc == 0 and p.variant == 5
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, window + 5, TOL_BF16)
+
+
 
 @pytest.mark.parametrize("cfg", SMALL, ids=[str(c) for c in SMALL])
 def test_bf16_small_full(cfg):
@@ -508,6 +533,25 @@ def test_retain_high_variant(window, sink, ratio, extra, dtype):
     _, _, tap_low = _run(k2, v2, wl, cur)
     ref_low = orc.compress_head(f64(k0[0, 0, 0, :cur]), cur, window, sink, ratio)[S:S + lc]
     assert rel_err(f64(tap_low[0, 0, 0, 0].cpu()), ref_low) <= (TOL_BF16 if dtype == torch.bfloat16 else TOL_F32)
+
+
+def test_single_fold_flag_matches_two_level_fold():
+    """Same operator through the one-level fold (on request) and the two-level fold (default where the span is
+    a multiple of 4): both within the tolerance of the oracle, and close to each other."""
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=1, batch=2, n_heads=3, window=1028)
+    k, v = _mk(wl, seed=8)
+    k1, v1 = k.clone(), v.clone()
+    k0 = k.cpu().clone()
+    rc, p, tap = _run(k, v, wl, wl.window, flags=fk.FLAG_TWO_LEVEL_FOLD)
+    rc1, p1, tap1 = _run(k1, v1, wl, wl.window, flags=fk.FLAG_SINGLE_FOLD)
+    assert (p.variant, p1.variant) == (5, 1)
+    assert p.flops_executed == pytest.approx(0.75 * p1.flops_executed)
+    S, lc = wl.n_sink, p.retained_len
+    for h in range(wl.n_heads):
+        ref = orc.compress_head(f64(k0[0, 1, h]), wl.window, wl.window, S, wl.retain_ratio)[S:S + lc]
+        assert rel_err(f64(tap[0, 0, 1, h].cpu()), ref) <= TOL_BF16
+        assert rel_err(f64(tap1[0, 0, 1, h].cpu()), ref) <= TOL_BF16
+        assert rel_err(f64(tap[0, 0, 1, h].cpu()), f64(tap1[0, 0, 1, h].cpu())) <= TOL_BF16
 
 
 def test_retain_high_rejects_dropping():
