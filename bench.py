@@ -22,9 +22,11 @@ sys.path.insert(0, ROOT)
 
 MFMA_F16_PEAK_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA
 HBM_PEAK_GBS = 8000.0
-# HBM bytes (read + write) of one contraction launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
-# what the same counters read for the library's plain copy kernel (profiles/contract_llama3_8b_128k_pmc.txt).
-TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
+# HBM bytes (read + write) of the contraction of one trigger (two launches with the two-level fold), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by what the same counters read for the library's plain copy
+# kernel (profiles/contract_llama3_8b_128k_pmc.txt).
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.245e5 + 1.065e6) + 1.0 * (5.24e5 + 5.568e5)) * 1024}
+TRAFFIC_BYTES_SINGLE_FOLD = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
 # the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
 ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
 
@@ -455,7 +457,8 @@ def main():
     else:
         roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
-                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                "traffic": (TRAFFIC_BYTES_SINGLE_FOLD if args.single_fold else TRAFFIC_BYTES_PER_LAUNCH).get(args.workload),
+                "launches_per_trigger": 2 if int(p.variant) == 5 else 1,
                 "ms_per_launch": ms_contract, "flops_per_launch": flops_launch,
                 "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops}
 
