@@ -673,3 +673,18 @@ def test_graph_capture_of_trigger_and_attention():
         assert torch.equal(k[:, :, :, :p.new_len], k_ref[:, :, :, :p.new_len]), i
         assert torch.equal(v[:, :, :, :p.new_len], v_ref[:, :, :, :p.new_len]), i
         assert torch.equal(out, out_ref), i
+
+
+def test_two_level_fold_in_several_passes():
+    """A workspace that holds one (layer, K|V) slab at a time: the two-level fold runs slab by slab, its fp32
+    even-part buffer indexed per pass, the optional tap per cache; same bits as the single pass."""
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=3, batch=2, n_heads=2, window=516)
+    k, v = _mk(wl, seed=31, capacity=530, cur_len=523)
+    k1, v1 = k.clone(), v.clone()
+    L = binding.layout_for(k, flags=fk.FLAG_TWO_LEVEL_FOLD)
+    _, p = fk.plan(L, wl.n_heads, wl.head_dim, 523, wl.window, wl.n_sink, wl.retain_ratio)
+    assert p.variant == 5 and p.workspace_min_bytes < p.workspace_bytes
+    rc, _, tap = _run(k, v, wl, 523, flags=fk.FLAG_TWO_LEVEL_FOLD)
+    rc1, _, tap1 = _run(k1, v1, wl, 523, flags=fk.FLAG_TWO_LEVEL_FOLD, ws_bytes=p.workspace_min_bytes)
+    assert rc == 0 and rc1 == 0
+    assert torch.equal(k, k1) and torch.equal(v, v1) and torch.equal(tap, tap1)
