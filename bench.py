@@ -369,6 +369,8 @@ def main():
                     help="time the power-spectrum diagnostic over the full window instead of compression")
     ap.add_argument("--single-fold", action="store_true",
                     help="use the one-level even/odd fold where the two-level fold would be chosen (comparison)")
+    ap.add_argument("--two-level", action="store_true",
+                    help="use the two-level fold wherever it applies, also for spans below its default threshold")
     ap.add_argument("--dropping", action="store_true",
                     help="time the Dropping variant (row moves only): the memcpy-roofline reference of the write-back step")
     args = ap.parse_args()
@@ -401,7 +403,7 @@ def main():
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)
     synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
-    L = binding.layout_for(k, flags=fk.FLAG_DROPPING if args.dropping else (fk.FLAG_SINGLE_FOLD if args.single_fold else 0))
+    L = binding.layout_for(k, flags=fk.FLAG_DROPPING if args.dropping else (fk.FLAG_SINGLE_FOLD if args.single_fold else (fk.FLAG_TWO_LEVEL_FOLD if args.two_level else 0)))
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
     ws = torch.empty(max(p.workspace_bytes, 1 << 30 if args.dropping else 256), dtype=torch.uint8, device=dev)
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes

@@ -59,10 +59,11 @@ typedef enum {
                                          coefficients of the n-point DCT are kept and handed, in order, to the
                                          Lc-point inverse; everything else as the default.  Not with DROPPING */
 
-#define FREQKV_FLAG_SINGLE_FOLD 0x8u  /* never use the two-level even/odd fold (default: spans of 6144 rows or more
-                                         that are a multiple of 4, with an even retained length) */
+#define FREQKV_FLAG_SINGLE_FOLD 0x8u  /* never use the two-level even/odd fold (default: spans of 2048 rows or more
+                                         that are a multiple of 4, with an even retained length, when the cache has
+                                         enough head-tensors to fill the device with the shorter launches) */
 #define FREQKV_FLAG_TWO_LEVEL_FOLD 0x10u /* use the two-level fold wherever it applies (span a multiple of 4, even
-                                         retained length), also below 6144 rows.  Not with SINGLE_FOLD */
+                                         retained length), whatever the sizes.  Not with SINGLE_FOLD */
 
 /*
  * Memory description of the cache ("layout"): everything the scalar arguments of

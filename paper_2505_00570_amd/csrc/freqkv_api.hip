@@ -118,7 +118,7 @@ Geom make_geom_l2(const Shape& sh, const freqkv_layout_t& L, int slabs, int slab
 }
 
 // Workspace slices of the two-level fold for a pass over `slabs` slabs: folded span of the even part,
-// plain span of the odd part, fp32 even part.
+// plain span of the odd part, fp16 even part.
 struct L2Slices { size_t off_b, off_e, total; };
 L2Slices l2_slices(const Shape& sh, int slabs)
 {
@@ -128,7 +128,7 @@ L2Slices l2_slices(const Shape& sh, int slabs)
     L2Slices s;
     s.off_b = (size_t)(ncoltiles * nksA * 2 * 8192);
     s.off_e = s.off_b + (size_t)(ncoltiles * (2 * nksA) * 8192);
-    s.total = s.off_e + (size_t)round_up((long long)slabs * sh.hts_per_slab * (sh.Lc / 2) * sh.d * 4, 256);
+    s.total = s.off_e + (size_t)round_up((long long)slabs * sh.hts_per_slab * (sh.Lc / 2) * sh.d * 2, 256);
     return s;
 }
 
@@ -167,9 +167,13 @@ size_t pass_workspace(const Shape& sh, int slabs)
 }
 
 // The two-level fold saves a quarter of the multiply-adds but runs two shorter launches and moves the even
-// part through an fp32 buffer: measured faster for the 8188-row span (2.07 vs 2.32 ms per trigger of the
-// LLaMA-3 cache) and not for the 4092-row span (2.92 vs 2.87 ms), so it is the default from here on.
-constexpr int kTwoLevelMinSpan = 6144;
+// part through a buffer.  Measured per trigger: 1.96 vs 2.35 ms (8188-row span, 512 head-tensors), 2.66 vs 2.89
+// (4092 rows, 2048 head-tensors), 22.0 vs 24.3 (4092 rows, 16384 head-tensors), but 0.133 vs 0.114 for a single
+// layer of 64 head-tensors, whose even-part launch has only 128 workgroups for 256 compute units.  So it is
+// the default when the span has at least kTwoLevelMinSpan rows and the even-part launch at least
+// kTwoLevelMinTiles workgroups.
+constexpr int kTwoLevelMinSpan = 2048;
+constexpr long long kTwoLevelMinTiles = 512;
 
 freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim, int cur_len, int window,
                             int n_sink, double ratio, Shape* out)
@@ -208,8 +212,13 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     if (sh.Lc == sh.n) sh.variant = kNone;
     else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
-    else if (sh.n % 4 == 0 && sh.Lc % 2 == 0 && !(L->flags & FREQKV_FLAG_SINGLE_FOLD) &&
-             (sh.n >= kTwoLevelMinSpan || (L->flags & FREQKV_FLAG_TWO_LEVEL_FOLD))) sh.variant = kFold2F16;
+    else if (sh.n % 4 == 0 && sh.Lc % 2 == 0 && !(L->flags & FREQKV_FLAG_SINGLE_FOLD)) {
+        // workgroups of the even-part launch over all slabs: column tiles x row tiles of 256 rows per parity
+        const long long coltiles = ((long long)sh.nslabs * hts * head_dim + kColTile - 1) / kColTile;
+        const long long rowtiles = ((sh.Lc / 2 + 1) / 2 + kRowsFold - 1) / kRowsFold;
+        const bool pays = sh.n >= kTwoLevelMinSpan && coltiles * rowtiles >= kTwoLevelMinTiles;
+        sh.variant = (pays || (L->flags & FREQKV_FLAG_TWO_LEVEL_FOLD)) ? kFold2F16 : kFoldF16;
+    }
     else sh.variant = (sh.n % 2 == 0 && sh.Lc % 2 == 0) ? kFoldF16 : kPlainF16;
     *out = sh;
     return FREQKV_OK;
@@ -553,7 +562,7 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
     if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
 
     if (sh.variant == kFold2F16) {
-        // Two-level fold: span -> (xee | xeo), xo;  E = Gee xee +/- Geo xeo into an fp32 buffer;  O = Go xo,
+        // Two-level fold: span -> (xee | xeo), xo;  E = Gee xee +/- Geo xeo into an fp16 buffer;  O = Go xo,
         // combined with E on its way into the cache.
         for (int s0 = 0; s0 < sh.nslabs; s0 += per_pass) {
             int slabs = sh.nslabs - s0 < per_pass ? sh.nslabs - s0 : per_pass;
@@ -561,7 +570,7 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
             const L2Slices sl = l2_slices(sh, slabs);
             _Float16* wsA = (_Float16*)L.workspace;
             _Float16* wsB = (_Float16*)((char*)L.workspace + sl.off_b);
-            float* ebuf = (float*)((char*)L.workspace + sl.off_e);
+            _Float16* ebuf = (_Float16*)((char*)L.workspace + sl.off_e);
             // the E buffer is indexed like a tap of this pass alone
             gA.tap_slab0 = 0;
             gB.ebuf = ebuf;
@@ -583,7 +592,7 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
                 HIP_TRY(prof_end(st, &sp));
             }
             HIP_TRY(prof_begin(st, 1, &sp));
-            HIP_TRY(launch_contract_f16(tab, gA, (const _Float16*)basis, wsA, ebuf, 2, st));
+            HIP_TRY(launch_contract_f16(tab, gA, (const _Float16*)basis, wsA, (float*)ebuf, 2, st));
             HIP_TRY(launch_contract_f16(tab, gB, (const _Float16*)((const char*)basis + l2_basis_offset(sh)), wsB,
                                         tap, 3, st));
             HIP_TRY(prof_end(st, &sp));

@@ -38,7 +38,7 @@ struct Geom {
     int l2;              // 0: not used, 1: even part (folded again, n = n0/2, Lc = Lc0/2), 2: odd part (plain)
     int n0, Lc0;         // span and retained length of the full problem
     int H;               // n0/4 rounded up to a pipeline stage: half the contraction length of the odd part
-    const float* ebuf;   // odd part: fp32 even part E[head-tensor][Lc0/2][d] written by the first launch
+    const _Float16* ebuf; // odd part: fp16 even part E[head-tensor][Lc0/2][d] written by the first launch
     int Kh;              // contraction length: n/2 (fold) or n
     int Kpad;            // Kh rounded up to kKStage
     int nkstages;        // Kpad / kKStage
@@ -61,7 +61,7 @@ hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hip
 // ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
 // mode 0: rows into the cache; 1: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (atomics);
-// 2: even part of the two-level fold, fp32 rows into tap only; 3: odd part, combined with g.ebuf into the cache
+// 2: even part of the two-level fold, fp16 rows into the buffer passed as tap, nothing else; 3: odd part, combined with g.ebuf into the cache
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,
                                const _Float16* ws, float* tap, int mode, hipStream_t st);
 // two-level fold: gA = geometry of the even-part launch; wsA folded layout (xee | xeo), wsB plain layout (xo)

@@ -363,7 +363,7 @@ __device__ __forceinline__ void lds_barrier()
 // MODE 0: rows into the cache (and the optional fp32 tap).
 // MODE 1 (spectrum): add the squared results, summed over the 8 channels of an item and scaled by
 //         g.spec_scale, to the spectrum line of the item's head: tap[(slab, head)][coefficient].
-// MODE 2 (even part of the two-level fold): results only into tap, which is then the fp32 buffer
+// MODE 2 (even part of the two-level fold): results only into tap, which is then the fp16 buffer
 //         E[head-tensor][Lc][d] of this (half-size) problem; the cache is not written.
 // MODE 3 (odd part of the two-level fold, plain operator): row m of the result is O_m; with E_m from
 //         g.ebuf, cache row m gets E+O and row Lc0-1-m gets E-O (tap likewise, full-size layout).
@@ -559,7 +559,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     const bool col_ok = vcol < g.ncols;
     char* base = nullptr;
     float* tp = nullptr;
-    const float* ep = nullptr;      // MODE 3: the even part of this thread's columns
+    const _Float16* ep = nullptr;   // MODE 3: the even part of this thread's columns (fp16 buffer)
+    _Float16* hp = nullptr;         // MODE 2: where this thread's columns of the even part go
     if (col_ok) {
         int ht;
         base = column_base(tab, g, vcol, 2, &ht);
@@ -571,10 +572,28 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
         } else if constexpr (MODE == 3) {
             if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc0) * g.d + c;
             ep = g.ebuf + ((long long)ht * g.Lc) * g.d + c;          // the buffer belongs to this pass alone
+        } else if constexpr (MODE == 2) {
+            hp = (_Float16*)tap + ((long long)ht * g.Lc) * g.d + c;
         } else {
             if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)g.Lc) * g.d + c;
         }
     }
+    // MODE 3: the even-part rows this thread will need, fetched one round of 32-row blocks ahead so that the
+    // global-load latency hides behind the LDS traffic of the round before (the operand registers of the main
+    // loop are free by now).
+    constexpr int NIT = ITEMS / NT;
+    half8 epre[2][MODE == 3 ? NIT : 1];
+    auto fetch_even = [&](auto mbf, auto buf) {
+        if constexpr (MODE == 3) {
+            static_for<NIT>([&](auto itc) {
+                const int item = threadIdx.x + itc.value * NT;
+                const int row_a = mt * kRowsPlain + (item >> 9) * WROWS + mbf.value * 32 + ((item >> 4) & 31);
+                epre[buf.value][itc.value] = (col_ok && row_a < g.Mh) ? *(const half8*)(ep + (long long)row_a * g.d)
+                                                                      : half8{};
+            });
+        }
+    };
+    fetch_even(IC<0>{}, IC<0>{});
     static_for<MBN>([&](auto mbc) {
         constexpr int MB = decltype(mbc)::value;
         static_for<4>([&](auto nb) {
@@ -583,9 +602,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                 T[(wave * 32 + row) * 128 + nb.value * 32 + l32] = acc[MB][nb.value][r.value];
             });
         });
+        if constexpr (MB + 1 < MBN) fetch_even(IC<MB + 1>{}, IC<(MB + 1) & 1>{});
         __syncthreads();
-#pragma unroll
-        for (int it = 0; it < ITEMS / NT; ++it) {
+        static_for<NIT>([&](auto itc) {
+            constexpr int it = decltype(itc)::value;
             const int item = threadIdx.x + it * NT;
             const int row = (item >> 4) & 31, w = item >> 9;
             if constexpr (MODE == 1) {
@@ -621,9 +641,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                         atomicAdd(tp + rh, pe);
                     }
                 }
-                continue;
+                return;
             }
-            if (!col_ok) continue;
+            if (!col_ok) return;
             float va[8], vb[8];
             int row_a, row_b = -1;
             if constexpr (FOLD) {
@@ -633,7 +653,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
 #pragma unroll
                 for (int i = 0; i < 8; ++i) { va[i] = e[i] + o[i]; vb[i] = e[i] - o[i]; }
                 const int rh = mt * kRowsFold + w * WROWS + MB * 32 + row;
-                if (rh >= g.Mh) continue;
+                if (rh >= g.Mh) return;
                 row_a = rh;
                 row_b = g.Lc - 1 - rh;
             } else {
@@ -641,26 +661,25 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
 #pragma unroll
                 for (int i = 0; i < 8; ++i) va[i] = e[i];
                 row_a = mt * kRowsPlain + w * WROWS + MB * 32 + row;
-                if (row_a >= g.Mh) continue;
+                if (row_a >= g.Mh) return;
             }
             if constexpr (MODE == 2) {
-                // even part of the two-level fold: fp32 rows of E only
+                // even part of the two-level fold: rows of E only, as fp16 (four times finer than the bf16
+                // grid of the rows they end up in; halves the round trip through HBM)
+                half8 ha, hb;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) tp[(long long)row_a * g.d + i] = va[i];
-                if constexpr (FOLD) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) tp[(long long)row_b * g.d + i] = vb[i];
-                }
-                continue;
+                for (int i = 0; i < 8; ++i) { ha[i] = (_Float16)va[i]; hb[i] = (_Float16)vb[i]; }
+                *(half8*)(hp + (long long)row_a * g.d) = ha;
+                if constexpr (FOLD) *(half8*)(hp + (long long)row_b * g.d) = hb;
+                return;
             }
             if constexpr (MODE == 3) {
                 // va = O_m; y_m = E_m + O_m, y_{Lc0-1-m} = E_m - O_m
                 row_b = g.Lc0 - 1 - row_a;
-                const f32x4 e0 = *(const f32x4*)(ep + (long long)row_a * g.d);
-                const f32x4 e1 = *(const f32x4*)(ep + (long long)row_a * g.d + 4);
+                const half8 eh = epre[MB & 1][it];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float e = i < 4 ? e0[i & 3] : e1[i & 3];
+                    const float e = (float)eh[i];
                     vb[i] = e - va[i];
                     va[i] = e + va[i];
                 }
@@ -684,7 +703,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                     for (int i = 0; i < 8; ++i) tp[(long long)row_b * g.d + i] = vb[i];
                 }
             }
-        }
+        });
         __syncthreads();
     });
 }
