@@ -307,3 +307,44 @@ def test_ragged_errors():
     assert f(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, cl, 129, check=False) == -1
     torch.cuda.synchronize()
     assert bool((out == 5.0).all())
+
+
+# ---------------------------------------------------------------- the benchmark's full sizes, sampled
+
+def _sampled_full(wl_name, n_pick, seed):
+    """All layers of a benchmark workload in one call (the launch configuration bench.py times); the oracle
+    checks a seeded sample of (layer, batch) slices that always holds the first and the last one."""
+    wl = synth.WORKLOADS[wl_name]
+    cur = wl.window
+    k, v = synth.empty_cache(wl, DEV)
+    synth.KVSource(wl, seed, DEV).fill(k, v, 0, cur)
+    q = synth.queries(wl, seed, DEV)
+    out, lse, p = _run(q, k, v, wl, cur)
+    assert not torch.isnan(out.float()).any()
+    rng = np.random.default_rng(seed)
+    picks = {(0, 0), (wl.n_layers - 1, wl.batch - 1)}
+    while len(picks) < n_pick:
+        picks.add((int(rng.integers(wl.n_layers)), int(rng.integers(wl.batch))))
+    worst = 0.0
+    for l, b in sorted(picks):
+        kk, vv = f64(k[l, b].cpu()), f64(v[l, b].cpu())
+        ref, rlse = att.attend_decode(f64(q[l, b].cpu()), kk, vv, cur, None, wl.rope_base)
+        vmax = float(np.abs(vv).max())
+        err = np.abs(f64(out[l, b].cpu()) - ref)
+        bound = 0.5 * bf16_ulp(ref) * 1.001 + TOL_ATT_F32 * vmax
+        assert (err <= bound).all(), (l, b, float((err / bound).max()))
+        worst = max(worst, float((err / bound).max()))
+        assert np.max(np.abs(f64(lse[l, b].cpu()) - rlse)) <= 2e-5 * (1.0 + np.abs(rlse).max())
+    _say(f"attend {wl_name}: n_split={p.n_split} GT={p.heads_together}, {len(picks)} slices, worst err/bound={worst:.3f}")
+
+
+def test_full_llama3_8b_128k():
+    _sampled_full("llama3_8b_128k", 4, 1)
+
+
+def test_full_llama2_7b_32k():
+    _sampled_full("llama2_7b_32k", 3, 2)
+
+
+def test_full_decode_b8_256k():
+    _sampled_full("decode_b8_256k", 4, 3)

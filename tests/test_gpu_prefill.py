@@ -162,3 +162,17 @@ def test_prefill_errors_leave_output_untouched():
     assert f(7, wl.n_heads, 128, 100, 40) == -1
     torch.cuda.synchronize()
     assert bool((out == 5.0).all())
+
+
+def test_prefill_llama2_chunk_sampled():
+    """Multi-head attention (one query head per KV head: the four waves of a workgroup take four query
+    blocks of different causal reach), LLaMA-2 window: 2050 compacted rows + a chunk of 2046 tokens."""
+    wl = synth.small(synth.WORKLOADS["llama2_7b_32k"], n_layers=1, total_tokens=4096)
+    cur_len, q_len = 4096, 2046
+    q, k, v = _mk(wl, cur_len, q_len, seed=12)
+    out, lse, p = _run(q, k, v, wl, cur_len)
+    sub = synth.small(wl, n_heads=4)                   # check the first four heads
+    w = _check(q[:, :, :4], k[:, :, :4], v[:, :, :4], out[:, :, :4], lse[:, :, :4], sub, cur_len,
+               rows=[0, 63, 64, 1000, 2045])
+    _say(f"prefill 4096/2046 MHA: worst excess / max|V| = {w:.2e}")
+    assert w <= TOL_PREFILL
