@@ -873,11 +873,11 @@ freqkv_status_t check_prefill(const freqkv_layout_t* L, int n_q, int n_kv, int d
     if (q_len < 1 || q_len > cur_len) return FREQKV_E_INVALID;
     if (d != 128 || L->dtype != FREQKV_BF16) return FREQKV_E_UNSUPPORTED;
     p.q_len = q_len;
-    p.q_pad = (int)round_up(q_len, 64);
+    p.q_pad = (int)round_up(q_len, 32);
     p.key_tiles = (cur_len + 31) / 32;
     p.layers_per_pass = p.a.n_layers < kMaxSlabs / 2 ? p.a.n_layers : kMaxSlabs / 2;
     const long long units = (long long)p.layers_per_pass * p.a.batch * n_kv;
-    if (units * p.a.G * (p.q_pad / 64) > (1LL << 30)) return FREQKV_E_UNSUPPORTED;
+    if (units * p.a.G * (p.q_pad / 32) > (1LL << 30)) return FREQKV_E_UNSUPPORTED;
     size_t cs_bytes = (size_t)round_up((long long)cur_len * (d / 2) * 8, 256);
     size_t kv_bytes = (size_t)units * p.key_tiles * 32 * d * 2;
     size_t q_bytes = (size_t)units * p.a.G * p.q_pad * d * 2;
@@ -900,7 +900,7 @@ freqkv_status_t freqkv_attend_prefill_plan(const freqkv_layout_t* layout, int n_
     memset(out, 0, sizeof(*out));
     out->workspace_bytes = p.workspace_bytes;
     out->key_tiles = p.key_tiles;
-    out->query_blocks = p.q_pad / 64;
+    out->query_blocks = p.q_pad / 32;
     // query i sees cur_len - q_len + i + 1 rows; 4 d flops per (query, row): scores and weighted sum
     const double rows_seen = (double)q_len * (cur_len - q_len) + 0.5 * (double)q_len * (q_len + 1);
     const double heads = (double)p.a.units_all * p.a.G;
@@ -947,7 +947,7 @@ freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, const void* 
         memset(&g, 0, sizeof(g));
         g.d = a.d; g.G = a.G; g.n_kv = a.n_kv;
         g.units = layers * upl; g.units_per_layer = upl;
-        g.cur_len = cur_len; g.q_len = q_len; g.q_pad = p.q_pad; g.q_blocks = p.q_pad / 64;
+        g.cur_len = cur_len; g.q_len = q_len; g.q_pad = p.q_pad; g.q_blocks = p.q_pad / 32;
         g.key_tiles = p.key_tiles; g.rope = rope_base > 0.0;
         g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
         g.qscale = (float)(1.4426950408889634 / std::sqrt((double)a.d));

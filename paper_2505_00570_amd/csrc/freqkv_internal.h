@@ -132,7 +132,7 @@ struct PrefillGeom {
     int cur_len;           // cached rows, the chunk's tokens included
     int q_len;             // tokens of the chunk = queries per head; they are the last q_len cached rows
     int q_pad;             // q_len rounded up to 64
-    int q_blocks;          // q_pad / 64
+    int q_blocks;          // q_pad / 32
     int key_tiles;         // ceil(cur_len / 32)
     int rope;
     long long stride_batch, stride_head, stride_token;   // elements

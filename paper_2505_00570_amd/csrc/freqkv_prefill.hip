@@ -15,7 +15,7 @@
 //                     keys permuted so that a softmax tile, as the matrix core leaves it in registers, is
 //                     already the second operand of the weighted sum
 //   k_prefill_prep_q  Qr = rotate(q) * log2(e)/sqrt(d), row-major
-// and k_attend_prefill computes, per wave, S^T = Kr Qr^T for 32 keys x 64 queries, the running softmax per
+// and k_attend_prefill computes, per wave, S^T = Kr Qr^T for 32 keys x 32 queries, the running softmax per
 // query (a query is a column, so its maximum and sum are in-lane reductions plus one exchange between the
 // two half-waves), and O^T += Vt P^T.
 #include "freqkv_internal.h"
@@ -44,7 +44,8 @@ __device__ __forceinline__ void static_for(F&& f)
 
 constexpr int kD = 128;            // head_dim served by this kernel
 constexpr int kKeyTile = 32;       // keys per tile
-constexpr int kQPerWave = 64;      // queries per wave
+constexpr int kQPerWave = 32;      // queries per wave
+constexpr int kPrefillWaves = 8;   // waves per workgroup of the attention kernel
 constexpr int kTileBytes = kKeyTile * kD * 2;   // one Kr or Vt tile, fp16
 constexpr float kMinusBig = -1.0e30f;
 constexpr float kSlack = 14.0f;    // log2 of the largest un-rescaled softmax weight (an fp16 operand: < 2^16)
@@ -53,11 +54,10 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ uint32_t pack_half2(float a, float b)
+__device__ __forceinline__ half2v pack_half2(float a, float b)
 {
     f32x2 v = {a, b};
-    half2v h = __builtin_convertvector(v, half2v);      // round to nearest even, one packed conversion
-    return __builtin_bit_cast(uint32_t, h);
+    return __builtin_convertvector(v, half2v);          // round to nearest even, one packed conversion
 }
 
 // Position of the key that sits at storage index s (0..31) of a Vt tile: the matrix core leaves a
@@ -203,23 +203,28 @@ __global__ void k_prefill_prep_q(const uint16_t* __restrict__ q, const PrefillGe
     *(half8*)(Qr + (head * g.q_pad + i) * kD + g8 * 8) = out;
 }
 
-// Workgroup = 4 waves = 4 tasks of one KV unit; a task is (query head of the KV group, block of 64 queries),
-// heads fastest, so that with 4 query heads per KV head the four waves walk the same keys.
-__global__ __launch_bounds__(256, 1)
+// Workgroup = 8 waves = 8 tasks of one KV unit, two waves per SIMD; a task is (query head of the KV group,
+// block of 32 queries), heads fastest, so that with 4 query heads per KV head the waves walk the same keys.
+// A wave keeps its 32 queries, their 128 x 32 output block and two 32 x 32 score blocks in vector registers
+// (under 256 in all, so that two waves share a SIMD and the matrix instructions take all operands from the
+// vector registers).
+__global__ __launch_bounds__(kPrefillWaves * 64, 2)
 void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, const _Float16* __restrict__ Vt,
                       const _Float16* __restrict__ Qr, uint16_t* __restrict__ out, float* __restrict__ lse)
 {
-    __shared__ __attribute__((aligned(1024))) char ksm[2][kTileBytes];   // Kr tiles t+1, t+2 (one step ahead)
+    __shared__ __attribute__((aligned(1024))) char ksm[4][kTileBytes];   // Kr tiles t+1, t+2, t+3 of step t (ring)
     __shared__ __attribute__((aligned(1024))) char vsm[2][kTileBytes];   // Vt tiles t, t+1
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    static_assert(kTileBytes == kPrefillWaves * 64 * 16, "one 16-byte piece of a tile per thread");
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: the loop bounds below are per wave
+    const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, hw = lane >> 5;
     const int tasks_per_unit = g.G * g.q_blocks;
-    const int wgs_per_unit = (tasks_per_unit + 3) / 4;
+    const int wgs_per_unit = (tasks_per_unit + kPrefillWaves - 1) / kPrefillWaves;
     const int unit = blockIdx.x / wgs_per_unit;
     // later query blocks see more keys: hand them out first so that the long workgroups start early
     const int wg_in_unit = wgs_per_unit - 1 - (blockIdx.x - unit * wgs_per_unit);
-    const int task = wg_in_unit * 4 + wave;
+    const int task = wg_in_unit * kPrefillWaves + wave;
     const bool active = task < tasks_per_unit;
     const int qb = active ? task / g.G : 0;
     const int gh = active ? task - qb * g.G : 0;
@@ -227,234 +232,190 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     const int q0 = qb * kQPerWave;                                 // first query row of this wave
     const int pos0 = g.cur_len - g.q_len + q0;                     // its in-cache position
 
-    // keys this wave needs: [0, pos0 + 63] cut at cur_len; the workgroup loads up to its largest need
+    // keys this wave needs: [0, pos0 + 31] cut at cur_len; the workgroup loads up to its largest need
     const int my_last = active ? min(pos0 + kQPerWave - 1, g.cur_len - 1) : -1;
     const int my_tiles = (my_last + kKeyTile) / kKeyTile;
+    const int full_tiles = active ? (pos0 + 1) / kKeyTile : 0;     // tiles every query of the wave sees whole
     int wg_tiles;
     {
-        const int last_task = min(wg_in_unit * 4 + 3, tasks_per_unit - 1);
+        const int last_task = min(wg_in_unit * kPrefillWaves + kPrefillWaves - 1, tasks_per_unit - 1);
         const int last_qb = last_task / g.G;
         const int wg_last = min(g.cur_len - g.q_len + last_qb * kQPerWave + kQPerWave - 1, g.cur_len - 1);
         wg_tiles = (wg_last + kKeyTile) / kKeyTile;
     }
 
     // ---- queries of this wave: second operand of S^T = Kr Qr^T, lane = query column, 8 channels per k-step half
-    half8 qf[2][8];
+    half8 qf[8];
     {
-        const _Float16* qrow = Qr + (head * g.q_pad + q0) * kD;
-        static_for<2>([&](auto qs) {
-            static_for<8>([&](auto s) {
-                const _Float16* p = qrow + (qs.value * 32 + l32) * kD + s.value * 16 + hw * 8;
-                qf[qs.value][s.value] = active ? *(const half8*)p : half8{};
-            });
-        });
+        const _Float16* qrow = Qr + (head * g.q_pad + q0 + l32) * kD + hw * 8;
+        static_for<8>([&](auto s) { qf[s.value] = active ? *(const half8*)(qrow + s.value * 16) : half8{}; });
     }
 
-    f32x16 acc[4][2];           // O^T: [channel block][query sub-block], 32 channels x 32 queries each
-    static_for<4>([&](auto db) {
-        static_for<2>([&](auto qs) {
-            static_for<16>([&](auto r) { acc[db.value][qs.value][r.value] = 0.f; });
-        });
-    });
-    float m[2] = {0.f, 0.f}, lsum[2] = {0.f, 0.f};     // per query column (lane), both half-waves agree
+    f32x16 acc[4];              // O^T: [channel block], 32 channels x 32 queries each
+    static_for<4>([&](auto db) { static_for<16>([&](auto r) { acc[db.value][r.value] = 0.f; }); });
+    float m = 0.f, lsum = 0.f;  // m: reference point of the lane's query (both half-waves agree); lsum: this half-wave's share
+    f32x16 negm;                // -m in every register: the accumulator input of the first score instruction of a tile
+    static_for<16>([&](auto r) { negm[r.value] = 0.f; });
 
     const char* ksrc = (const char*)(Kr + (long long)unit * g.key_tiles * (kKeyTile * kD));
     const char* vsrc = (const char*)(Vt + (long long)unit * g.key_tiles * (kKeyTile * kD));
     const int tid16 = threadIdx.x * 16;
+    const int frag = (hw * kKeyTile + l32) * 16;       // this lane's 16 bytes inside a k-step of a tile
 
-    // Tiles travel global -> registers -> LDS, two tiles ahead of the weighted sum and one ahead of the scores:
-    //   step t:  issue loads of tile t+2;  S(t+1) = Kr(t+1) Qr^T;  softmax of S(t);  O^T += Vt(t) P(t)^T;
-    //            Kr(t+2) -> K slot t%2 (its tile t was consumed a step ago);  barrier;  Vt(t+2) -> V slot t%2.
-    // The scores of the next tile are independent of the softmax of this one, so the matrix cores have work
-    // while the vector units do the exponentials.
-    u32x4 stage[4];
-    auto load_tile = [&](int tile) {
-        const char* ks = ksrc + (long long)tile * kTileBytes + tid16;
-        const char* vs = vsrc + (long long)tile * kTileBytes + tid16;
-        stage[0] = *(const u32x4*)ks;
-        stage[1] = *(const u32x4*)(ks + 4096);
-        stage[2] = *(const u32x4*)vs;
-        stage[3] = *(const u32x4*)(vs + 4096);
-    };
-    auto store_k = [&](int slot) {
-        *(u32x4*)(ksm[slot] + tid16) = stage[0];
-        *(u32x4*)(ksm[slot] + tid16 + 4096) = stage[1];
-    };
-    auto store_v = [&](int slot) {
-        *(u32x4*)(vsm[slot] + tid16) = stage[2];
-        *(u32x4*)(vsm[slot] + tid16 + 4096) = stage[3];
-    };
-    load_tile(0);
-    store_k(0);
-    store_v(0);
-    if (wg_tiles > 1) {
-        load_tile(1);
-        store_k(1);
-        store_v(1);
-    }
+    // Tiles travel global -> registers -> LDS.  Step t consumes tile t: it computes S(t+1) = Kr(t+1) Qr^T while
+    // the softmax of S(t) runs, then O^T += Vt(t) P(t)^T.  Kr(t+3) is loaded at the start of step t and stored
+    // before the barrier that ends it, Vt(t+2) likewise but stored after that barrier (its slot holds Vt(t)
+    // until then).  Keys are two barriers ahead of their use so that the first fragments of Kr(t+2) can be read
+    // before the barrier of step t: the matrix instructions of step t+1 then start right behind it.
+    u32x4 stage_k, stage_v;
+    auto load_k = [&](int tile) { stage_k = *(const u32x4*)(ksrc + (long long)tile * kTileBytes + tid16); };
+    auto load_v = [&](int tile) { stage_v = *(const u32x4*)(vsrc + (long long)tile * kTileBytes + tid16); };
+    auto store_k = [&](int tile) { *(u32x4*)(ksm[tile & 3] + tid16) = stage_k; };
+    auto store_v = [&](int slot) { *(u32x4*)(vsm[slot] + tid16) = stage_v; };
+    // Loads and stores past the last tile are not branched around: they repeat the last tile into a slot that
+    // nobody reads any more, which keeps the loop free of branches and lets the compiler count the loads in
+    // flight exactly.
+    const int last_tile = wg_tiles - 1;
+    static_for<3>([&](auto i) {
+        load_k(min(i.value, last_tile));
+        store_k(i.value);
+    });
+    static_for<2>([&](auto i) {
+        load_v(min(i.value, last_tile));
+        store_v(i.value);
+    });
     __syncthreads();
 
-    // Causal mask: tiles that reach past the first query of the wave.
-    auto mask_tile = [&](int tile, f32x16 (&cur)[2]) {
-        const int key_base = tile * kKeyTile;
-        if (key_base + kKeyTile - 1 <= pos0) return;
-        static_for<2>([&](auto qs) {
-            constexpr int QS = decltype(qs)::value;
-            const int qpos = pos0 + QS * 32 + l32;
-            static_for<16>([&](auto r) {
-                constexpr int R = decltype(r)::value;
-                const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
-                if (key > qpos) cur[QS][R] = -INFINITY;
-            });
-        });
-    };
+    half8 kf[8], vf[8];         // fragments of Kr(t+1) and Vt(t), read from LDS a few matrix instructions ahead
+    auto read_k = [&](auto s8, const char* kt) { kf[s8.value] = *(const half8*)(kt + s8.value * (2 * kKeyTile * 16)); };
 
     // cur holds S(t) - m: the accumulators of the scores start at minus the query's reference point, so the
-    // exponent needs no subtraction; nxt receives S(t+1) - m during step t.
-    f32x16 cur[2], nxt[2];
+    // exponent needs no subtraction; nxt receives S(t+1) - m during step t; the two swap roles every step.
+    f32x16 cur, nxt;
+    static_for<16>([&](auto r) { cur[r.value] = 0.f; });
     if (my_tiles > 0) {
-        const char* kt = ksm[0];
-        static_for<2>([&](auto qs) { static_for<16>([&](auto r) { cur[qs.value][r.value] = 0.f; }); });
+        const char* kt = ksm[0] + frag;
         static_for<8>([&](auto s8) {
-            half8 kf = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16);
-            static_for<2>([&](auto qs) {
-                cur[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[qs.value][s8.value], cur[qs.value], 0, 0, 0);
-            });
+            read_k(s8, kt);
+            cur = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s8.value], qf[s8.value], cur, 0, 0, 0);
         });
+        static_for<2>([&](auto s8) { read_k(s8, ksm[1] + frag); });
     }
-    __syncthreads();          // K slot 0 is overwritten with tile 2 in step 0: every wave must have read tile 0
 
-    // The reference point m of a query's running softmax moves only when a score exceeds it by more than
-    // 2^kSlack (weights up to 2^kSlack are accumulated as they are; any reference point gives the same
-    // quotient).  Moving it rescales the accumulators with vector instructions, which would drag them out of
-    // the accumulation registers of the matrix cores; so the tile loop is split: the inner loop never touches
-    // the accumulators with vector instructions and leaves, before consuming a tile, when some query of the
-    // wave needs a new reference point; the outer loop moves the reference points and re-enters.
-    int tile = 0;
-    bool first = true;        // the first tile sets the reference points whatever the scores are
-    while (tile < wg_tiles) {
-        if (tile < my_tiles) {
-            mask_tile(tile, cur);
-            static_for<2>([&](auto qs) {
-                constexpr int QS = decltype(qs)::value;
-                float v = cur[QS][0];
-                static_for<16>([&](auto r) { v = fmaxf(v, cur[QS][r.value]); });
-                const float mx = fmaxf(v, __shfl_xor(v, 32));
-                const bool grow = first || mx > kSlack;
-                const float delta = grow ? mx : 0.f;              // the reference point moves up by delta
-                const float f = exp2_fast(-delta);
-                m[QS] += delta;
-                lsum[QS] *= f;
-                static_for<4>([&](auto db) {
-                    static_for<16>([&](auto r) { acc[db.value][QS][r.value] *= f; });
-                });
-                static_for<16>([&](auto r) { cur[QS][r.value] -= delta; });   // the pending tile follows
-            });
+    // Causal mask of a tile that reaches past the first query of the wave.
+    auto mask_tile = [&](int tile, f32x16& s) {
+        const int key_base = tile * kKeyTile;
+        const int qpos = pos0 + l32;
+        static_for<16>([&](auto r) {
+            constexpr int R = decltype(r)::value;
+            const int key = key_base + 8 * (R / 4) + 4 * hw + (R % 4);
+            if (key > qpos) s[R] = -INFINITY;
+        });
+    };
+    // Does any score of the tile exceed its query's reference point by more than the slack?  (each lane's own 16
+    // scores suffice for the vote; exact maxima are only needed when the answer is yes)
+    auto wants_move = [&](const f32x16& s) -> bool {
+        float v = s[0];
+        static_for<16>([&](auto r) { v = fmaxf(v, s[r.value]); });
+        return __builtin_amdgcn_ballot_w64(v > kSlack) != 0;
+    };
+    // Moves the reference point m of every query whose largest score in s exceeds it by more than the slack
+    // (all of them on the first tile): the accumulated sums and the pending scores follow.  A weight may reach
+    // 2^kSlack before that happens; any reference point gives the same quotient.  Rare after the first tiles.
+    auto move_refs = [&](f32x16& s, bool all) {
+        float v = s[0];
+        static_for<16>([&](auto r) { v = fmaxf(v, s[r.value]); });
+        const float mx = fmaxf(v, __shfl_xor(v, 32));
+        const bool grow = all || mx > kSlack;
+        const float delta = grow ? mx : 0.f;              // the reference point moves up by delta
+        const float f = exp2_fast(-delta);
+        m += delta;
+        lsum *= f;
+        static_for<4>([&](auto db) { static_for<16>([&](auto r) { acc[db.value][r.value] *= f; }); });
+        static_for<16>([&](auto r) { s[r.value] -= delta; });
+        static_for<16>([&](auto r) { negm[r.value] = -m; });
+    };
+
+    // One step: tile t, whose scores minus m are in s, is consumed while the scores of tile t+1 go to n.
+    bool first = true;          // the first tile sets the reference points whatever the scores are
+    auto step = [&](auto par, int t, f32x16& s, f32x16& n) {
+        constexpr int P = decltype(par)::value;           // t % 2: the Vt slot
+        const bool mine = t < my_tiles;
+        if (mine) {
+            if (t >= full_tiles) mask_tile(t, s);
+            if (first || wants_move(s)) move_refs(s, first);
+            first = false;
         }
-        first = false;
-        while (tile < wg_tiles) {
-            const bool mine = tile < my_tiles;
-            if (mine) {
-                // does any score of this tile exceed its query's reference point by more than the slack?  (the
-                // lanes' own 16 scores suffice for the vote; exact maxima are only needed when it is yes)
-                mask_tile(tile, cur);
-                float v0 = cur[0][0], v1 = cur[1][0];
-                static_for<16>([&](auto r) {
-                    v0 = fmaxf(v0, cur[0][r.value]);
-                    v1 = fmaxf(v1, cur[1][r.value]);
-                });
-                if (__builtin_amdgcn_ballot_w64(fmaxf(v0, v1) > kSlack) != 0) break;
-            }
-            const int slot = tile & 1;
-            if (tile + 2 < wg_tiles) load_tile(tile + 2);
-            if (mine) {
-                // Fragments come from LDS a few matrix instructions ahead of their use: Kr(t+1) for the next
-                // scores (past the wave's last tile this is a stale slot; the result is never used), then Vt(t).
-                half8 kf[8], vf[8];
-                const char* kt = ksm[slot ^ 1];
-                const char* vt = vsm[slot];
-                auto read_k = [&](auto s8) { kf[s8.value] = *(const half8*)(kt + ((s8.value * 2 + hw) * kKeyTile + l32) * 16); };
-                auto read_v = [&](auto i) { vf[i.value] = *(const half8*)(vt + ((i.value * 2 + hw) * 32 + l32) * 16); };
-                static_for<2>([&](auto s8) { read_k(s8); });
-                // ---- scores of the next tile on the matrix cores, dealt out between the exponentials of this
-                // tile on the vector units: per 16-channel step two matrix instructions and four weights,
-                // packed to fp16 as they are produced
-                static_for<2>([&](auto qs) { static_for<16>([&](auto r) { nxt[qs.value][r.value] = -m[qs.value]; }); });
-                float ps[2] = {0.f, 0.f};
-                u32x4 pw[2][2];         // P^T, the second operand of the weighted sum: [query sub-block][k-step]
-                static_for<8>([&](auto s8) {
-                    constexpr int S8 = decltype(s8)::value;
-                    if constexpr (S8 < 6) {
-                        read_k(IC<S8 + 2>{});
-                    } else {                                   // first k-step of the weighted sum: vf[2*db]
-                        read_v(IC<(S8 - 6) * 4>{});
-                        read_v(IC<(S8 - 6) * 4 + 2>{});
-                    }
-                    static_for<2>([&](auto qs) {
-                        nxt[qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[S8], qf[qs.value][S8], nxt[qs.value], 0, 0, 0);
-                    });
-                    static_for<2>([&](auto e) {
-                        constexpr int I = S8 * 4 + 2 * decltype(e)::value;  // (query sub-block, register pair)
-                        constexpr int QS = I / 16, R = I % 16;
-                        const float p0 = exp2_fast(cur[QS][R]), p1 = exp2_fast(cur[QS][R + 1]);
-                        ps[QS] += p0 + p1;
-                        pw[QS][R / 8][(R % 8) / 2] = pack_half2(p0, p1);
-                    });
+        load_k(min(t + 3, last_tile));
+        load_v(min(t + 2, last_tile));
+        if (mine) {
+            const char* kt = ksm[(t + 1) & 3] + frag;     // past the wave's last tile a stale slot: result unused
+            const char* vt = vsm[P] + frag;
+            auto read_v = [&](auto i) { vf[i.value] = *(const half8*)(vt + i.value * (2 * kKeyTile * 16)); };
+            // ---- scores of the next tile on the matrix cores, dealt out between the exponentials of this tile
+            // on the vector units: per 16-channel step one matrix instruction and two weights, packed to fp16
+            // as they are produced; kf[0], kf[1] were read before the barrier
+            float ps = 0.f;
+            u32x4 pw[2];        // P^T, the second operand of the weighted sum, per k-step
+            static_for<8>([&](auto s8) {
+                constexpr int S8 = decltype(s8)::value;
+                if constexpr (S8 < 6) {
+                    read_k(IC<S8 + 2>{}, kt);
+                } else {                                   // first k-step of the weighted sum: vf[2*db]
+                    read_v(IC<(S8 - 6) * 4>{});
+                    read_v(IC<(S8 - 6) * 4 + 2>{});
+                }
+                n = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[S8], qf[S8], S8 == 0 ? negm : n, 0, 0, 0);
+                constexpr int R = 2 * S8;
+                const half2v ph = pack_half2(exp2_fast(s[R]), exp2_fast(s[R + 1]));
+                ps = __builtin_amdgcn_fdot2(ph, half2v{(_Float16)1, (_Float16)1}, ps, false);   // sums the rounded weights
+                pw[R / 8][(R % 8) / 2] = __builtin_bit_cast(uint32_t, ph);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            lsum += ps;
+            // ---- O^T += Vt P^T : 128 channels x 32 queries, contraction over the 32 keys; k-step outermost so
+            // that dependent accumulations are four instructions apart
+            static_for<2>([&](auto k2) {
+                const half8 pf = __builtin_bit_cast(half8, pw[k2.value]);
+                static_for<4>([&](auto db) {
+                    if constexpr (decltype(k2)::value == 0) read_v(IC<decltype(db)::value * 2 + 1>{});   // second k-step
+                    else if constexpr (decltype(db)::value < 2) read_k(db, ksm[(t + 2) & 3] + frag);   // first fragments of the step after
+                    acc[db.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[db.value * 2 + k2.value], pf, acc[db.value], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 });
-                half8 pf[2][2];
-                static_for<2>([&](auto qs) {
-                    constexpr int QS = decltype(qs)::value;
-                    lsum[QS] += ps[QS] + __shfl_xor(ps[QS], 32);
-                    static_for<2>([&](auto t) { pf[QS][t.value] = __builtin_bit_cast(half8, pw[QS][t.value]); });
-                });
-                // ---- O^T += Vt P^T : 128 channels x 64 queries, contraction over the 32 keys; k-step outermost so
-                // that dependent accumulations are eight instructions apart
-                static_for<2>([&](auto t) {
-                    static_for<4>([&](auto db) {
-                        if constexpr (decltype(t)::value == 0) read_v(IC<decltype(db)::value * 2 + 1>{});   // second k-step
-                        static_for<2>([&](auto qs) {
-                            acc[db.value][qs.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                                vf[db.value * 2 + t.value], pf[qs.value][t.value], acc[db.value][qs.value], 0, 0, 0);
-                        });
-                        __builtin_amdgcn_sched_barrier(0);
-                    });
-                });
-                static_for<2>([&](auto qs) { cur[qs.value] = nxt[qs.value]; });
-                // keep the output accumulators in the accumulation registers across the loop edge: only the
-                // rare reference-point move above may copy them to vector registers
-                asm volatile("" : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[1][0]), "+a"(acc[1][1]),
-                                  "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[3][0]), "+a"(acc[3][1]));
-            }
-            if (tile + 2 < wg_tiles) store_k(slot);
-            __syncthreads();
-            if (tile + 2 < wg_tiles) store_v(slot);
-            ++tile;
+            });
         }
+        store_k(t + 3);
+        __syncthreads();
+        store_v(P);
+    };
+    // The queries are consumed above only by waves that have tiles; using them here makes the compiler wait for
+    // their loads on every path, instead of in front of the first matrix instruction of each step (where the
+    // wait would also cover the tile loads just issued).
+    asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
+    for (int t = 0; t < wg_tiles; t += 2) {
+        step(IC<0>{}, t, cur, nxt);
+        if (t + 1 < wg_tiles) step(IC<1>{}, t + 1, nxt, cur);
     }
 
     // ---- normalise and store: lane = query, registers = channels 8*(r/4) + 4*hw + r%4 of each block
-    if (active) {
-        static_for<2>([&](auto qs) {
-            constexpr int QS = decltype(qs)::value;
-            const int qi = q0 + QS * 32 + l32;
-            if (qi < g.q_len) {
-                const float inv = 1.0f / lsum[QS];
-                uint16_t* orow = out + (head * g.q_len + qi) * kD;
-                static_for<4>([&](auto db) {
-                    static_for<4>([&](auto r4) {
-                        constexpr int R = 4 * decltype(r4)::value;
-                        f32x2 a = {acc[db.value][QS][R] * inv, acc[db.value][QS][R + 1] * inv};
-                        f32x2 b = {acc[db.value][QS][R + 2] * inv, acc[db.value][QS][R + 3] * inv};
-                        u32x2 w;
-                        w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
-                        w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
-                        *(u32x2*)(orow + db.value * 32 + 8 * r4.value + 4 * hw) = w;
-                    });
-                });
-                if (lse && hw == 0) lse[head * g.q_len + qi] = 0.6931471805599453f * (m[QS] + log2f(lsum[QS]));
-            }
+    lsum += __shfl_xor(lsum, 32);
+    const int qi = q0 + l32;
+    if (active && qi < g.q_len) {
+        const float inv = 1.0f / lsum;
+        uint16_t* orow = out + (head * g.q_len + qi) * kD;
+        static_for<4>([&](auto db) {
+            static_for<4>([&](auto r4) {
+                constexpr int R = 4 * decltype(r4)::value;
+                f32x2 a = {acc[db.value][R] * inv, acc[db.value][R + 1] * inv};
+                f32x2 b = {acc[db.value][R + 2] * inv, acc[db.value][R + 3] * inv};
+                u32x2 w;
+                w[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, bf16x2));
+                w[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, bf16x2));
+                *(u32x2*)(orow + db.value * 32 + 8 * r4.value + 4 * hw) = w;
+            });
         });
+        if (lse && hw == 0) lse[head * g.q_len + qi] = 0.6931471805599453f * (m + log2f(lsum));
     }
 }
 
@@ -489,9 +450,9 @@ hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const
                                  void* out, float* lse, hipStream_t st)
 {
     if (g.d != kD || g.q_blocks * kQPerWave != g.q_pad) return hipErrorInvalidValue;
-    const int wgs_per_unit = (g.G * g.q_blocks + 3) / 4;
-    hipLaunchKernelGGL(k_attend_prefill, dim3((unsigned)((long long)g.units * wgs_per_unit)), dim3(256), 0, st, g, Kr,
-                       Vt, Qr, (uint16_t*)out, lse);
+    const int wgs_per_unit = (g.G * g.q_blocks + kPrefillWaves - 1) / kPrefillWaves;
+    hipLaunchKernelGGL(k_attend_prefill, dim3((unsigned)((long long)g.units * wgs_per_unit)), dim3(kPrefillWaves * 64), 0,
+                       st, g, Kr, Vt, Qr, (uint16_t*)out, lse);
     return hipGetLastError();
 }
 

@@ -282,7 +282,7 @@ def test_prefill_plan():
     L = _layout()                                     # 32 layers x 8 KV heads x 8192 rows x 128, bf16
     out = binding.PrefillPlan()
     rc, p = fk.attend_prefill_plan(L, 32, 8, 128, 8192, 4094)
-    assert rc == 0 and p.key_tiles == 256 and p.query_blocks == 64
+    assert rc == 0 and p.key_tiles == 256 and p.query_blocks == 128
     # causal flops: query i sees cur_len - q_len + i + 1 rows
     rows = sum(8192 - 4094 + i + 1 for i in range(4094))
     assert p.flops == 32 * 32 * 4.0 * 128 * rows
