@@ -213,7 +213,7 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
                       const _Float16* __restrict__ Qr, uint16_t* __restrict__ out, float* __restrict__ lse)
 {
     __shared__ __attribute__((aligned(1024))) char ksm[4][kTileBytes];   // Kr tiles t+1, t+2, t+3 of step t (ring)
-    __shared__ __attribute__((aligned(1024))) char vsm[2][kTileBytes];   // Vt tiles t, t+1
+    __shared__ __attribute__((aligned(1024))) char vsm[4][kTileBytes];   // Vt tiles t .. t+3 (ring)
 
     static_assert(kTileBytes == kPrefillWaves * 64 * 16, "one 16-byte piece of a tile per thread");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: the loop bounds below are per wave
@@ -267,23 +267,26 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     // before the barrier that ends it, Vt(t+2) likewise but stored after that barrier (its slot holds Vt(t)
     // until then).  Keys are two barriers ahead of their use so that the first fragments of Kr(t+2) can be read
     // before the barrier of step t: the matrix instructions of step t+1 then start right behind it.
-    u32x4 stage_k, stage_v;
-    auto load_k = [&](int tile) { stage_k = *(const u32x4*)(ksrc + (long long)tile * kTileBytes + tid16); };
-    auto load_v = [&](int tile) { stage_v = *(const u32x4*)(vsrc + (long long)tile * kTileBytes + tid16); };
-    auto store_k = [&](int tile) { *(u32x4*)(ksm[tile & 3] + tid16) = stage_k; };
-    auto store_v = [&](int slot) { *(u32x4*)(vsm[slot] + tid16) = stage_v; };
+    // Direct global -> LDS copy of one tile: lane i of a wave delivers its 16 bytes to M0 + 16 i.  Written as
+    // assembly because the compiler, which cannot tell the ring slots apart, would wait for a copy issued
+    // through its builtin in front of the next LDS read; the waits are placed by hand, before each barrier.
+    typedef __attribute__((address_space(3))) char* lptr_t;
+    const uint32_t k_lds = (uint32_t)(uintptr_t)(lptr_t)ksm[0] + wave * 1024;
+    const uint32_t v_lds = (uint32_t)(uintptr_t)(lptr_t)vsm[0] + wave * 1024;
+    auto dma = [&](const char* src, uint32_t lds) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");   // M0 has no other user in this kernel
+    };
+    auto dma_k = [&](int tile, int slot) { dma(ksrc + (long long)tile * kTileBytes + tid16, k_lds + (slot & 3) * kTileBytes); };
+    auto dma_v = [&](int tile, int slot) { dma(vsrc + (long long)tile * kTileBytes + tid16, v_lds + (slot & 3) * kTileBytes); };
     // Loads and stores past the last tile are not branched around: they repeat the last tile into a slot that
     // nobody reads any more, which keeps the loop free of branches and lets the compiler count the loads in
     // flight exactly.
     const int last_tile = wg_tiles - 1;
     static_for<3>([&](auto i) {
-        load_k(min(i.value, last_tile));
-        store_k(i.value);
+        dma_k(min(i.value, last_tile), i.value);
     });
-    static_for<2>([&](auto i) {
-        load_v(min(i.value, last_tile));
-        store_v(i.value);
-    });
+    static_for<3>([&](auto i) { dma_v(min(i.value, last_tile), i.value); });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     half8 kf[8], vf[8];         // fragments of Kr(t+1) and Vt(t), read from LDS a few matrix instructions ahead
@@ -346,11 +349,11 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
             if (first || wants_move(s)) move_refs(s, first);
             first = false;
         }
-        load_k(min(t + 3, last_tile));
-        load_v(min(t + 2, last_tile));
+        dma_k(min(t + 3, last_tile), t + 3);
+        dma_v(min(t + 3, last_tile), t + 3);
         if (mine) {
             const char* kt = ksm[(t + 1) & 3] + frag;     // past the wave's last tile a stale slot: result unused
-            const char* vt = vsm[P] + frag;
+            const char* vt = vsm[t & 3] + frag;
             auto read_v = [&](auto i) { vf[i.value] = *(const half8*)(vt + i.value * (2 * kKeyTile * 16)); };
             // ---- scores of the next tile on the matrix cores, dealt out between the exponentials of this tile
             // on the vector units: per 16-channel step one matrix instruction and two weights, packed to fp16
@@ -385,9 +388,8 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
                 });
             });
         }
-        store_k(t + 3);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        store_v(P);
     };
     // The queries are consumed above only by waves that have tiles; using them here makes the compiler wait for
     // their loads on every path, instead of in front of the first matrix instruction of each step (where the
