@@ -49,6 +49,7 @@ constexpr int kPrefillWaves = 8;   // waves per workgroup of the attention kerne
 constexpr int kTileBytes = kKeyTile * kD * 2;   // one Kr or Vt tile, fp16
 constexpr float kMinusBig = -1.0e30f;
 constexpr float kSlack = 14.0f;    // log2 of the largest un-rescaled softmax weight (an fp16 operand: < 2^16)
+constexpr float kWeightLimit = 16384.0f;   // 2^kSlack
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -315,28 +316,23 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
             if (key > qpos) s[R] = -INFINITY;
         });
     };
-    // Does any score of the tile exceed its query's reference point by more than the slack?  (each lane's own 16
-    // scores suffice for the vote; exact maxima are only needed when the answer is yes)
-    auto wants_move = [&](const f32x16& s) -> bool {
-        float v = s[0];
-        static_for<16>([&](auto r) { v = fmaxf(v, s[r.value]); });
-        return __builtin_amdgcn_ballot_w64(v > kSlack) != 0;
-    };
     // Moves the reference point m of every query whose largest score in s exceeds it by more than the slack
-    // (all of them on the first tile): the accumulated sums and the pending scores follow.  A weight may reach
-    // 2^kSlack before that happens; any reference point gives the same quotient.  Rare after the first tiles.
-    auto move_refs = [&](f32x16& s, bool all) {
+    // (all of them on the first tile) up to that score: the accumulated sums and the pending scores follow.
+    // Returns the lane's shift.  Any reference point gives the same quotient, so the point only has to keep
+    // the weights inside the fp16 range.  Rare after the first tiles.
+    auto move_refs = [&](f32x16& s, bool all) -> float {
         float v = s[0];
         static_for<16>([&](auto r) { v = fmaxf(v, s[r.value]); });
         const float mx = fmaxf(v, __shfl_xor(v, 32));
         const bool grow = all || mx > kSlack;
-        const float delta = grow ? mx : 0.f;              // the reference point moves up by delta
+        const float delta = grow ? mx : 0.f;
         const float f = exp2_fast(-delta);
         m += delta;
         lsum *= f;
         static_for<4>([&](auto db) { static_for<16>([&](auto r) { acc[db.value][r.value] *= f; }); });
         static_for<16>([&](auto r) { s[r.value] -= delta; });
         static_for<16>([&](auto r) { negm[r.value] = -m; });
+        return delta;
     };
 
     // One step: tile t, whose scores minus m are in s, is consumed while the scores of tile t+1 go to n.
@@ -346,7 +342,7 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
         const bool mine = t < my_tiles;
         if (mine) {
             if (t >= full_tiles) mask_tile(t, s);
-            if (first || wants_move(s)) move_refs(s, first);
+            if (first) move_refs(s, true);
             first = false;
         }
         dma_k(min(t + 3, last_tile), t + 3);
@@ -375,6 +371,21 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
                 pw[R / 8][(R % 8) / 2] = __builtin_bit_cast(uint32_t, ph);
                 __builtin_amdgcn_sched_barrier(0);
             });
+            // No weight may exceed 2^kSlack (fp16 operands).  That is checked after the fact, on the sum of the
+            // lane's 16 weights, which is there anyway (an overflowed weight makes it infinite): if it is too
+            // large for some lane, the reference points move, the scores of the next tile, which started from
+            // the old ones, follow, and the weights of this tile are computed again.
+            if (__builtin_amdgcn_ballot_w64(!(ps <= kWeightLimit)) != 0) {
+                const float delta = move_refs(s, false);
+                static_for<16>([&](auto r) { n[r.value] -= delta; });
+                ps = 0.f;
+                static_for<8>([&](auto s8) {
+                    constexpr int R = 2 * decltype(s8)::value;
+                    const half2v ph = pack_half2(exp2_fast(s[R]), exp2_fast(s[R + 1]));
+                    ps = __builtin_amdgcn_fdot2(ph, half2v{(_Float16)1, (_Float16)1}, ps, false);
+                    pw[R / 8][(R % 8) / 2] = __builtin_bit_cast(uint32_t, ph);
+                });
+            }
             lsum += ps;
             // ---- O^T += Vt P^T : 128 channels x 32 queries, contraction over the 32 keys; k-step outermost so
             // that dependent accumulations are four instructions apart

@@ -55,7 +55,7 @@ def _run(q, k, v, wl, cur_len, base=None, want_lse=True):
     return out, lse, p
 
 
-def _check(q, k, v, out, lse, wl, cur_len, base=None, rows=None):
+def _check(q, k, v, out, lse, wl, cur_len, base=None, rows=None, lse_tol=2e-2):
     """Compare against the oracle; `rows` selects query rows (default: all)."""
     base = wl.rope_base if base is None else base
     q_len = q.shape[3]
@@ -84,7 +84,7 @@ def _check(q, k, v, out, lse, wl, cur_len, base=None, rows=None):
             over = np.maximum(err - 0.5 * bf16_ulp(ref) * 1.001, 0.0) / vmax
             worst = max(worst, float(over.max()))
             if glse is not None:
-                assert np.max(np.abs(glse - rlse)) <= 2e-2, float(np.max(np.abs(glse - rlse)))
+                assert np.max(np.abs(glse - rlse)) <= lse_tol, float(np.max(np.abs(glse - rlse)))
     return worst
 
 
@@ -129,6 +129,38 @@ def test_prefill_last_query_is_the_decode_case_and_rope_off():
     assert diff <= 0.05, diff
     out2, lse2, _ = _run(q, k, v, wl, 333, base=0.0)
     w = _check(q, k, v, out2, lse2, wl, 333, base=0.0)
+    assert w <= TOL_PREFILL
+
+
+@pytest.mark.parametrize("base", [0.0, 10000.0])
+def test_prefill_scores_that_outgrow_the_reference_point(base):
+    """Keys whose alignment with the queries grows along the cache: the scores of later tiles exceed the running
+    reference point of the softmax by far more than the fp16 range of the weights, so the reference point has
+    to move several times (and the weights of the tile that shows it are computed twice).  All operands are
+    short binary fractions, so without the rotary embedding the fp16 operands are exact and the scores reach
+    tens of units without losing accuracy; with it the keys turn and scores of both signs and all sizes mix."""
+    wl = _wl(hkv=2, hq=8, cap=640)
+    cur_len, q_len = 600, 333
+    k, v = synth.empty_cache(wl, DEV, wl.window)
+    k.fill_(float("nan"))
+    v.fill_(float("nan"))
+    g = torch.Generator(device="cpu").manual_seed(77)
+    d = wl.head_dim
+    u = (torch.randint(0, 2, (wl.n_heads, d), generator=g) * 2 - 1).float()                 # +-1 per KV head
+    ramp = torch.floor(torch.arange(cur_len).float() / cur_len * 256) / 64                  # 0 .. 4 in steps of 1/64
+    ramp = ramp * (1 + (torch.arange(cur_len) % 7 == 0).float())                            # with spikes
+    kk = u[:, None, :] * ramp[None, :, None]
+    k[0, 0, :, :cur_len] = kk.to(torch.bfloat16).to(DEV)
+    v[0, 0, :, :cur_len] = torch.randn(wl.n_heads, cur_len, d, generator=g).to(torch.bfloat16).to(DEV)
+    # query i of head h: u of its KV head on a random subset of 16..128 channels
+    grp = wl.q_heads // wl.n_heads
+    keep = torch.rand(wl.q_heads, q_len, d, generator=g) < (torch.randint(1, 9, (wl.q_heads, q_len, 1), generator=g) / 8.0)
+    q = (u.repeat_interleave(grp, dim=0)[:, None, :] * keep.float())[None, None].to(torch.bfloat16).to(DEV)
+    out, lse, _ = _run(q, k, v, wl, cur_len, base=base)
+    # the scaled queries are rounded to fp16: a score of s nats is off by up to s * 2^-11, and lse with it
+    # (scores here reach 90 nats, and every channel of a query carries the same rounding error)
+    w = _check(q, k, v, out, lse, wl, cur_len, base=base, lse_tol=90 * 2.0 ** -11 + 2e-2)
+    _say(f"growing scores, rotary base {base:g}: worst excess / max|V| = {w:.2e}")
     assert w <= TOL_PREFILL
 
 
