@@ -468,19 +468,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             });
         });
     };
-    // One step at phase PH = s mod 6.  `rem` = stages after s; STEADY (compile time) means rem >= 3.
+    // One step at phase PH = s mod 6.  Nothing in a step is conditional: near the end the loads ask for the last
+    // stage again (stage indices are clamped) and the LDS traffic moves copies nobody uses, so that every step
+    // is the same straight-line code and the compiler can count the loads in flight exactly; with guarded loads
+    // it made each group of matrix instructions wait for loads issued in the same step.
     // The 32 MFMAs run as 8 groups of 4 (one basis fragment against the 4 column blocks); the
     // step's 12 global loads, 8 LDS fragment reads and XR LDS stores are dealt out between the
     // groups, so the vector-memory and LDS queues drain while the matrix cores work instead of
     // blocking the wave in one burst at the top of the step.
-    auto step = [&](int st, auto ph, auto steady, int rem) {
+    auto step = [&](int st, auto ph) {
         constexpr int PH = decltype(ph)::value;
-        constexpr bool STEADY = decltype(steady)::value != 0;
         constexpr int A0 = PH % 3, A2 = (PH + 2) % 3, X0 = PH % 2, X1 = (PH + 1) % 2;
-        const bool do_x = STEADY || rem >= 3, do_a = STEADY || rem >= 2, do_r = STEADY || rem >= 1;
-        const bool do_w = STEADY || rem >= 2;
-        const char* xsrc_s = xsrc + (size_t)(st + 3) * XSTAGE + tid16;
-        const half8* pa = Gv + a_lane + (size_t)(st + 2) * a_stage;
+        const char* xsrc_s = xsrc + (size_t)min(st + 3, nks - 1) * XSTAGE + tid16;
+        const half8* pa = Gv + a_lane + (size_t)min(st + 2, nks - 1) * a_stage;
         const char* xs = smem + X1 * XSTAGE + par * 8192;
         constexpr int NG = 2 * MBN;             // MFMA groups per step: (substep u, row block mb)
         constexpr int RPG = 8 / NG;             // LDS fragment reads per group
@@ -488,19 +488,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             constexpr int G = decltype(gi)::value;
             constexpr int U = G / MBN, MB = G % MBN;
             // global loads: basis fragment G of stage s+2, and one span piece while there are any
-            if (do_a) aset[A2][U][MB] = pa[U * a_kstep + MB * 32];
+            aset[A2][U][MB] = pa[U * a_kstep + MB * 32];
             if constexpr (G < XR) {
-                if (do_x) xr[X1][G] = *(const half8*)(xsrc_s + G * XPIECE);
+                xr[X1][G] = *(const half8*)(xsrc_s + G * XPIECE);
             }
             // LDS: fragments of stage s+1
             static_for<RPG>([&](auto ri) {
                 constexpr int F = G * RPG + decltype(ri)::value, FU = F / 4, FN = F % 4;
-                if (do_r) xf[X1][FU][FN] = *(const half8*)(xs + (((FU * 2 + lhi) * kColTile) + FN * 32 + l32) * 16);
+                xf[X1][FU][FN] = *(const half8*)(xs + (((FU * 2 + lhi) * kColTile) + FN * 32 + l32) * 16);
             });
             // LDS: store the span pieces of stage s+2 late in the step (they were loaded one step ago)
             if constexpr (G >= NG - XR) {
                 constexpr int R = G - (NG - XR);
-                if (do_w) *(half8*)(smem + X0 * XSTAGE + R * XPIECE + tid16) = xr[X0][R];
+                *(half8*)(smem + X0 * XSTAGE + R * XPIECE + tid16) = xr[X0][R];
             }
             static_for<4>([&](auto nb) {
                 acc[MB][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
@@ -508,37 +508,34 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             });
             __builtin_amdgcn_sched_barrier(0);
         });
-        if (do_r) lds_barrier();
+        lds_barrier();
     };
 
     // prologue: span stages 0,1 -> LDS, stage 2 in flight; basis stages 0,1 in flight
     {
         load_x(0, IC<0>{});
         load_a(0, IC<0>{});
-        if (nks > 1) {
-            load_x(1, IC<1>{});
-            load_a(1, IC<1>{});
-        }
+        load_x(min(1, nks - 1), IC<1>{});
+        load_a(min(1, nks - 1), IC<1>{});
         write_x(IC<0>{}, IC<0>{});
-        if (nks > 1) write_x(IC<1>{}, IC<1>{});
-        if (nks > 2) load_x(2, IC<0>{});
+        write_x(IC<1>{}, IC<1>{});
+        load_x(min(2, nks - 1), IC<0>{});
         lds_barrier();
         read_xf(IC<0>{}, IC<0>{});
     }
 
     int st = 0;
-    for (; st + 9 <= nks; st += 6) {
-        step(st + 0, IC<0>{}, IC<1>{}, 3);
-        step(st + 1, IC<1>{}, IC<1>{}, 3);
-        step(st + 2, IC<2>{}, IC<1>{}, 3);
-        step(st + 3, IC<3>{}, IC<1>{}, 3);
-        step(st + 4, IC<4>{}, IC<1>{}, 3);
-        step(st + 5, IC<5>{}, IC<1>{}, 3);
+    for (; st + 6 <= nks; st += 6) {
+        step(st + 0, IC<0>{});
+        step(st + 1, IC<1>{});
+        step(st + 2, IC<2>{});
+        step(st + 3, IC<3>{});
+        step(st + 4, IC<4>{});
+        step(st + 5, IC<5>{});
     }
-    // tail: at most eight steps, same rotation, loads guarded at run time (st is a multiple of 6 here)
-    static_for<8>([&](auto i) {
-        const int s2 = st + i.value;
-        if (s2 < nks) step(s2, IC<i.value % 6>{}, IC<0>{}, nks - 1 - s2);
+    // tail: at most five steps, same rotation (st is a multiple of 6 here)
+    static_for<5>([&](auto i) {
+        if (st + i.value < nks) step(st + i.value, i);
     });
     __syncthreads();      // every wave is done with the LDS slots before the epilogue reuses them
 
