@@ -351,6 +351,13 @@ hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws
 //     (lane L: column L%32, k group L/32), conflict-free.
 // ------------------------------------------------------------------------------------------
 
+// One wave copies 64 x 16 bytes global -> LDS without passing registers: lane i reads 16 bytes at its own
+// address src and the data lands at LDS byte address lds + 16 i (lds is the same for the whole wave).
+__device__ __forceinline__ void lds_dma16(uint32_t lds, const void* src)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");
+}
+
 // Workgroup barrier that orders LDS traffic only (waits lgkmcnt, not vmcnt): __syncthreads() would
 // also drain every outstanding global load and with it the register prefetch of the next stage.
 __device__ __forceinline__ void lds_barrier()
@@ -428,20 +435,24 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     const size_t a_kstep = (size_t)2 * g.Grows;     // one 16-k substep
     const size_t a_stage = (size_t)4 * g.Grows;
 
-    // Software pipeline over the K stages (32 contraction rows each).  Global loads run two stages
-    // ahead of the matrix cores so that an L2 miss (the span and the basis stream from HBM / the
-    // Infinity Cache) has two stages of MFMA work to arrive:
-    //   step s:  issue  basis(s+2) -> aset[(s+2)%3]         (global -> registers)
-    //            issue  span(s+3)  -> xr[(s+1)%2]           (global -> registers)
-    //            read   span(s+1)  LDS slot (s+1)%2 -> xf[(s+1)%2]
-    //            MFMA   stage s    (aset[s%3], xf[s%2])
-    //            write  span(s+2)  xr[s%2] -> LDS slot s%2,  barrier
-    // Register buffers rotate with periods 3 and 2, so the loop body is six steps long.
+    // Software pipeline over the K stages (32 contraction rows each).  Global traffic runs three stages ahead of
+    // the matrix cores so that an L2 miss (the span and the basis stream from HBM / the Infinity Cache) has two
+    // stages of MFMA work to arrive:
+    //   step s:  issue  span(s+3)  -> LDS slot (s+3)%4       (global -> LDS directly, no registers)
+    //            issue  basis(s+3) -> aset[(s+3)%4]          (global -> registers)
+    //            read   span(s+1)  LDS slot (s+1)%4 -> xf[(s+1)%2]
+    //            MFMA   stage s    (aset[s%4], xf[s%2])
+    //            wait until span(s+2) has landed, barrier
+    // Register buffers rotate with periods 4 and 2, so the loop body is four steps long.  Nothing in a step is
+    // conditional: near the end the stage indices are clamped (the last stage is requested again, into slots
+    // and registers nobody reads), so that every step is the same straight-line code and the loads in flight
+    // can be counted exactly; with guarded loads the compiler made each group of matrix instructions wait for
+    // loads issued in the same step.
     constexpr int XR = XSTAGE / (NT * 16);  // 16-byte pieces per thread per stage
     constexpr int XPIECE = NT * 16;         // bytes the workgroup moves per piece
-    half8 aset[3][2][MBN];                  // basis fragments [buffer][16-k substep][row block]
+    static_assert(4 * XSTAGE <= LDS_BYTES, "four span stages in LDS");
+    half8 aset[4][2][MBN];                  // basis fragments [buffer][16-k substep][row block]
     half8 xf[2][2][4];                      // span fragments  [buffer][16-k substep][column block]
-    half8 xr[2][XR];                        // span stages in flight global -> LDS
     const int tid16 = threadIdx.x * 16;
 
     auto load_a = [&](int st, auto buf) {
@@ -450,17 +461,22 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             static_for<MBN>([&](auto mb) { aset[buf.value][u.value][mb.value] = pa[u.value * a_kstep + mb.value * 32]; });
         });
     };
-    auto load_x = [&](int st, auto buf) {
+    // Direct global -> LDS copy of one span stage: lane i of a wave delivers its 16 bytes to M0 + 16 i, so a
+    // piece of XPIECE bytes arrives in the order it has in the workspace.  Written as assembly because the
+    // compiler, which cannot tell the ring slots apart, would wait for a copy issued through its builtin in
+    // front of the next LDS read; it does not count these copies, so the waits for them are placed by hand and
+    // its own waits for the basis loads are at worst early.  M0 has no other user in this kernel.
+    const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem +
+                              __builtin_amdgcn_readfirstlane(wave) * 1024;
+    auto dma_x = [&](int st) {
         const char* src = xsrc + (size_t)st * XSTAGE + tid16;
-        static_for<XR>([&](auto r) { xr[buf.value][r.value] = *(const half8*)(src + r.value * XPIECE); });
-    };
-    auto write_x = [&](auto slot, auto buf) {
+        const uint32_t dst = lds_wave + (st & 3) * XSTAGE;
         static_for<XR>([&](auto r) {
-            *(half8*)(smem + slot.value * XSTAGE + r.value * XPIECE + tid16) = xr[buf.value][r.value];
+            lds_dma16(dst + r.value * XPIECE, src + r.value * XPIECE);
         });
     };
-    auto read_xf = [&](auto slot, auto buf) {
-        const char* xs = smem + slot.value * XSTAGE + par * 8192;
+    auto read_xf = [&](int st, auto buf) {
+        const char* xs = smem + (st & 3) * XSTAGE + par * 8192;
         static_for<2>([&](auto u) {
             static_for<4>([&](auto nb) {
                 xf[buf.value][u.value][nb.value] =
@@ -468,75 +484,64 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
             });
         });
     };
-    // One step at phase PH = s mod 6.  Nothing in a step is conditional: near the end the loads ask for the last
-    // stage again (stage indices are clamped) and the LDS traffic moves copies nobody uses, so that every step
-    // is the same straight-line code and the compiler can count the loads in flight exactly; with guarded loads
-    // it made each group of matrix instructions wait for loads issued in the same step.
-    // The 32 MFMAs run as 8 groups of 4 (one basis fragment against the 4 column blocks); the
-    // step's 12 global loads, 8 LDS fragment reads and XR LDS stores are dealt out between the
-    // groups, so the vector-memory and LDS queues drain while the matrix cores work instead of
-    // blocking the wave in one burst at the top of the step.
+    // One step at phase PH = s mod 4.  The 32 MFMAs run as 8 groups of 4 (one basis fragment against the 4
+    // column blocks); the step's 8 basis loads and 8 LDS fragment reads are dealt out between the groups, so
+    // the vector-memory and LDS queues drain while the matrix cores work instead of blocking the wave in one
+    // burst at the top of the step.
     auto step = [&](int st, auto ph) {
         constexpr int PH = decltype(ph)::value;
-        constexpr int A0 = PH % 3, A2 = (PH + 2) % 3, X0 = PH % 2, X1 = (PH + 1) % 2;
-        const char* xsrc_s = xsrc + (size_t)min(st + 3, nks - 1) * XSTAGE + tid16;
-        const half8* pa = Gv + a_lane + (size_t)min(st + 2, nks - 1) * a_stage;
-        const char* xs = smem + X1 * XSTAGE + par * 8192;
+        constexpr int A0 = PH % 4, A3 = (PH + 3) % 4, X0 = PH % 2, X1 = (PH + 1) % 2;
+        const int ahead = min(st + 3, nks - 1);
+        dma_x(ahead);
+        const half8* pa = Gv + a_lane + (size_t)ahead * a_stage;
+        const char* xs = smem + ((st + 1) & 3) * XSTAGE + par * 8192;
         constexpr int NG = 2 * MBN;             // MFMA groups per step: (substep u, row block mb)
         constexpr int RPG = 8 / NG;             // LDS fragment reads per group
         static_for<NG>([&](auto gi) {
             constexpr int G = decltype(gi)::value;
             constexpr int U = G / MBN, MB = G % MBN;
-            // global loads: basis fragment G of stage s+2, and one span piece while there are any
-            aset[A2][U][MB] = pa[U * a_kstep + MB * 32];
-            if constexpr (G < XR) {
-                xr[X1][G] = *(const half8*)(xsrc_s + G * XPIECE);
-            }
-            // LDS: fragments of stage s+1
-            static_for<RPG>([&](auto ri) {
+            aset[A3][U][MB] = pa[U * a_kstep + MB * 32];         // basis fragment G of stage s+3
+            static_for<RPG>([&](auto ri) {                         // fragments of stage s+1
                 constexpr int F = G * RPG + decltype(ri)::value, FU = F / 4, FN = F % 4;
                 xf[X1][FU][FN] = *(const half8*)(xs + (((FU * 2 + lhi) * kColTile) + FN * 32 + l32) * 16);
             });
-            // LDS: store the span pieces of stage s+2 late in the step (they were loaded one step ago)
-            if constexpr (G >= NG - XR) {
-                constexpr int R = G - (NG - XR);
-                *(half8*)(smem + X0 * XSTAGE + R * XPIECE + tid16) = xr[X0][R];
-            }
             static_for<4>([&](auto nb) {
                 acc[MB][nb.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
                     aset[A0][U][MB], xf[X0][U][nb.value], acc[MB][nb.value], 0, 0, 0);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
+        // span(s+2) was requested one step ago; younger than it are that step's NG basis loads and this step's
+        // XR copies and NG basis loads
+        asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * NG + XR) : "memory");
         lds_barrier();
     };
 
-    // prologue: span stages 0,1 -> LDS, stage 2 in flight; basis stages 0,1 in flight
+    // prologue: span stages 0..2 -> LDS, basis stages 0..2 in flight
     {
-        load_x(0, IC<0>{});
+        dma_x(0);
         load_a(0, IC<0>{});
-        load_x(min(1, nks - 1), IC<1>{});
+        dma_x(min(1, nks - 1) == 1 ? 1 : 0);
         load_a(min(1, nks - 1), IC<1>{});
-        write_x(IC<0>{}, IC<0>{});
-        write_x(IC<1>{}, IC<1>{});
-        load_x(min(2, nks - 1), IC<0>{});
+        if (nks > 2) dma_x(2);
+        load_a(min(2, nks - 1), IC<2>{});
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         lds_barrier();
-        read_xf(IC<0>{}, IC<0>{});
+        read_xf(0, IC<0>{});
     }
 
     int st = 0;
-    for (; st + 6 <= nks; st += 6) {
+    for (; st + 4 <= nks; st += 4) {
         step(st + 0, IC<0>{});
         step(st + 1, IC<1>{});
         step(st + 2, IC<2>{});
         step(st + 3, IC<3>{});
-        step(st + 4, IC<4>{});
-        step(st + 5, IC<5>{});
     }
-    // tail: at most five steps, same rotation (st is a multiple of 6 here)
-    static_for<5>([&](auto i) {
+    // tail: at most three steps, same rotation (st is a multiple of 4 here)
+    static_for<3>([&](auto i) {
         if (st + i.value < nks) step(st + i.value, i);
     });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy may land in LDS once the epilogue owns it
     __syncthreads();      // every wave is done with the LDS slots before the epilogue reuses them
 
     // ---- epilogue ------------------------------------------------------------------------
