@@ -46,18 +46,10 @@ __device__ __forceinline__ void static_for(F&& f)
 
 // ---- P consecutive channels (P = 4 or 8), as stored and as floats ---------------------------------
 template <typename T, int P> struct Raw;
-template <> struct Raw<uint16_t, 8> { u32x4 a; };
 template <> struct Raw<uint16_t, 4> { u32x2 a; };
-template <> struct Raw<float, 8>    { f32x4 a, b; };
 template <> struct Raw<float, 4>    { f32x4 a; };
 
-__device__ __forceinline__ void load_raw(const uint16_t* p, Raw<uint16_t, 8>& r) { r.a = *(const u32x4*)p; }
 __device__ __forceinline__ void load_raw(const uint16_t* p, Raw<uint16_t, 4>& r) { r.a = *(const u32x2*)p; }
-__device__ __forceinline__ void load_raw(const float* p, Raw<float, 8>& r)
-{
-    r.a = *(const f32x4*)p;
-    r.b = *(const f32x4*)(p + 4);
-}
 __device__ __forceinline__ void load_raw(const float* p, Raw<float, 4>& r) { r.a = *(const f32x4*)p; }
 
 template <int P> __device__ __forceinline__ void unpack(const Raw<uint16_t, P>& r, float (&f)[P])
@@ -66,14 +58,6 @@ template <int P> __device__ __forceinline__ void unpack(const Raw<uint16_t, P>& 
         constexpr int I = decltype(i)::value;
         f[2 * I]     = __uint_as_float(r.a[I] << 16);
         f[2 * I + 1] = __uint_as_float(r.a[I] & 0xffff0000u);
-    });
-}
-__device__ __forceinline__ void unpack(const Raw<float, 8>& r, float (&f)[8])
-{
-    static_for<4>([&](auto i) {
-        constexpr int I = decltype(i)::value;
-        f[I] = r.a[I];
-        f[4 + I] = r.b[I];
     });
 }
 __device__ __forceinline__ void unpack(const Raw<float, 4>& r, float (&f)[4])

@@ -47,7 +47,6 @@ constexpr int kKeyTile = 32;       // keys per tile
 constexpr int kQPerWave = 32;      // queries per wave
 constexpr int kPrefillWaves = 8;   // waves per workgroup of the attention kernel
 constexpr int kTileBytes = kKeyTile * kD * 2;   // one Kr or Vt tile, fp16
-constexpr float kMinusBig = -1.0e30f;
 constexpr float kSlack = 14.0f;    // log2 of the largest un-rescaled softmax weight (an fp16 operand: < 2^16)
 constexpr float kWeightLimit = 16384.0f;   // 2^kSlack
 
@@ -337,8 +336,7 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
 
     // One step: tile t, whose scores minus m are in s, is consumed while the scores of tile t+1 go to n.
     bool first = true;          // the first tile sets the reference points whatever the scores are
-    auto step = [&](auto par, int t, f32x16& s, f32x16& n) {
-        constexpr int P = decltype(par)::value;           // t % 2: the Vt slot
+    auto step = [&](int t, f32x16& s, f32x16& n) {
         const bool mine = t < my_tiles;
         if (mine) {
             if (t >= full_tiles) mask_tile(t, s);
@@ -407,8 +405,8 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     // wait would also cover the tile loads just issued).
     asm volatile("" : "+v"(qf[0]), "+v"(qf[1]), "+v"(qf[2]), "+v"(qf[3]), "+v"(qf[4]), "+v"(qf[5]), "+v"(qf[6]), "+v"(qf[7]));
     for (int t = 0; t < wg_tiles; t += 2) {
-        step(IC<0>{}, t, cur, nxt);
-        if (t + 1 < wg_tiles) step(IC<1>{}, t + 1, nxt, cur);
+        step(t, cur, nxt);
+        if (t + 1 < wg_tiles) step(t + 1, nxt, cur);
     }
 
     // ---- normalise and store: lane = query, registers = channels 8*(r/4) + 4*hw + r%4 of each block
