@@ -262,11 +262,11 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     const int tid16 = threadIdx.x * 16;
     const int frag = (hw * kKeyTile + l32) * 16;       // this lane's 16 bytes inside a k-step of a tile
 
-    // Tiles travel global -> registers -> LDS.  Step t consumes tile t: it computes S(t+1) = Kr(t+1) Qr^T while
-    // the softmax of S(t) runs, then O^T += Vt(t) P(t)^T.  Kr(t+3) is loaded at the start of step t and stored
-    // before the barrier that ends it, Vt(t+2) likewise but stored after that barrier (its slot holds Vt(t)
-    // until then).  Keys are two barriers ahead of their use so that the first fragments of Kr(t+2) can be read
-    // before the barrier of step t: the matrix instructions of step t+1 then start right behind it.
+    // Step t consumes tile t: it computes S(t+1) = Kr(t+1) Qr^T while the softmax of S(t) runs, then
+    // O^T += Vt(t) P(t)^T.  Kr(t+3) and Vt(t+3) are requested at the start of step t, straight into their ring
+    // slots (whose tiles t-1 were consumed a step ago), and have landed at the barrier that ends it.  Keys are
+    // thus two barriers ahead of their use, so that the first fragments of Kr(t+2) can be read before the
+    // barrier of step t: the matrix instructions of step t+1 then start right behind it.
     // Direct global -> LDS copy of one tile: lane i of a wave delivers its 16 bytes to M0 + 16 i.  Written as
     // assembly because the compiler, which cannot tell the ring slots apart, would wait for a copy issued
     // through its builtin in front of the next LDS read; the waits are placed by hand, before each barrier.
