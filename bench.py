@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes (read + write) of the contraction of one trigger (two launches with the two-level fold), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by what the same counters read for the library's plain copy
 # kernel (profiles/contract_llama3_8b_128k_pmc.txt).
-TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.245e5 + 9.362e5) + 1.0 * (2.62e5 + 5.609e5)) * 1024}
+TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.244e5 + 9.187e5) + 1.0 * (2.62e5 + 5.24e5)) * 1024}
 TRAFFIC_BYTES_SINGLE_FOLD = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
 # the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
 ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
