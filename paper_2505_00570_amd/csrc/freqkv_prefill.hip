@@ -137,33 +137,40 @@ __global__ void k_prefill_prep_k(const SlabTable tab, const PrefillGeom g, const
     *(half8*)dst = out;
 }
 
-// One thread per (unit, tile, 16-byte group of a Vt tile).
+// One workgroup per (unit, tile of 32 keys): the 32 x 128 bf16 block of V is read row by row with 16-byte
+// loads, turned through LDS, and written as the Vt tile.
 // Vt tile layout (fp16): [channel block db = 0..3][k-step t = 0..1][half-wave hw = 0..1][channel 0..31][8 keys].
-__global__ void k_prefill_prep_v(const SlabTable tab, const PrefillGeom g, _Float16* __restrict__ Vt)
+__global__ __launch_bounds__(256) void k_prefill_prep_v(const SlabTable tab, const PrefillGeom g, _Float16* __restrict__ Vt)
 {
-    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int groups = kKeyTile * kD / 8;                     // 16-byte groups per tile
-    long long total = (long long)g.units * g.key_tiles * groups;
-    if (idx >= total) return;
-    int grp = (int)(idx % groups);
-    long long rest = idx / groups;
-    int tile = (int)(rest % g.key_tiles);
-    int unit = (int)(rest / g.key_tiles);
-    int dl = grp & 31, hw = (grp >> 5) & 1, t = (grp >> 6) & 1, db = grp >> 7;
-    int layer = unit / g.units_per_layer;
-    int rem = unit - layer * g.units_per_layer;
-    int b = rem / g.n_kv, kvh = rem - b * g.n_kv;
+    __shared__ uint32_t sm[kKeyTile][kD / 2 + 1];             // [key][pair of channels], one word of padding per row
+    const int tile = blockIdx.x % g.key_tiles;
+    const int unit = blockIdx.x / g.key_tiles;
+    const int layer = unit / g.units_per_layer;
+    const int rem = unit - layer * g.units_per_layer;
+    const int b = rem / g.n_kv, kvh = rem - b * g.n_kv;
     const uint16_t* head = (const uint16_t*)tab.base[2 * layer + 1] + (long long)b * g.stride_batch +
                            (long long)kvh * g.stride_head;
-    const int ch = db * 32 + dl;
-    half8 out;
-    for (int e = 0; e < 8; ++e) {
-        int key = tile * kKeyTile + vt_key(16 * t + 8 * hw + e);
-        float x = 0.f;
-        if (key < g.cur_len) x = __uint_as_float((uint32_t)head[(long long)key * g.stride_token + ch] << 16);
-        out[e] = (_Float16)x;
+    for (int piece = threadIdx.x; piece < kKeyTile * (kD / 8); piece += 256) {
+        const int key = piece / (kD / 8), seg = piece % (kD / 8);
+        const int row = tile * kKeyTile + key;
+        u32x4 w = {0u, 0u, 0u, 0u};                           // rows beyond cur_len are zero
+        if (row < g.cur_len) w = *(const u32x4*)(head + (long long)row * g.stride_token + seg * 8);
+        static_for<4>([&](auto i) { sm[key][seg * 4 + i.value] = w[i.value]; });
     }
-    *(half8*)(Vt + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) + (long long)grp * 8) = out;
+    __syncthreads();
+    // thread = (k-step t, half-wave hw, pair of channels): two adjacent 16-byte groups of the tile
+    const int cp = threadIdx.x & 63, hw = (threadIdx.x >> 6) & 1, t = threadIdx.x >> 7;
+    half8 lo, hi;
+    static_for<8>([&](auto e) {
+        const uint32_t w = sm[vt_key(16 * t + 8 * hw + e.value)][cp];
+        lo[e.value] = (_Float16)bf16_lo(w);
+        hi[e.value] = (_Float16)bf16_hi(w);
+    });
+    const int ch = 2 * cp, db = ch >> 5, dl = ch & 31;
+    _Float16* dst = Vt + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) +
+                    (long long)(((db * 2 + t) * 2 + hw) * 32 + dl) * 8;
+    *(half8*)dst = lo;
+    *(half8*)(dst + 8) = hi;
 }
 
 // One thread per (query head, query row, group of 8 channels): rotate at the query's in-cache position,
@@ -447,7 +454,7 @@ hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, co
     {
         long long total = (long long)g.units * g.key_tiles * kKeyTile * (kD / 8);
         hipLaunchKernelGGL(k_prefill_prep_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, cs, Kr);
-        hipLaunchKernelGGL(k_prefill_prep_v, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, Vt);
+        hipLaunchKernelGGL(k_prefill_prep_v, dim3((unsigned)((long long)g.units * g.key_tiles)), dim3(256), 0, st, tab, g, Vt);
     }
     {
         long long total = (long long)g.units * g.G * g.q_pad * (kD / 8);
