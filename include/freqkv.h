@@ -260,7 +260,7 @@ FREQKV_API freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, f
 
 /* Result of the chunk-attention buffer-plan query (host arithmetic only). */
 typedef struct freqkv_prefill_plan {
-    size_t  workspace_bytes;    /* rotary table, rotated keys, transposed values, rotated queries (fp16)      */
+    size_t  workspace_bytes;    /* rotary table (fp32), rotated keys and transposed values (fp16)             */
     int32_t key_tiles;          /* ceil(cur_len / 32)                                                         */
     int32_t query_blocks;       /* ceil(q_len / 32)                                                           */
     double  flops;              /* 4 * head_dim per (query, visible row), summed                              */

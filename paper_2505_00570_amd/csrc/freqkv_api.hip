@@ -861,7 +861,7 @@ namespace {
 struct PrefillShape {
     AttShape a;
     int q_len, q_pad, key_tiles, layers_per_pass;
-    size_t off_kr, off_vt, off_qr, workspace_bytes;
+    size_t off_kr, off_vt, workspace_bytes;
 };
 
 freqkv_status_t check_prefill(const freqkv_layout_t* L, int n_q, int n_kv, int d, int cur_len, int q_len,
@@ -880,11 +880,9 @@ freqkv_status_t check_prefill(const freqkv_layout_t* L, int n_q, int n_kv, int d
     if (units * p.a.G * (p.q_pad / 32) > (1LL << 30)) return FREQKV_E_UNSUPPORTED;
     size_t cs_bytes = (size_t)round_up((long long)cur_len * (d / 2) * 8, 256);
     size_t kv_bytes = (size_t)units * p.key_tiles * 32 * d * 2;
-    size_t q_bytes = (size_t)units * p.a.G * p.q_pad * d * 2;
     p.off_kr = cs_bytes;
     p.off_vt = p.off_kr + kv_bytes;
-    p.off_qr = p.off_vt + kv_bytes;
-    p.workspace_bytes = p.off_qr + q_bytes;
+    p.workspace_bytes = p.off_vt + kv_bytes;
     *out = p;
     return FREQKV_OK;
 }
@@ -956,13 +954,12 @@ freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, const void* 
         char* op = (char*)out + head0 * q_len * a.d * a.elem;
         ProfSpan sp;
         HIP_TRY(prof_begin(st, 0, &sp));
-        HIP_TRY(launch_prefill_prepare(tab, g, qp, rope_base > 0.0 ? rope_base : 1.0, (float2*)ws,
-                                       (_Float16*)(ws + p.off_kr), (_Float16*)(ws + p.off_vt),
-                                       (_Float16*)(ws + p.off_qr), st));
+        HIP_TRY(launch_prefill_prepare(tab, g, rope_base > 0.0 ? rope_base : 1.0, (float2*)ws,
+                                       (_Float16*)(ws + p.off_kr), (_Float16*)(ws + p.off_vt), st));
         HIP_TRY(prof_end(st, &sp));
         HIP_TRY(prof_begin(st, 3, &sp));
-        HIP_TRY(launch_attend_prefill(g, (const _Float16*)(ws + p.off_kr), (const _Float16*)(ws + p.off_vt),
-                                      (const _Float16*)(ws + p.off_qr), op, lse ? lse + head0 * q_len : nullptr, st));
+        HIP_TRY(launch_attend_prefill(g, (const _Float16*)(ws + p.off_kr), (const _Float16*)(ws + p.off_vt), qp,
+                                      (const float2*)ws, op, lse ? lse + head0 * q_len : nullptr, st));
         HIP_TRY(prof_end(st, &sp));
     }
     return FREQKV_OK;

@@ -141,9 +141,9 @@ struct PrefillGeom {
 
 // cs: [cur_len][d/2] (cos, sin); Kr, Vt: [units][key_tiles] tiles of 32 keys x d fp16 in fragment order;
 // Qr: [units*G][q_pad][d] fp16.  q: dense [units*G][q_len][d] bf16.
-hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, const void* q, double rope_base,
-                                  float2* cs, _Float16* Kr, _Float16* Vt, _Float16* Qr, hipStream_t st);
-hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const _Float16* Qr,
+hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, double rope_base, float2* cs,
+                                  _Float16* Kr, _Float16* Vt, hipStream_t st);
+hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const void* q, const float2* cs,
                                  void* out, float* lse, hipStream_t st);
 
 }  // namespace freqkv

@@ -6,18 +6,18 @@
 // row index when they are read; queries take the one of p_i (closing paragraph of Sec. 3.4).
 //
 // Unlike the one-token case this is a dense contraction (q_len x cur_len x d per head, twice), so it runs
-// on the matrix cores, as a streaming-softmax attention kernel.  Three small passes put the operands into
-// MFMA fragment order first (all fp16: a bf16 cache value is exact in fp16, and the rotated keys and
+// on the matrix cores, as a streaming-softmax attention kernel.  Three small passes put the cached operands
+// into MFMA fragment order first (all fp16: a bf16 cache value is exact in fp16, and the rotated keys and
 // queries keep 11 significant bits instead of 8):
 //   k_prefill_cs      cos/sin of (row * theta_j) for every cached row, fp64 angle reduction, fp32 table
 //   k_prefill_prep_k  Kr = rotate(K) in tiles of 32 keys, [tile][group of 8 channels][key][8]
 //   k_prefill_prep_v  Vt = V transposed in tiles of 32 keys, [tile][channel block][k-step][half][channel][8 keys],
 //                     keys permuted so that a softmax tile, as the matrix core leaves it in registers, is
 //                     already the second operand of the weighted sum
-//   k_prefill_prep_q  Qr = rotate(q) * log2(e)/sqrt(d), row-major
-// and k_attend_prefill computes, per wave, S^T = Kr Qr^T for 32 keys x 32 queries, the running softmax per
-// query (a query is a column, so its maximum and sum are in-lane reductions plus one exchange between the
-// two half-waves), and O^T += Vt P^T.
+// and k_attend_prefill first builds, per wave, Qr = rotate(q) * log2(e)/sqrt(d) for its 32 queries in
+// registers (once), then computes S^T = Kr Qr^T for 32 keys x 32 queries at a time, the running softmax per
+// query (a query is a column, so its sum is an in-lane reduction plus one exchange between the two
+// half-waves at the end), and O^T += Vt P^T.
 #include "freqkv_internal.h"
 
 namespace freqkv {
@@ -173,43 +173,6 @@ __global__ __launch_bounds__(256) void k_prefill_prep_v(const SlabTable tab, con
     *(half8*)(dst + 8) = hi;
 }
 
-// One thread per (query head, query row, group of 8 channels): rotate at the query's in-cache position,
-// scale, store row-major [head][q_pad][d]; rows beyond q_len are zero.
-__global__ void k_prefill_prep_q(const uint16_t* __restrict__ q, const PrefillGeom g,
-                                 const float2* __restrict__ cs, _Float16* __restrict__ Qr)
-{
-    long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int g8n = kD / 8;
-    long long total = (long long)g.units * g.G * g.q_pad * g8n;
-    if (idx >= total) return;
-    int g8 = (int)(idx % g8n);
-    long long rest = idx / g8n;
-    int i = (int)(rest % g.q_pad);
-    long long head = rest / g.q_pad;
-    half8 out;
-    for (int e = 0; e < 8; ++e) out[e] = (_Float16)0.f;
-    if (i < g.q_len) {
-        const uint16_t* row = q + (head * g.q_len + i) * kD;
-        const int half = kD / 2;
-        const bool upper = g8 * 8 >= half;
-        const int j0 = upper ? g8 * 8 - half : g8 * 8;
-        u32x4 own = *(const u32x4*)(row + g8 * 8);
-        u32x4 oth = *(const u32x4*)(row + (upper ? j0 : j0 + half));
-        const int pos = g.cur_len - g.q_len + i;
-        const float2* c = cs + (long long)pos * half + j0;
-        for (int e = 0; e < 4; ++e) {
-            float a0 = bf16_lo(own[e]), a1 = bf16_hi(own[e]);
-            float b0 = bf16_lo(oth[e]), b1 = bf16_hi(oth[e]);
-            float2 c0 = c[2 * e], c1 = c[2 * e + 1];
-            float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
-            float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
-            out[2 * e] = (_Float16)(r0 * g.qscale);
-            out[2 * e + 1] = (_Float16)(r1 * g.qscale);
-        }
-    }
-    *(half8*)(Qr + (head * g.q_pad + i) * kD + g8 * 8) = out;
-}
-
 // Workgroup = 8 waves = 8 tasks of one KV unit, two waves per SIMD; a task is (query head of the KV group,
 // block of 32 queries), heads fastest, so that with 4 query heads per KV head the waves walk the same keys.
 // A wave keeps its 32 queries, their 128 x 32 output block and two 32 x 32 score blocks in vector registers
@@ -217,7 +180,8 @@ __global__ void k_prefill_prep_q(const uint16_t* __restrict__ q, const PrefillGe
 // vector registers).
 __global__ __launch_bounds__(kPrefillWaves * 64, 2)
 void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, const _Float16* __restrict__ Vt,
-                      const _Float16* __restrict__ Qr, uint16_t* __restrict__ out, float* __restrict__ lse)
+                      const uint16_t* __restrict__ q, const float2* __restrict__ cs, uint16_t* __restrict__ out,
+                      float* __restrict__ lse)
 {
     __shared__ __attribute__((aligned(1024))) char ksm[4][kTileBytes];   // Kr tiles t+1, t+2, t+3 of step t (ring)
     __shared__ __attribute__((aligned(1024))) char vsm[4][kTileBytes];   // Vt tiles t .. t+3 (ring)
@@ -251,11 +215,36 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
         wg_tiles = (wg_last + kKeyTile) / kKeyTile;
     }
 
-    // ---- queries of this wave: second operand of S^T = Kr Qr^T, lane = query column, 8 channels per k-step half
+    // ---- queries of this wave: second operand of S^T = Kr Qr^T, lane = query column, 8 channels per k-step half.
+    // Qr = rotate(q at its in-cache position) * log2(e)/sqrt(d), computed here once per wave: the lane's groups
+    // of 8 channels in the lower half (k-steps 0..3) and their rotary partners in the upper half (k-steps 4..7)
+    // come from the same two 16-byte loads.  Rows of the block beyond q_len are zero.
     half8 qf[8];
     {
-        const _Float16* qrow = Qr + (head * g.q_pad + q0 + l32) * kD + hw * 8;
-        static_for<8>([&](auto s) { qf[s.value] = active ? *(const half8*)(qrow + s.value * 16) : half8{}; });
+        const bool have = active && q0 + l32 < g.q_len;
+        const uint16_t* qrow = q + (head * g.q_len + (have ? q0 + l32 : 0)) * kD;
+        const float2* crow = cs + (long long)(have ? pos0 + l32 : 0) * (kD / 2);
+        static_for<4>([&](auto sc) {
+            constexpr int S = decltype(sc)::value;
+            const int j0 = S * 16 + hw * 8;                   // first rotary pair of the group
+            half8 lo8 = {}, up8 = {};
+            if (have) {
+                const u32x4 lo = *(const u32x4*)(qrow + j0), up = *(const u32x4*)(qrow + kD / 2 + j0);
+                static_for<4>([&](auto ec) {
+                    constexpr int E = decltype(ec)::value;
+                    const float a0 = bf16_lo(lo[E]), a1 = bf16_hi(lo[E]);
+                    const float b0 = bf16_lo(up[E]), b1 = bf16_hi(up[E]);
+                    const float2 c0 = crow[j0 + 2 * E], c1 = crow[j0 + 2 * E + 1];
+                    // lower half: x_j cos - x_{j+d/2} sin;  upper half: x_{j+d/2} cos + x_j sin
+                    lo8[2 * E]     = (_Float16)((a0 * c0.x - b0 * c0.y) * g.qscale);
+                    lo8[2 * E + 1] = (_Float16)((a1 * c1.x - b1 * c1.y) * g.qscale);
+                    up8[2 * E]     = (_Float16)((b0 * c0.x + a0 * c0.y) * g.qscale);
+                    up8[2 * E + 1] = (_Float16)((b1 * c1.x + a1 * c1.y) * g.qscale);
+                });
+            }
+            qf[S] = lo8;
+            qf[S + 4] = up8;
+        });
     }
 
     f32x16 acc[4];              // O^T: [channel block], 32 channels x 32 queries each
@@ -441,8 +430,8 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
 // launchers
 // ---------------------------------------------------------------------------------------------
 
-hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, const void* q, double rope_base,
-                                  float2* cs, _Float16* Kr, _Float16* Vt, _Float16* Qr, hipStream_t st)
+hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, double rope_base, float2* cs,
+                                  _Float16* Kr, _Float16* Vt, hipStream_t st)
 {
     if (g.d != kD || g.cur_len < 1 || g.q_len < 1 || g.q_len > g.cur_len) return hipErrorInvalidValue;
     if (g.key_tiles * kKeyTile < g.cur_len || g.q_pad < g.q_len || g.q_pad % kQPerWave) return hipErrorInvalidValue;
@@ -456,21 +445,16 @@ hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, co
         hipLaunchKernelGGL(k_prefill_prep_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, cs, Kr);
         hipLaunchKernelGGL(k_prefill_prep_v, dim3((unsigned)((long long)g.units * g.key_tiles)), dim3(256), 0, st, tab, g, Vt);
     }
-    {
-        long long total = (long long)g.units * g.G * g.q_pad * (kD / 8);
-        hipLaunchKernelGGL(k_prefill_prep_q, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                           (const uint16_t*)q, g, cs, Qr);
-    }
     return hipGetLastError();
 }
 
-hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const _Float16* Qr,
+hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const void* q, const float2* cs,
                                  void* out, float* lse, hipStream_t st)
 {
     if (g.d != kD || g.q_blocks * kQPerWave != g.q_pad) return hipErrorInvalidValue;
     const int wgs_per_unit = (g.G * g.q_blocks + kPrefillWaves - 1) / kPrefillWaves;
     hipLaunchKernelGGL(k_attend_prefill, dim3((unsigned)((long long)g.units * wgs_per_unit)), dim3(kPrefillWaves * 64), 0,
-                       st, g, Kr, Vt, Qr, (uint16_t*)out, lse);
+                       st, g, Kr, Vt, (const uint16_t*)q, cs, (uint16_t*)out, lse);
     return hipGetLastError();
 }
 
