@@ -6,6 +6,16 @@
 
 namespace freqkv {
 
+// One wave copies 64 x 16 bytes global -> LDS without passing registers: lane i reads 16 bytes at its own
+// address src and the data lands at LDS byte address lds + 16 i (lds is the same for the whole wave).  The copy
+// counts as a vector-memory load (vmcnt); the compiler does not know that it writes LDS, so the kernel waits
+// for it by hand (s_waitcnt vmcnt) before the barrier that publishes the data.  M0 carries the LDS address:
+// kernels that use this have no other user of M0.
+__device__ __forceinline__ void lds_dma16(uint32_t lds, const void* src)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");
+}
+
 // One launch group addresses at most this many (layer, K|V) slabs; their base
 // pointers travel by value in the kernel arguments.
 constexpr int kMaxSlabs = 192;

@@ -351,13 +351,6 @@ hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws
 //     (lane L: column L%32, k group L/32), conflict-free.
 // ------------------------------------------------------------------------------------------
 
-// One wave copies 64 x 16 bytes global -> LDS without passing registers: lane i reads 16 bytes at its own
-// address src and the data lands at LDS byte address lds + 16 i (lds is the same for the whole wave).
-__device__ __forceinline__ void lds_dma16(uint32_t lds, const void* src)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");
-}
-
 // Workgroup barrier that orders LDS traffic only (waits lgkmcnt, not vmcnt): __syncthreads() would
 // also drain every outstanding global load and with it the register prefetch of the next stage.
 __device__ __forceinline__ void lds_barrier()

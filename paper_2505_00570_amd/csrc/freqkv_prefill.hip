@@ -263,25 +263,21 @@ void k_attend_prefill(const PrefillGeom g, const _Float16* __restrict__ Kr, cons
     // slots (whose tiles t-1 were consumed a step ago), and have landed at the barrier that ends it.  Keys are
     // thus two barriers ahead of their use, so that the first fragments of Kr(t+2) can be read before the
     // barrier of step t: the matrix instructions of step t+1 then start right behind it.
-    // Direct global -> LDS copy of one tile: lane i of a wave delivers its 16 bytes to M0 + 16 i.  Written as
-    // assembly because the compiler, which cannot tell the ring slots apart, would wait for a copy issued
-    // through its builtin in front of the next LDS read; the waits are placed by hand, before each barrier.
+    // A tile is copied global -> LDS directly, each wave its 1 KB share (the copy is issued from assembly: the
+    // compiler, which cannot tell the ring slots apart, would wait for a copy issued through its builtin in
+    // front of the next LDS read; the waits are placed by hand, before each barrier).
     typedef __attribute__((address_space(3))) char* lptr_t;
     const uint32_t k_lds = (uint32_t)(uintptr_t)(lptr_t)ksm[0] + wave * 1024;
     const uint32_t v_lds = (uint32_t)(uintptr_t)(lptr_t)vsm[0] + wave * 1024;
-    auto dma = [&](const char* src, uint32_t lds) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");   // M0 has no other user in this kernel
-    };
-    auto dma_k = [&](int tile, int slot) { dma(ksrc + (long long)tile * kTileBytes + tid16, k_lds + (slot & 3) * kTileBytes); };
-    auto dma_v = [&](int tile, int slot) { dma(vsrc + (long long)tile * kTileBytes + tid16, v_lds + (slot & 3) * kTileBytes); };
-    // Loads and stores past the last tile are not branched around: they repeat the last tile into a slot that
-    // nobody reads any more, which keeps the loop free of branches and lets the compiler count the loads in
-    // flight exactly.
+    auto dma_k = [&](int tile, int slot) { lds_dma16(k_lds + (slot & 3) * kTileBytes, ksrc + (long long)tile * kTileBytes + tid16); };
+    auto dma_v = [&](int tile, int slot) { lds_dma16(v_lds + (slot & 3) * kTileBytes, vsrc + (long long)tile * kTileBytes + tid16); };
+    // Copies past the last tile are not branched around: they repeat the last tile into a slot that nobody
+    // reads any more, which keeps the loop free of branches.
     const int last_tile = wg_tiles - 1;
     static_for<3>([&](auto i) {
         dma_k(min(i.value, last_tile), i.value);
+        dma_v(min(i.value, last_tile), i.value);
     });
-    static_for<3>([&](auto i) { dma_v(min(i.value, last_tile), i.value); });
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
