@@ -314,6 +314,8 @@ freqkv_status_t check_attend(const freqkv_layout_t* L, int n_q, int n_kv, int d,
     if (L->n_layers > (1 << 20)) return FREQKV_E_UNSUPPORTED;
     long long units = (long long)L->n_layers * L->batch * n_kv;
     if (units * (n_q / n_kv) > (1LL << 24)) return FREQKV_E_UNSUPPORTED;    // grid and index ranges
+    // the attention kernels address the rows of one head by 32-bit byte offsets (a few steps past cur_len included)
+    if (((long long)cur_len + 1024) * L->stride_token * (L->dtype == FREQKV_BF16 ? 2 : 4) >= (1LL << 32)) return FREQKV_E_UNSUPPORTED;
 
     AttShape a;
     a.d = d; a.n_q = n_q; a.n_kv = n_kv; a.G = n_q / n_kv;

@@ -236,32 +236,38 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     // ---- main loop over the rows of this lane group: p0, p0+STEP, p0+2*STEP, ...
     const int nit = row_end > row0 ? (row_end - row0 + STEP * U - 1) / (STEP * U) : 0;
     const int last = cur_len - 1;
-    RawT kl[U], kh[U], vl[U], vh[U];
-    auto issue = [&](int it, RawT (&a)[U], RawT (&bq)[U], RawT (&cv)[U], RawT (&dv)[U]) {
+    // Rows are addressed by 32-bit byte offsets inside the head's slab (uniform base + per-lane offset; the host
+    // checks the range).  Rows past the end re-read the last row: no load is conditional, so the loads in
+    // flight can be counted exactly; such rows are masked in the steps that can contain them.
+    const char* kb = (const char*)kbase;
+    const char* vb = (const char*)vbase;
+    const uint32_t row_bytes = (uint32_t)g.stride_token * (uint32_t)sizeof(T);
+    const uint32_t lane_off = (uint32_t)(P * l) * (uint32_t)sizeof(T);
+    const uint32_t last_off = (uint32_t)last * row_bytes + lane_off;
+    uint32_t next_off = (uint32_t)p0 * row_bytes + lane_off;      // first row of the step to be loaded next
+    struct Rows { RawT kl[U], kh[U], vl[U], vh[U]; };
+    auto issue = [&](Rows& r) {
         static_for<U>([&](auto uu) {
             constexpr int u = decltype(uu)::value;
-            int row = min(p0 + (it * U + u) * STEP, last);      // rows past the end re-read the last row, masked below
-            const T* kp = kbase + (long long)row * g.stride_token;
-            const T* vp = vbase + (long long)row * g.stride_token;
-            load_raw(kp + P * l, a[u]);
-            load_raw(kp + D / 2 + P * l, bq[u]);
-            load_raw(vp + P * l, cv[u]);
-            load_raw(vp + D / 2 + P * l, dv[u]);
+            const uint32_t o = min(next_off + (uint32_t)(u * STEP) * row_bytes, last_off);
+            load_raw((const T*)(kb + o), r.kl[u]);
+            load_raw((const T*)(kb + o) + D / 2, r.kh[u]);
+            load_raw((const T*)(vb + o), r.vl[u]);
+            load_raw((const T*)(vb + o) + D / 2, r.vh[u]);
         });
+        next_off += (uint32_t)(U * STEP) * row_bytes;
     };
-    issue(0, kl, kh, vl, vh);
-    for (int it = 0; it < nit; ++it) {
-        // start the loads of the next step, then consume this step's rows
-        RawT nkl[U], nkh[U], nvl[U], nvh[U];
-        if (it + 1 < nit) issue(it + 1, nkl, nkh, nvl, nvh);
+    // One step: the U rows in r (loaded a step ago) against the GT queries.
+    auto consume = [&](const Rows& r, int it) {
         if (it != 0 && (it & (kReseed - 1)) == 0) seed_rows(p0 + it * U * STEP);
+        const bool tail = row0 + (it + 1) * U * STEP > row_end;       // same for the whole workgroup
 
         float sc[U][GT];
         static_for<U>([&](auto uu) {
             constexpr int u = decltype(uu)::value;
             float a[P], bb[P];
-            unpack(kl[u], a);
-            unpack(kh[u], bb);
+            unpack(r.kl[u], a);
+            unpack(r.kh[u], bb);
             float part[GT];
             static_for<GT>([&](auto gg) { part[decltype(gg)::value] = 0.f; });
             static_for<P>([&](auto jj) {
@@ -277,12 +283,17 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
                 s[j] = s[j] * cd[j] + c[j] * sd[j];
                 c[j] = cn;
             });
-            const bool valid = p0 + (it * U + u) * STEP < row_end;
             static_for<GT>([&](auto gg) {
                 constexpr int gi = decltype(gg)::value;
-                float t = group_sum<LPR>(part[gi]);
-                sc[u][gi] = valid ? t : -INFINITY;
+                sc[u][gi] = group_sum<LPR>(part[gi]);
             });
+            if (tail) {                                        // only the last steps of a chunk can hold rows past its end
+                const bool valid = p0 + (it * U + u) * STEP < row_end;
+                static_for<GT>([&](auto gg) {
+                    constexpr int gi = decltype(gg)::value;
+                    sc[u][gi] = valid ? sc[u][gi] : -INFINITY;
+                });
+            }
         });
 
         static_for<GT>([&](auto gg) {
@@ -304,21 +315,26 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
                 constexpr int u = decltype(uu)::value;
                 float pw = exp2_fast(sc[u][gi] - m[gi]);
                 lsum[gi] += pw;
-                float va[P], vb[P];
-                unpack(vl[u], va);
-                unpack(vh[u], vb);
+                float va[P], vb2[P];
+                unpack(r.vl[u], va);
+                unpack(r.vh[u], vb2);
                 static_for<P>([&](auto jj) {
                     constexpr int j = decltype(jj)::value;
                     acc[gi][j] = fmaf(pw, va[j], acc[gi][j]);
-                    acc[gi][P + j] = fmaf(pw, vb[j], acc[gi][P + j]);
+                    acc[gi][P + j] = fmaf(pw, vb2[j], acc[gi][P + j]);
                 });
             });
         });
-
-        static_for<U>([&](auto uu) {
-            constexpr int u = decltype(uu)::value;
-            kl[u] = nkl[u]; kh[u] = nkh[u]; vl[u] = nvl[u]; vh[u] = nvh[u];
-        });
+    };
+    // Two register sets take turns: while one step is consumed the loads of the next are in flight.  The step
+    // count is rounded up to even; a surplus step sees only rows past the end (weights exactly zero).
+    Rows ra, rb;
+    issue(ra);
+    for (int it = 0; it < nit; it += 2) {
+        issue(rb);
+        consume(ra, it);
+        issue(ra);
+        consume(rb, it + 1);
     }
 
     // ---- combine the lane groups of the workgroup

@@ -122,7 +122,7 @@ constexpr int attend_pairs_per_lane(int d) { return d > 256 ? 8 : 4; }
 // Rows between two consecutive rows handled by one lane group: 4 waves x 64 lanes / (lanes per row).
 constexpr int attend_row_step(int d) { return 4 * 64 / (d / (2 * attend_pairs_per_lane(d))); }
 // Waves per SIMD the compiler must leave room for (bounds the registers of a lane).
-constexpr int attend_min_waves(int elem_bytes, int GT, int P) { return elem_bytes == 2 ? (P == 4 ? (GT == 4 ? 3 : 4) : 2) : (P == 4 ? 2 : 1); }
+constexpr int attend_min_waves(int elem_bytes, int GT, int P) { return elem_bytes == 2 ? (P == 4 ? (GT == 1 ? 4 : 3) : 2) : (P == 4 ? 2 : 1); }
 
 hipError_t launch_rope_table(RopeEntry* rt, int d, double base, hipStream_t st);
 // tab.base[2*i] / [2*i+1]: K / V slab of the pass's i-th layer.  part_acc: [units*G][n_split][d] fp32,
