@@ -247,6 +247,12 @@ def test_attend_plan_invalid_arguments():
     assert call(4, 2, 4, 100) == -1
     assert lib.freqkv_attend_plan(None, 4, 2, 128, 100, C.byref(out)) == -1
     assert lib.freqkv_attend_plan(C.byref(L), 4, 2, 128, 100, None) == -1
+    # rows of one head are addressed by 32-bit byte offsets: a head whose rows span 4 GiB or more is refused
+    big = _layout(n_layers=1, n_heads=1, cap=1 << 20)
+    big.stride_token = 2048                     # token-major interleaving: 4 KiB between rows, 4 GiB per head
+    big.stride_head = 128
+    assert lib.freqkv_attend_plan(C.byref(big), 4, 1, 128, 1 << 19, C.byref(out)) == 0
+    assert lib.freqkv_attend_plan(C.byref(big), 4, 1, 128, 1 << 20, C.byref(out)) == -2
 
 
 def test_attend_decode_validates_without_gpu():
