@@ -195,7 +195,9 @@ FREQKV_API freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window,
 /*
  * Buffer plan of freqkv_attend_decode.  HOST only, like freqkv_plan.  Valid ranges: n_kv_heads >= 1,
  * n_q_heads a multiple of n_kv_heads, 1 <= cur_len <= layout.token_capacity; head_dim 64, 128 or 256
- * (anything else: FREQKV_E_UNSUPPORTED).
+ * (anything else: FREQKV_E_UNSUPPORTED).  The cur_len rows of one head must span less than 4 GiB
+ * ((cur_len + 1024) * stride_token * element size < 2^32; FREQKV_E_UNSUPPORTED otherwise): rows are addressed
+ * by 32-bit byte offsets.  The same limits hold for the chunk-wise entry points below.
  */
 FREQKV_API freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
                                    int head_dim, int cur_len, freqkv_attend_plan_t* out);
