@@ -183,6 +183,34 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     const int row_end = min(row0 + g.chunk, cur_len);   // <= row0 for a chunk beyond a short sequence: no rows
     const int p0 = row0 + wave * RPW + slot;           // first row of this lane group
 
+    // ---- rows of this lane group: p0, p0+STEP, p0+2*STEP, ...
+    const int nit = row_end > row0 ? (row_end - row0 + STEP * U - 1) / (STEP * U) : 0;
+    const int last = cur_len - 1;
+    // Rows are addressed by 32-bit byte offsets inside the head's slab (uniform base + per-lane offset; the host
+    // checks the range).  Rows past the end re-read the last row: no load is conditional, so the loads in
+    // flight can be counted exactly; such rows are masked in the steps that can contain them.
+    const char* kb = (const char*)kbase;
+    const char* vb = (const char*)vbase;
+    const uint32_t row_bytes = (uint32_t)g.stride_token * (uint32_t)sizeof(T);
+    const uint32_t lane_off = (uint32_t)(P * l) * (uint32_t)sizeof(T);
+    const uint32_t last_off = (uint32_t)last * row_bytes + lane_off;
+    uint32_t next_off = (uint32_t)p0 * row_bytes + lane_off;      // first row of the step to be loaded next
+    struct Rows { RawT kl[U], kh[U], vl[U], vh[U]; };
+    auto issue = [&](Rows& r) {
+        static_for<U>([&](auto uu) {
+            constexpr int u = decltype(uu)::value;
+            const uint32_t o = min(next_off + (uint32_t)(u * STEP) * row_bytes, last_off);
+            load_raw((const T*)(kb + o), r.kl[u]);
+            load_raw((const T*)(kb + o) + D / 2, r.kh[u]);
+            load_raw((const T*)(vb + o), r.vl[u]);
+            load_raw((const T*)(vb + o) + D / 2, r.vh[u]);
+        });
+        next_off += (uint32_t)(U * STEP) * row_bytes;
+    };
+    // the first rows are requested before anything else: the seeds below need no cache data
+    Rows ra, rb;
+    issue(ra);
+
     // ---- rotary state of the P pairs this lane owns: pair j couples channels P*l+j and D/2+P*l+j.
     // (c, s) = cos/sin of (row position * theta_j); each processed row advances them by the fixed rotation
     // (cd, sd) of STEP rows, and every kReseed loop steps they are recomputed exactly.
@@ -234,29 +262,6 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     });
 
     // ---- main loop over the rows of this lane group: p0, p0+STEP, p0+2*STEP, ...
-    const int nit = row_end > row0 ? (row_end - row0 + STEP * U - 1) / (STEP * U) : 0;
-    const int last = cur_len - 1;
-    // Rows are addressed by 32-bit byte offsets inside the head's slab (uniform base + per-lane offset; the host
-    // checks the range).  Rows past the end re-read the last row: no load is conditional, so the loads in
-    // flight can be counted exactly; such rows are masked in the steps that can contain them.
-    const char* kb = (const char*)kbase;
-    const char* vb = (const char*)vbase;
-    const uint32_t row_bytes = (uint32_t)g.stride_token * (uint32_t)sizeof(T);
-    const uint32_t lane_off = (uint32_t)(P * l) * (uint32_t)sizeof(T);
-    const uint32_t last_off = (uint32_t)last * row_bytes + lane_off;
-    uint32_t next_off = (uint32_t)p0 * row_bytes + lane_off;      // first row of the step to be loaded next
-    struct Rows { RawT kl[U], kh[U], vl[U], vh[U]; };
-    auto issue = [&](Rows& r) {
-        static_for<U>([&](auto uu) {
-            constexpr int u = decltype(uu)::value;
-            const uint32_t o = min(next_off + (uint32_t)(u * STEP) * row_bytes, last_off);
-            load_raw((const T*)(kb + o), r.kl[u]);
-            load_raw((const T*)(kb + o) + D / 2, r.kh[u]);
-            load_raw((const T*)(vb + o), r.vl[u]);
-            load_raw((const T*)(vb + o) + D / 2, r.vh[u]);
-        });
-        next_off += (uint32_t)(U * STEP) * row_bytes;
-    };
     // One step: the U rows in r (loaded a step ago) against the GT queries.
     auto consume = [&](const Rows& r, int it) {
         if (it != 0 && (it & (kReseed - 1)) == 0) seed_rows(p0 + it * U * STEP);
@@ -328,8 +333,6 @@ void k_attend_partial(const SlabTable tab, const AttGeom g, const T* __restrict_
     };
     // Two register sets take turns: while one step is consumed the loads of the next are in flight.  The step
     // count is rounded up to even; a surplus step sees only rows past the end (weights exactly zero).
-    Rows ra, rb;
-    issue(ra);
     for (int it = 0; it < nit; it += 2) {
         issue(rb);
         consume(ra, it);
