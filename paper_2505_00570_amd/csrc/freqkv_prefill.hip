@@ -94,47 +94,46 @@ __global__ void k_prefill_cs(float2* __restrict__ cs, int rows, int d, double ba
     cs[idx] = o;
 }
 
-// One thread per (unit, key row, group of 8 channels): rotate and store in fragment order.
+// One thread per (unit, key row, group of 8 rotary pairs): rotate and store in fragment order; the group of
+// the lower half and its partner group of the upper half come from the same two 16-byte loads.
 // Kr tile layout (fp16): [group of 8 channels g8 = 0..15][key 0..31][8].
 __global__ void k_prefill_prep_k(const SlabTable tab, const PrefillGeom g, const float2* __restrict__ cs,
                                  _Float16* __restrict__ Kr)
 {
     long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int g8n = kD / 8;
-    long long total = (long long)g.units * g.key_tiles * kKeyTile * g8n;
+    constexpr int half = kD / 2;
+    constexpr int pgn = half / 8;                             // groups of 8 pairs per row
+    long long total = (long long)g.units * g.key_tiles * kKeyTile * pgn;
     if (idx >= total) return;
-    int g8 = (int)(idx % g8n);
-    long long rest = idx / g8n;
+    int pg = (int)(idx % pgn);
+    long long rest = idx / pgn;
     int p = (int)(rest % ((long long)g.key_tiles * kKeyTile));
     int unit = (int)(rest / ((long long)g.key_tiles * kKeyTile));
-    half8 out;
-    for (int i = 0; i < 8; ++i) out[i] = (_Float16)0.f;
+    half8 lo8 = {}, up8 = {};                                 // rows beyond cur_len are zero
     if (p < g.cur_len) {
         int layer = unit / g.units_per_layer;
         int rem = unit - layer * g.units_per_layer;
         int b = rem / g.n_kv, kvh = rem - b * g.n_kv;
         const uint16_t* row = (const uint16_t*)tab.base[2 * layer] + (long long)b * g.stride_batch +
                               (long long)kvh * g.stride_head + (long long)p * g.stride_token;
-        const int half = kD / 2;
-        const bool upper = g8 * 8 >= half;
-        const int j0 = upper ? g8 * 8 - half : g8 * 8;         // first rotary pair of this group
-        u32x4 own = *(const u32x4*)(row + g8 * 8);
-        u32x4 oth = *(const u32x4*)(row + (upper ? j0 : j0 + half));
+        const int j0 = pg * 8;                                // first rotary pair of this group
+        const u32x4 lo = *(const u32x4*)(row + j0), up = *(const u32x4*)(row + half + j0);
         const float2* c = cs + (long long)p * half + j0;
         for (int i = 0; i < 4; ++i) {
-            float a0 = bf16_lo(own[i]), a1 = bf16_hi(own[i]);
-            float b0 = bf16_lo(oth[i]), b1 = bf16_hi(oth[i]);
+            float a0 = bf16_lo(lo[i]), a1 = bf16_hi(lo[i]);
+            float b0 = bf16_lo(up[i]), b1 = bf16_hi(up[i]);
             float2 c0 = c[2 * i], c1 = c[2 * i + 1];
             // lower half: x_j cos - x_{j+d/2} sin;  upper half: x_{j+d/2} cos + x_j sin
-            float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
-            float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
-            out[2 * i] = (_Float16)r0;
-            out[2 * i + 1] = (_Float16)r1;
+            lo8[2 * i]     = (_Float16)(a0 * c0.x - b0 * c0.y);
+            lo8[2 * i + 1] = (_Float16)(a1 * c1.x - b1 * c1.y);
+            up8[2 * i]     = (_Float16)(b0 * c0.x + a0 * c0.y);
+            up8[2 * i + 1] = (_Float16)(b1 * c1.x + a1 * c1.y);
         }
     }
     int tile = p / kKeyTile, key = p % kKeyTile;
-    _Float16* dst = Kr + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) + ((long long)g8 * kKeyTile + key) * 8;
-    *(half8*)dst = out;
+    _Float16* dst = Kr + ((long long)unit * g.key_tiles + tile) * (kKeyTile * kD) + ((long long)pg * kKeyTile + key) * 8;
+    *(half8*)dst = lo8;
+    *(half8*)(dst + (long long)pgn * kKeyTile * 8) = up8;
 }
 
 // One workgroup per (unit, tile of 32 keys): the 32 x 128 bf16 block of V is read row by row with 16-byte
@@ -437,7 +436,7 @@ hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, do
                            rope_base, g.rope);
     }
     {
-        long long total = (long long)g.units * g.key_tiles * kKeyTile * (kD / 8);
+        long long total = (long long)g.units * g.key_tiles * kKeyTile * (kD / 16);
         hipLaunchKernelGGL(k_prefill_prep_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, tab, g, cs, Kr);
         hipLaunchKernelGGL(k_prefill_prep_v, dim3((unsigned)((long long)g.units * g.key_tiles)), dim3(256), 0, st, tab, g, Vt);
     }
