@@ -630,7 +630,7 @@ def test_power_spectrum_errors():
 # ------------------------------------------------------------------------------------------
 # HIP graph capture: the library only enqueues kernels on the caller's stream (no allocation, no
 # memset, no synchronisation once the basis and rotary tables exist), so a trigger followed by decode
-# attention can be captured once and replayed
+# and chunk-wise attention can be captured once and replayed
 # ------------------------------------------------------------------------------------------
 
 def test_graph_capture_of_trigger_and_attention():
@@ -641,20 +641,27 @@ def test_graph_capture_of_trigger_and_attention():
     L = binding.layout_for(k)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
     _, ap = fk.attend_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len)
-    ws = torch.empty(max(p.workspace_bytes, ap.workspace_bytes), dtype=torch.uint8, device=DEV)
+    q_len = 100                                       # chunk-wise attention of the last 100 compacted rows
+    _, pp = fk.attend_prefill_plan(L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len, q_len)
+    ws = torch.empty(max(p.workspace_bytes, ap.workspace_bytes, pp.workspace_bytes), dtype=torch.uint8, device=DEV)
     L.workspace, L.workspace_bytes = ws.data_ptr(), ws.numel()
     out = torch.zeros_like(q)
+    g = torch.Generator(device="cpu").manual_seed(18)
+    qc = (torch.randn(wl.n_layers, wl.batch, wl.q_heads, q_len, wl.head_dim, generator=g) * 0.5).to(torch.bfloat16).to(DEV)
+    outc = torch.zeros_like(qc)
 
     def work(stream):
         k.copy_(k0)
         v.copy_(v0)
         fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, stream)
         fk.attend_decode(q, k, v, out, None, L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len, -1, wl.rope_base, stream)
+        fk.attend_prefill(qc, k, v, outc, None, L, wl.q_heads, wl.n_heads, wl.head_dim, p.new_len, q_len, wl.rope_base, stream)
 
     # eager reference (also builds the cached basis and rotary tables: the only allocations the library makes)
     work(torch.cuda.current_stream())
     torch.cuda.synchronize()
-    k_ref, v_ref, out_ref = k.clone(), v.clone(), out.clone()
+    k_ref, v_ref, out_ref, outc_ref = k.clone(), v.clone(), out.clone(), outc.clone()
+    assert outc_ref.float().abs().max() > 0
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -666,13 +673,14 @@ def test_graph_capture_of_trigger_and_attention():
             work(torch.cuda.current_stream())
     torch.cuda.synchronize()
     for i in range(4):
-        k.zero_(); v.zero_(); out.zero_()             # eager work between the replays
+        k.zero_(); v.zero_(); out.zero_(); outc.zero_()    # eager work between the replays
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(k[:, :, :, :p.new_len], k_ref[:, :, :, :p.new_len]), i
         assert torch.equal(v[:, :, :, :p.new_len], v_ref[:, :, :, :p.new_len]), i
         assert torch.equal(out, out_ref), i
+        assert torch.equal(outc, outc_ref), i
 
 
 def test_two_level_fold_in_several_passes():
