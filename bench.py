@@ -29,6 +29,8 @@ TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.244e5 + 9.187e5) + 1.0 *
 TRAFFIC_BYTES_SINGLE_FOLD = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
 # the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
 ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
+# the same for k_attend_prefill (profiles/prefill_llama3_8b_128k.txt)
+PREFILL_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 1.705e6 + 1.0 * 1.049e6) * 1024}
 
 
 def cpu_baseline(wl, k_cache, cores):
@@ -210,7 +212,8 @@ def bench_prefill(args, wl, dev):
                                f"rotary base {wl.rope_base:g}", "operator": "attend_prefill"},
         "ms_prepare_kernels": prof.ms_prepare / max(int(prof.launches_prepare), 1), "ms_attend_kernel": ms_kernel,
         "roofline": {"bound": "mfma", "kernel": "k_attend_prefill", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None, "ms_per_launch": ms_kernel,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                     "traffic": PREFILL_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload), "ms_per_launch": ms_kernel,
                      "flops_per_launch": flops_launch, "measured_mfma_loop_tflops": mfma_tflops,
                      "frac_of_measured_mfma_loop": achieved / mfma_tflops},
         "cpu_baseline": cpu}))
