@@ -112,6 +112,17 @@ def test_prefill_head_groupings(hkv, hq):
     assert w <= TOL_PREFILL
 
 
+def test_prefill_unit_count_that_is_not_a_multiple_of_eight():
+    """Workgroups are dealt to the KV units in groups of eight units; 11 units = one full group and a remainder."""
+    wl = _wl(hkv=11, hq=22, layers=1, batch=1, cap=200)
+    cur_len, q_len = 190, 97
+    q, k, v = _mk(wl, cur_len, q_len, seed=5)
+    out, lse, _ = _run(q, k, v, wl, cur_len)
+    w = _check(q, k, v, out, lse, wl, cur_len)
+    _say(f"11 KV units: worst excess / max|V| = {w:.2e}")
+    assert w <= TOL_PREFILL
+
+
 def test_prefill_last_query_is_the_decode_case_and_rope_off():
     wl = _wl(cap=400)
     q, k, v = _mk(wl, 333, 70, seed=4)
