@@ -10,7 +10,7 @@
 // The work is bound by reading K and V once from HBM, so it runs on the vector ALUs, not on the matrix
 // cores.  Two kernels:
 //   k_attend_partial  one workgroup per (KV head, chunk of rows, group of <= 4 query heads that share
-//                     the KV head); every lane owns 8 rotary pairs of a row (16 channels), D/16 lanes
+//                     the KV head); every lane owns 4 rotary pairs of a row (8 channels), D/8 lanes
 //                     share a row, and each such lane group walks its rows with a running
 //                     max / sum / weighted-V state (online softmax).  cos/sin of the row position are
 //                     advanced by a fixed rotation per step from seeds computed with an fp64 range

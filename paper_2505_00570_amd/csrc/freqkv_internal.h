@@ -10,7 +10,8 @@ namespace freqkv {
 // address src and the data lands at LDS byte address lds + 16 i (lds is the same for the whole wave).  The copy
 // counts as a vector-memory load (vmcnt); the compiler does not know that it writes LDS, so the kernel waits
 // for it by hand (s_waitcnt vmcnt) before the barrier that publishes the data.  M0 carries the LDS address:
-// kernels that use this have no other user of M0.
+// kernels that use this have no other user of M0 (the compiler rejects M0 in a clobber list, so the build
+// script checks the generated assembly for that instead).
 __device__ __forceinline__ void lds_dma16(uint32_t lds, const void* src)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(lds), "v"(src) : "memory");
@@ -141,7 +142,7 @@ struct PrefillGeom {
     int units_per_layer;   // batch * n_kv
     int cur_len;           // cached rows, the chunk's tokens included
     int q_len;             // tokens of the chunk = queries per head; they are the last q_len cached rows
-    int q_pad;             // q_len rounded up to 64
+    int q_pad;             // q_len rounded up to 32
     int q_blocks;          // q_pad / 32
     int key_tiles;         // ceil(cur_len / 32)
     int rope;
@@ -149,8 +150,8 @@ struct PrefillGeom {
     float qscale;          // log2(e) / sqrt(d)
 };
 
-// cs: [cur_len][d/2] (cos, sin); Kr, Vt: [units][key_tiles] tiles of 32 keys x d fp16 in fragment order;
-// Qr: [units*G][q_pad][d] fp16.  q: dense [units*G][q_len][d] bf16.
+// cs: [cur_len][d/2] (cos, sin); Kr, Vt: [units][key_tiles] tiles of 32 keys x d fp16 in fragment order.
+// q: dense [units*G][q_len][d] bf16, rotated inside the attention kernel.
 hipError_t launch_prefill_prepare(const SlabTable& tab, const PrefillGeom& g, double rope_base, float2* cs,
                                   _Float16* Kr, _Float16* Vt, hipStream_t st);
 hipError_t launch_attend_prefill(const PrefillGeom& g, const _Float16* Kr, const _Float16* Vt, const void* q, const float2* cs,

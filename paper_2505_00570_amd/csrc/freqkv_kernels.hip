@@ -18,7 +18,7 @@
 //     EE = Gee xee,  EO = Geo xeo,  Gee/Geo[m][j] = (Ge[m][j] +/- Ge[Lc/2-1-m][j]) / 2
 //     E_m = EE_m + EO_m,  E_{Lc/2-1-m} = EE_m - EO_m                (m < ceil(Lc/4))
 // and the multiply-adds drop to 3/8 of the dense count ("two-level" variant: one launch for E into an
-// fp32 buffer, one for O that adds and subtracts E on its way into the cache).
+// fp16 buffer, one for O that adds and subtracts E on its way into the cache).
 // The kernels below build Ge/Go (or M), fold and
 // convert the span into an MFMA-ready fp16 workspace, and contract on the matrix
 // cores with fp32 accumulation, writing the Lc rows straight into the cache.
@@ -347,7 +347,7 @@ hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws
 //   - operand A (basis) is private to a wave: loaded global -> registers, already in
 //     fragment order ([kgroup][row][8]: lane L takes row L%32, k group L/32);
 //   - operand B (folded span) is shared by the waves: one contiguous stage of the workspace
-//     is copied global -> registers -> LDS (two slots) and read back as 16-byte fragments
+//     is copied global -> LDS directly (a ring of four slots) and read back as 16-byte fragments
 //     (lane L: column L%32, k group L/32), conflict-free.
 // ------------------------------------------------------------------------------------------
 
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     constexpr int WPP = FOLD ? NW / 2 : NW;                // waves per parity
     constexpr int WROWS = (FOLD ? kRowsFold : kRowsPlain) / WPP;   // rows per wave
     constexpr int MBN = WROWS / 32;                        // 32-row accumulator blocks per wave
-    constexpr int LDS_BYTES = NW * 16384;                  // pipeline: 2 slots of XSTAGE; epilogue: NW x 16 KiB
+    constexpr int LDS_BYTES = NW * 16384;                  // pipeline: 4 slots of XSTAGE; epilogue: NW x 16 KiB
     __shared__ __attribute__((aligned(1024))) char smem[LDS_BYTES];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

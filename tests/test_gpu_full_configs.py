@@ -77,11 +77,13 @@ def _check_sample(wl, before, after, tap, p, picks, tol=TOL_BF16, n_cols=None):
     return worst_raw, worst_floor
 
 
-def _one_trigger_full(wl, n_pick, seed, with_tap):
+def _one_trigger_full(wl, n_pick, seed, with_tap, extra_picks=(), expect=None):
     k, v = synth.empty_cache(wl, DEV)
     synth.KVSource(wl, seed, DEV).fill(k, v, 0, wl.window)
     L = binding.layout_for(k)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    if expect is not None:
+        assert (p.span_len, p.retained_len, p.head_tensors) == expect
     ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
     tapt = None
@@ -89,7 +91,7 @@ def _one_trigger_full(wl, n_pick, seed, with_tap):
         tapt = torch.empty(2, wl.n_layers, wl.batch, wl.n_heads, p.retained_len, wl.head_dim,
                            dtype=torch.float32, device=DEV)
         L.tap_f32 = tapt.data_ptr()
-    picks = _sample_heads(wl, n_pick, seed)
+    picks = sorted(set(_sample_heads(wl, n_pick, seed)) | set(extra_picks))
     src = (k, v)
     before = {key: src[key[0]][key[1], key[2], key[3]].cpu().clone() for key in picks}
     sinks_k = k[:, :, :, :wl.n_sink].clone()
@@ -139,6 +141,18 @@ def test_llama2_7b_full_model_trigger():
     wl = synth.WORKLOADS["llama2_7b_32k"]
     _say(f"config 3 {wl.name} (one full-size trigger)")
     _one_trigger_full(wl, n_pick=32, seed=3, with_tap=False)
+
+
+def test_decode_b8_full_size_trigger():
+    """Config 5 at full size (the launch `bench.py --workload decode_b8_256k` times): batch 8 x 32 layers x
+    32 heads = 16384 head-tensors of span 4092 in one call, 17.2 GB of cache and 8.6 GB of workspace.
+    20 whole head-tensors against the oracle (first and last layer, first and last sequence of the
+    batch, K heads with their outlier channels), sinks of the whole cache bit for bit."""
+    wl = synth.WORKLOADS["decode_b8_256k"]
+    _say(f"config 5 {wl.name} (one full-size trigger)")
+    extra = [(0, wl.n_layers - 1, wl.batch - 1, 5), (0, 0, wl.batch - 1, wl.n_heads - 1), (1, 0, 0, 0),
+             (0, 17, 3, 11)]
+    _one_trigger_full(wl, n_pick=16, seed=5, with_tap=False, extra_picks=extra, expect=(4092, 2046, 16384))
 
 
 def _iterative(wl, seed, picks_per_trigger, max_triggers=None, n_cols=None):
