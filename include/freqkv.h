@@ -229,6 +229,25 @@ FREQKV_API freqkv_status_t freqkv_attend_decode(const void* q, const void* k, co
                                      double rope_base, void* stream);
 
 /*
+ * freqkv_attend_decode for callers that cannot allocate device memory or pass a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but layout.workspace is ignored: the per-chunk softmax states and the
+ * small rotary table live in a static device array inside the library (8 MiB per GPU, held until the
+ * process ends), and the call allocates nothing, on the host or on the device.
+ * Limits: freqkv_attend_plan(...).workspace_bytes <= freqkv_noalloc_scratch_bytes() and n_layers <= 96;
+ * beyond either the call returns FREQKV_E_WORKSPACE (freqkv_last_error says which) and writes nothing.
+ * The array is shared by every call on a GPU and keeps the last call's contents; every call overwrites
+ * all the states it reads, so nothing has to be cleared, but two calls that overlap in time on one GPU
+ * (different streams, different threads) race: serialise them.
+ */
+FREQKV_API freqkv_status_t freqkv_attend_decode_noalloc(const void* q, const void* k, const void* v, void* out,
+                                             float* lse, const freqkv_layout_t* layout, int n_q_heads,
+                                             int n_kv_heads, int head_dim, int cur_len, int q_pos,
+                                             double rope_base, void* stream);
+/* Bytes of the static array available to the softmax states of freqkv_attend_decode_noalloc (host). */
+FREQKV_API size_t freqkv_noalloc_scratch_bytes(void);
+
+/*
  * The same attention for a batch whose sequences hold different numbers of cached rows (a serving batch:
  * Sec. 3.4's cache of each sequence fills and compacts on its own schedule).
  *   cur_lens     DEVICE array [layout.batch] of int32: cached rows of each sequence, shared by all layers;

@@ -101,6 +101,10 @@ def load() -> C.CDLL:
         lib.freqkv_attend_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
                                              C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, C.c_void_p]
         lib.freqkv_attend_decode.restype = C.c_int
+        lib.freqkv_attend_decode_noalloc.argtypes = lib.freqkv_attend_decode.argtypes
+        lib.freqkv_attend_decode_noalloc.restype = C.c_int
+        lib.freqkv_noalloc_scratch_bytes.argtypes = []
+        lib.freqkv_noalloc_scratch_bytes.restype = C.c_size_t
         lib.freqkv_attend_decode_ragged.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, LP,
                                                     C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_double,
                                                     C.c_void_p]
@@ -202,6 +206,20 @@ def attend_decode(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads:
                                      C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_pos,
                                      float(rope_base), _stream_ptr(stream))
     return _check(rc) if check else rc
+
+
+def attend_decode_noalloc(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                          cur_len: int, q_pos: int = -1, rope_base: float = 10000.0, stream=None,
+                          check: bool = True) -> int:
+    """freqkv_attend_decode_noalloc: as attend_decode, scratch inside the library, layout.workspace ignored."""
+    rc = load().freqkv_attend_decode_noalloc(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(out), _dev_ptr(lse),
+                                             C.byref(layout), n_q_heads, n_kv_heads, head_dim, cur_len, q_pos,
+                                             float(rope_base), _stream_ptr(stream))
+    return _check(rc) if check else rc
+
+
+def noalloc_scratch_bytes() -> int:
+    return int(load().freqkv_noalloc_scratch_bytes())
 
 
 def attend_decode_ragged(q, k, v, out, lse, layout: Layout, n_q_heads: int, n_kv_heads: int, head_dim: int,

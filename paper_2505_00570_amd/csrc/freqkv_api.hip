@@ -382,6 +382,37 @@ freqkv_status_t get_rope_table(int d, double base, hipStream_t st, RopeEntry** o
     return FREQKV_OK;
 }
 
+// ---------------------------------------------------------------- static scratch of the entry point that allocates nothing
+// freqkv_attend_decode_noalloc keeps the per-chunk softmax states and the rotary table here instead of in a
+// caller's workspace and a cached allocation.  Every device the library runs on holds its own copy of the
+// array until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device, with that device current, and only that pointer is ever
+// handed to a kernel.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+constexpr size_t kScratchRopeBytes = 4096;            // rotary table of up to 256 channels (128 entries x 16 B)
+constexpr int kScratchMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+void* g_scratch_ptr[kScratchMaxDevices] = {};
+
+freqkv_status_t scratch_for_current_device(void** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kScratchMaxDevices) return FREQKV_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) {
+            snprintf(g_last_error, sizeof(g_last_error), "static scratch: bad device address %p", ptr);
+            return FREQKV_E_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return FREQKV_OK;
+}
+
 // ---------------------------------------------------------------- profiling
 struct ProfSpan { hipEvent_t a, b; int kind; };
 std::atomic<bool> g_prof_on{false};
@@ -725,9 +756,12 @@ freqkv_status_t freqkv_attend_plan(const freqkv_layout_t* layout, int n_q_heads,
 }
 
 namespace {
+// use_static: the softmax states and the rotary table live in the library's static device array instead of
+// layout->workspace and a cached allocation; nothing is allocated, on the host or on the device.
 freqkv_status_t attend_impl(const void* q, const void* k, const void* v, void* out, float* lse,
                             const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads, int head_dim,
-                            int cur_len, int q_pos, const int32_t* cur_lens, double rope_base, void* stream)
+                            int cur_len, int q_pos, const int32_t* cur_lens, double rope_base, void* stream,
+                            bool use_static = false)
 {
     g_last_error[0] = 0;
     AttShape a;
@@ -740,7 +774,17 @@ freqkv_status_t attend_impl(const void* q, const void* k, const void* v, void* o
     if (q_pos < 0) q_pos = cur_len - 1;
     const freqkv_layout_t& L = *layout;
 
-    std::vector<char*> bases((size_t)2 * a.n_layers);          // [layer][K|V]
+    char* fixed_bases[kMaxSlabs];                              // [layer][K|V]; one pass needs no more
+    std::vector<char*> heap_bases;
+    char** bases = fixed_bases;
+    if (2 * a.n_layers > kMaxSlabs) {
+        if (use_static) {
+            snprintf(g_last_error, sizeof(g_last_error), "at most %d layers per call without a workspace", kMaxSlabs / 2);
+            return FREQKV_E_WORKSPACE;
+        }
+        heap_bases.resize((size_t)2 * a.n_layers);
+        bases = heap_bases.data();
+    }
     for (int l = 0; l < a.n_layers; ++l) {
         for (int kv = 0; kv < 2; ++kv) {
             const void* root = kv ? v : k;
@@ -750,17 +794,34 @@ freqkv_status_t attend_impl(const void* q, const void* k, const void* v, void* o
             bases[(size_t)2 * l + kv] = p;
         }
     }
-    if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < a.workspace_bytes)
-        return FREQKV_E_WORKSPACE;
-
     hipStream_t st = (hipStream_t)stream;
     const int rope = rope_base > 0.0;
     RopeEntry* rt = nullptr;
-    rc = get_rope_table(a.d, rope ? rope_base : 1.0, st, &rt);
-    if (rc < 0) return rc;
+    char* ws = (char*)L.workspace;
+    if (use_static) {
+        if (kScratchRopeBytes + a.workspace_bytes > kScratchBytes) {
+            snprintf(g_last_error, sizeof(g_last_error),
+                     "softmax states need %zu bytes, the static scratch holds %zu", a.workspace_bytes,
+                     kScratchBytes - kScratchRopeBytes);
+            return FREQKV_E_WORKSPACE;
+        }
+        void* sp = nullptr;
+        rc = scratch_for_current_device(&sp);
+        if (rc < 0) return rc;
+        // the table is rebuilt by every call (a few hundred bytes, one tiny kernel on the caller's stream),
+        // so that calls on different streams never depend on each other's table
+        rt = (RopeEntry*)sp;
+        HIP_TRY(launch_rope_table(rt, a.d, rope ? rope_base : 1.0, st));
+        ws = (char*)sp + kScratchRopeBytes;
+    } else {
+        if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < a.workspace_bytes)
+            return FREQKV_E_WORKSPACE;
+        rc = get_rope_table(a.d, rope ? rope_base : 1.0, st, &rt);
+        if (rc < 0) return rc;
+    }
 
-    float* part_acc = (float*)L.workspace;
-    float* part_ml = (float*)((char*)L.workspace + a.ml_offset);
+    float* part_acc = (float*)ws;
+    float* part_ml = (float*)(ws + a.ml_offset);
     const int upl = a.batch * a.n_kv;
     const int layers_per_pass = kMaxSlabs / 2;
     for (int l0 = 0; l0 < a.n_layers; l0 += layers_per_pass) {
@@ -782,9 +843,10 @@ freqkv_status_t attend_impl(const void* q, const void* k, const void* v, void* o
         float* pa = part_acc + head0 * a.n_split * a.d;
         float* pm = part_ml + head0 * a.n_split * 2;
         ProfSpan sp;
-        HIP_TRY(prof_begin(st, 3, &sp));
+        sp.a = sp.b = nullptr;
+        if (!use_static) HIP_TRY(prof_begin(st, 3, &sp));       // timing events are created per call: not here
         HIP_TRY(launch_attend_partial(tab, g, a.elem, qp, rt, pa, pm, st));
-        HIP_TRY(prof_end(st, &sp));
+        if (!use_static) HIP_TRY(prof_end(st, &sp));
         HIP_TRY(launch_attend_merge(g, a.elem, pa, pm, op, lse ? lse + head0 : nullptr, st));
     }
     return FREQKV_OK;
@@ -798,6 +860,16 @@ freqkv_status_t freqkv_attend_decode(const void* q, const void* k, const void* v
     return attend_impl(q, k, v, out, lse, layout, n_q_heads, n_kv_heads, head_dim, cur_len, q_pos, nullptr,
                        rope_base, stream);
 }
+
+freqkv_status_t freqkv_attend_decode_noalloc(const void* q, const void* k, const void* v, void* out, float* lse,
+                                             const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
+                                             int head_dim, int cur_len, int q_pos, double rope_base, void* stream)
+{
+    return attend_impl(q, k, v, out, lse, layout, n_q_heads, n_kv_heads, head_dim, cur_len, q_pos, nullptr,
+                       rope_base, stream, true);
+}
+
+size_t freqkv_noalloc_scratch_bytes(void) { return kScratchBytes - kScratchRopeBytes; }
 
 freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void* k, const void* v, void* out, float* lse,
                                             const freqkv_layout_t* layout, int n_q_heads, int n_kv_heads,
