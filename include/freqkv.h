@@ -65,6 +65,11 @@ typedef enum {
 #define FREQKV_FLAG_TWO_LEVEL_FOLD 0x10u /* use the two-level fold wherever it applies (span a multiple of 4, even
                                          retained length), whatever the sizes.  Not with SINGLE_FOLD */
 
+#define FREQKV_FLAG_DENSE 0x20u      /* never use the factored transform (variant 6); the matrix forms (variants 1, 2, 5)
+                                         run instead (SINGLE_FOLD and TWO_LEVEL_FOLD imply it).  Default: spans n = 4pq with a compiled factorization (8188 = 4*23*89,
+                                         4092 = 4*11*93, and 1260, 140 for tests) at retain_ratio 0.5 on bf16 caches take the
+                                         factored form, which needs no workspace */
+
 /*
  * Memory description of the cache ("layout"): everything the scalar arguments of
  * freqkv_compress do not say.  One head-tensor is the [token][dim] matrix of one
@@ -103,7 +108,8 @@ typedef struct freqkv_plan {
     int32_t new_len;            /* cache length after the call: n_sink + Lc + (cur_len - window) */
     int32_t head_tensors;       /* 2 * n_layers * batch * n_heads                                */
     int32_t variant;            /* 0 none (no-op or ratio 1), 1 folded fp16-MFMA, 2 plain fp16-MFMA, 3 fp32 FMA,
-                                   4 dropping (row moves only), 5 two-level folded fp16-MFMA */
+                                   4 dropping (row moves only), 5 two-level folded fp16-MFMA,
+                                   6 factored transform (prime-factor DFT stages on the matrix cores, LDS resident) */
     int32_t reserved;
     size_t  workspace_bytes;    /* scratch for all head-tensors in one pass (fastest)            */
     size_t  workspace_min_bytes;/* smallest scratch accepted (one (layer,K|V) slab per pass)     */
@@ -309,6 +315,21 @@ FREQKV_API freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, c
                                       float* lse, const freqkv_layout_t* layout, int n_q_heads,
                                       int n_kv_heads, int head_dim, int cur_len, int q_len,
                                       double rope_base, void* stream);
+
+/*
+ * Diagnostic of the factored transform (variant 6), used by the tests to check its stages one by one: runs
+ * the kernel on the K cache of layer 0 up to and including stage `stop` (1 load and length-4 butterfly,
+ * 2 q-point forward stage, 3 p-point forward stage, 4 step between the transforms, 5 p-point inverse stage,
+ * 6 q-point inverse stage), copies the fp16 LDS image of the workgroup that owns channels 0..7 of the first
+ * head-tensor to `dump` (device memory, dump_bytes >= what the span needs, at most 160 KiB) and writes
+ * nothing to the cache.  stop = 8 instead runs the whole transform on the K cache of layer 0 (the cache IS
+ * written) and leaves, per workgroup, 8 int64 shader-clock readings in dump (start, then after each of the
+ * stages above and after the store; dump_bytes >= 64 * batch * n_heads * head_dim / 8).
+ * retain_ratio is 0.5.  FREQKV_E_UNSUPPORTED when the span has no factored form.
+ */
+FREQKV_API freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t* layout, int n_heads,
+                                        int head_dim, int window, int n_sink, int stop, void* dump,
+                                        size_t dump_bytes, void* stream);
 
 /* Human-readable name of a status code (static string, host). */
 FREQKV_API const char* freqkv_status_string(freqkv_status_t status);

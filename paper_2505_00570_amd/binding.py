@@ -19,6 +19,7 @@ FLAG_DROPPING = 0x2
 FLAG_RETAIN_HIGH = 0x4
 FLAG_SINGLE_FOLD = 0x8
 FLAG_TWO_LEVEL_FOLD = 0x10
+FLAG_DENSE = 0x20
 
 OK, NOOP = 0, 1
 E_INVALID, E_UNSUPPORTED, E_WORKSPACE, E_HIP, E_ALLOC = -1, -2, -3, -4, -5

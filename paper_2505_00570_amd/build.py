@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(LIB_DIR, "libfreqkv.so")
-SOURCES = ["freqkv_kernels.hip", "freqkv_attend.hip", "freqkv_prefill.hip", "freqkv_api.hip"]
+SOURCES = ["freqkv_kernels.hip", "freqkv_fast.hip", "freqkv_attend.hip", "freqkv_prefill.hip", "freqkv_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops off: the device compiler must not form v_pk_{add,mul,fma}_f32 from float code.  The

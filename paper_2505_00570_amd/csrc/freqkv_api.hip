@@ -150,12 +150,14 @@ size_t basis_bytes(const Shape& sh, const Geom& g)
     }
     if (sh.variant == kF32) return (size_t)sh.n * sh.Lc * sizeof(float);
     if (sh.variant == kNone) return 0;
+    if (sh.variant == kFast) return fast_table_bytes(sh.n);
     return (size_t)(g.Kpad / 8) * g.Grows * 16;
 }
 
 // Workspace bytes for a pass over `slabs` slabs.
 size_t pass_workspace(const Shape& sh, int slabs)
 {
+    if (sh.variant == kFast) return 0;
     if (sh.variant == kFold2F16) return l2_slices(sh, slabs).total;
     long long ncols = (long long)slabs * sh.hts_per_slab * sh.d;
     if (sh.variant == kF32) return (size_t)sh.n * (size_t)round_up(ncols, 64) * sizeof(float);
@@ -187,7 +189,7 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     if (cur_len < 0 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
     if (!(ratio > 0.0) || !(ratio <= 1.0)) return FREQKV_E_INVALID;      // also rejects NaN
     if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
-    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD)) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD | FREQKV_FLAG_DENSE)) return FREQKV_E_INVALID;
     if ((L->flags & FREQKV_FLAG_DROPPING) && (L->flags & FREQKV_FLAG_RETAIN_HIGH)) return FREQKV_E_INVALID;
     if ((L->flags & FREQKV_FLAG_SINGLE_FOLD) && (L->flags & FREQKV_FLAG_TWO_LEVEL_FOLD)) return FREQKV_E_INVALID;
     if (L->stride_token < head_dim) return FREQKV_E_INVALID;
@@ -212,6 +214,9 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     if (sh.Lc == sh.n) sh.variant = kNone;
     else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
+    else if (!sh.high && !(L->flags & (FREQKV_FLAG_DENSE | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD)) &&
+             fast_supported(sh.n, sh.Lc, nullptr, nullptr))
+        sh.variant = kFast;
     else if (sh.n % 4 == 0 && sh.Lc % 2 == 0 && !(L->flags & FREQKV_FLAG_SINGLE_FOLD)) {
         // workgroups of the even-part launch over all slabs: column tiles x row tiles of 256 rows per parity
         const long long coltiles = ((long long)sh.nslabs * hts * head_dim + kColTile - 1) / kColTile;
@@ -237,6 +242,7 @@ struct BasisEntry {
     void* ptr = nullptr;
     size_t bytes = 0;
     hipEvent_t ready = nullptr;   // recorded after the build kernel; other streams wait on it
+    void* host = nullptr;         // pinned staging copy of tables built on the host (kept until shutdown)
 };
 
 std::mutex g_mu;
@@ -258,7 +264,14 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
             (void)hipGetLastError();
             return FREQKV_E_ALLOC;
         }
-        if (sh.variant == kF32) {
+        if (sh.variant == kFast) {
+            // built on the host in fp64, copied from pinned memory in stream order (no synchronisation)
+            err = hipHostMalloc(&e.host, e.bytes, hipHostMallocDefault);
+            if (err == hipSuccess) {
+                fast_build_tables_host(sh.n, (char*)e.host);
+                err = hipMemcpyAsync(e.ptr, e.host, e.bytes, hipMemcpyHostToDevice, st);
+            }
+        } else if (sh.variant == kF32) {
             err = launch_basis_f32((float*)e.ptr, sh.n, sh.Lc, rescale, sh.high, st);
         } else if (sh.variant == kFold2F16) {
             freqkv_layout_t L0;
@@ -275,6 +288,7 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
         if (err != hipSuccess) {
             set_error("basis build", err);
             (void)hipFree(e.ptr);
+            if (e.host) (void)hipHostFree(e.host);
             return FREQKV_E_HIP;
         }
         it = g_basis.emplace(key, e).first;
@@ -306,7 +320,7 @@ freqkv_status_t check_attend(const freqkv_layout_t* L, int n_q, int n_kv, int d,
     if (d != 64 && d != 128 && d != 256) return FREQKV_E_UNSUPPORTED;
     if (cur_len < 1 || cur_len > L->token_capacity) return FREQKV_E_INVALID;
     if (L->pointer_table != 0 && L->pointer_table != 1) return FREQKV_E_INVALID;
-    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD)) return FREQKV_E_INVALID;
+    if (L->flags & ~(FREQKV_FLAG_NO_RESCALE | FREQKV_FLAG_DROPPING | FREQKV_FLAG_RETAIN_HIGH | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD | FREQKV_FLAG_DENSE)) return FREQKV_E_INVALID;
     if (L->stride_token < d) return FREQKV_E_INVALID;
     if (L->stride_token % 8 || L->stride_head % 8 || L->stride_batch % 8) return FREQKV_E_INVALID;
     if (!L->pointer_table && L->stride_layer % 8) return FREQKV_E_INVALID;
@@ -507,6 +521,15 @@ freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head
         out->flops_dense = 2.0 * sh.Lc * (double)sh.n * sh.d * hts;
         out->flops_executed = sh.variant == kFoldF16 ? out->flops_dense * 0.5
                             : sh.variant == kFold2F16 ? out->flops_dense * 0.375 : out->flops_dense;
+        if (sh.variant == kFast) {
+            // multiply-adds of the four matrix stages and the middle step, per channel, padding not counted
+            int p = 0, q = 0;
+            fast_supported(sh.n, sh.Lc, &p, &q);
+            const double qh = (q + 1) / 2;
+            const double per_channel = 2.0 * (4.0 * p * q * 2 * qh + 4.0 * qh * 4.0 * p * p + 16.0 * p * qh +
+                                              2.0 * qh * 4.0 * p * p + 2.0 * p * 2 * qh * q);
+            out->flops_executed = per_channel * sh.d * hts;
+        }
         out->bytes_algorithmic = ((double)sh.n + sh.Lc + 2.0 * sh.tail) * sh.d * sh.elem * hts;
     }
     return cur_len < window ? FREQKV_NOOP : FREQKV_OK;
@@ -577,10 +600,44 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
         return FREQKV_OK;
     }
 
+    const int rescale = !(L.flags & FREQKV_FLAG_NO_RESCALE);
+
+    if (sh.variant == kFast) {
+        // Factored transform: one kernel reads the span from the cache and writes the retained rows in place
+        // (a workgroup owns its channels for all rows); the tail moves afterwards, when the span has been read.
+        void* tables = nullptr;
+        {
+            Geom g0 = make_geom(sh, L, 1, 0);
+            freqkv_status_t rc = get_basis(sh, g0, 1, st, &tables);       // the tables do not depend on the rescale
+            if (rc < 0) return rc;
+        }
+        if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
+        const float rest = rescale ? 0.5f : (float)(0.5 * std::sqrt((double)sh.n / (double)sh.Lc));
+        for (int s0 = 0; s0 < sh.nslabs; s0 += kMaxSlabs) {
+            int slabs = sh.nslabs - s0 < kMaxSlabs ? sh.nslabs - s0 : kMaxSlabs;
+            Geom g = make_geom(sh, L, slabs, s0);
+            SlabTable tab;
+            memset(&tab, 0, sizeof(tab));
+            for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
+            ProfSpan sp;
+            HIP_TRY(prof_begin(st, 1, &sp));
+            HIP_TRY(launch_fast(tab, g, tables, rest, tap, nullptr, 0, st));
+            HIP_TRY(prof_end(st, &sp));
+            if (sh.tail > 0) {
+                HIP_TRY(prof_begin(st, 2, &sp));
+                const int gap = sh.n - sh.Lc;
+                for (int r0 = 0; r0 < sh.tail; r0 += gap) {
+                    int rows = sh.tail - r0 < gap ? sh.tail - r0 : gap;
+                    HIP_TRY(launch_move_rows(tab, g, sh.elem, sh.W + r0, sh.S + sh.Lc + r0, rows, st));
+                }
+                HIP_TRY(prof_end(st, &sp));
+            }
+        }
+        return FREQKV_OK;
+    }
+
     size_t min_ws = pass_workspace(sh, 1);
     if (!L.workspace || ((uintptr_t)L.workspace & 255) || L.workspace_bytes < min_ws) return FREQKV_E_WORKSPACE;
-
-    const int rescale = !(L.flags & FREQKV_FLAG_NO_RESCALE);
 
     // slabs per pass: as many as the workspace and the pointer table hold
     int per_pass = sh.nslabs < kMaxSlabs ? sh.nslabs : kMaxSlabs;
@@ -684,6 +741,33 @@ freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
     rc = resolve_bases(k, v, *layout, sh, 0, &bases);
     if (rc < 0) return rc;
     return compress_resolved(bases, *layout, sh, layout->tap_f32, (hipStream_t)stream);
+}
+
+freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
+                                        int window, int n_sink, int stop, void* dump, size_t dump_bytes,
+                                        void* stream)
+{
+    g_last_error[0] = 0;
+    Shape sh;
+    freqkv_status_t rc = check_shape(layout, n_heads, head_dim, window, window, n_sink, 0.5, &sh);
+    if (rc < 0) return rc;
+    if (!k || !v || !dump || stop < 1 || stop > 8 || stop == 7) return FREQKV_E_INVALID;
+    if (sh.variant != kFast) return FREQKV_E_UNSUPPORTED;
+    const size_t need = stop == 8 ? (size_t)sh.hts_per_slab * sh.d / 8 * 64 : fast_lds_halfs(sh.n) * 2;
+    if (dump_bytes < need) return FREQKV_E_WORKSPACE;
+    std::vector<char*> bases;
+    rc = resolve_bases(k, v, *layout, sh, 0, &bases);
+    if (rc < 0) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    void* tables = nullptr;
+    Geom g0 = make_geom(sh, *layout, 1, 0);
+    rc = get_basis(sh, g0, 1, st, &tables);
+    if (rc < 0) return rc;
+    SlabTable tab;
+    memset(&tab, 0, sizeof(tab));
+    tab.base[0] = bases[0];
+    HIP_TRY(launch_fast(tab, g0, tables, 0.5f, nullptr, (_Float16*)dump, stop, st));
+    return FREQKV_OK;
 }
 
 freqkv_status_t freqkv_compress_ragged(void* k, void* v, const freqkv_layout_t* layout, int n_heads, int head_dim,
@@ -1051,6 +1135,7 @@ void freqkv_shutdown(void)
             (void)hipEventDestroy(kv.second.ready);
         }
         (void)hipFree(kv.second.ptr);
+        if (kv.second.host) (void)hipHostFree(kv.second.host);
     }
     g_basis.clear();
     for (auto& kv : g_rope) {

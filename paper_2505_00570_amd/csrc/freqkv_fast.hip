@@ -1,0 +1,683 @@
+// Factored ("fast") form of the compression operator for spans n = 4pq with p, q odd and coprime and a
+// retained length Lc = n/2 (the paper's default ratio 0.5 on its windows: 8188 = 4*23*89, 4092 = 4*11*93).
+//
+// What is computed is exactly Sec. 3.3 Eq. 2-3 with the transforms of Appendix A -- orthonormal n-point
+// DCT-II along tokens, the Lc lowest coefficients, Lc-point inverse, times sqrt(Lc/n) -- but evaluated the
+// way Sec. 3.4 and Appendix A point to (an O(N log N) transform instead of the O(N^2) sums):
+//
+//   forward   C_t = sum_j x_j cos(pi t (2j+1) / 2n) is Re(e^{-i pi t/2n} V_t), V = DFT_n(v), where v is x with
+//             its even-indexed samples first and its odd-indexed samples reversed behind them;
+//   inverse   y = sum_t c_t cos(pi t (2m+1) / 2Lc) is recovered the same way from an Lc-point inverse DFT of
+//             U_k = e^{i pi k/2Lc} (C_k - i C_{Lc-k}) / n  (C_Lc := 0: that coefficient is not kept);
+//   both DFTs are prime-factor transforms: n = 4*p*q and Lc = 2*p*q have coprime factors, so with the
+//             input index taken as j = j1 (n/4) + j2 (n/p) + j3 (n/q) mod n and the output index by its
+//             residues (t mod 4, t mod p, t mod q) the length-n DFT is a 4 x p x q DFT with no twiddle factors
+//             between its stages, and likewise 2 x p x q for the inverse.
+//
+// One workgroup owns 8 channels of one head-tensor for all rows (column ownership): it reads its 16 bytes of
+// every span row straight from the cache, keeps every intermediate in LDS, and writes its 16 bytes of the Lc
+// result rows back.  No workspace, no second pass over HBM, and no in-place hazard: nobody else touches
+// these channels.  The length-p and length-q stages are small dense DFT matrices applied on the matrix cores
+// (fp16 operands, fp32 accumulation) to the rows or columns of LDS-resident tiles; the length-4 and length-2
+// stages are butterflies folded into the load and the store; the step between the two transforms (twiddles,
+// real parts, Hermitian pairing) is a 2x4 real matrix per frequency pair and parity, precomputed in fp64.
+//
+// Phases (a barrier after each), with g = (array, channel) and all LDS values fp16:
+//   load     rows -> X[g][j2][j3], four real p x q arrays per channel: the length-4 butterfly of the samples
+//            j1 = 0..3 (sum, alternating sum, real and imaginary part of the odd outputs), scaled by a power
+//            of two chosen from the largest magnitude of the slice so that no stage can overflow fp16
+//   stage Q  real -> half-complex DFT over j3:  B[g][f][j2], f = Re 0..qh-1 | Im qh..2qh-1   (in place)
+//   stage P  complex DFT over j2:               D[g][f][f2]                                    (in place)
+//   middle   per (f2, f3): the four arrays' coefficients -> U of the even and of the odd k:  G[(k1,ch)][f][k2]
+//   stage P' inverse complex DFT over k2:       E[(k1,m2,ch)][Re 0..47 | Im 48..95]    (other half of LDS)
+//   stage Q' half-complex -> real over k3:      u[(k1,m2)][m3][ch]                      (first half again)
+//   store    length-2 butterfly over k1, output index m = m1 (Lc/2) + m2 (Lc/p) + m3 (Lc/q) mod Lc, rows
+//            y_{2m} = u_m, y_{2m+1} = u_{Lc-1-m}, one rounding to bf16
+#include "freqkv_internal.h"
+
+#include <cmath>
+#include <vector>
+
+namespace freqkv {
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int I> struct IC { static constexpr int value = I; };
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+constexpr int kFragBytes = 1024;          // one 32 x 16 operand fragment set: 64 lanes x 8 halfs
+
+template <int P_, int Q_>
+struct FastCfg {
+    static constexpr int P = P_, Q = Q_;
+    static constexpr int J2 = (P + 7) / 8 * 8;        // p padded to whole 16-byte groups
+    static constexpr int QH = (Q + 1) / 2;            // half-complex length of the q stage
+    static constexpr int N = P * Q, n = 4 * N, Lc = 2 * N;
+    static constexpr int NG = 32;                     // (array, channel) groups
+    static constexpr int GH = 96 * J2;                // halfs per group
+    static constexpr int LDS_HALFS = NG * GH;
+    static constexpr int KP = 2 * J2;                 // contraction length of the complex p stage (Re | Im)
+    static constexpr int KSP = KP / 16;               // its 16-deep steps
+    static constexpr int NTP = (KP + 31) / 32;        // its 32-wide output tiles
+    static constexpr int UROWS = (J2 % 32 == 0) ? J2 : (J2 == 24 ? 96 : (J2 == 8 ? 32 : 32));   // lcm(32, J2)
+    static constexpr int RT = UROWS / 32;
+    static constexpr int NUNITS = NG * J2 / UROWS;
+    static constexpr int NPOS = P * Q;
+    static constexpr int NJOBS = P * QH;
+    // table offsets (bytes)
+    static constexpr int OFF_Q = 0;
+    static constexpr int OFF_P = OFF_Q + 3 * 6 * kFragBytes;
+    static constexpr int OFF_PI = OFF_P + NTP * KSP * kFragBytes;
+    static constexpr int OFF_QI = OFF_PI + NTP * KSP * kFragBytes;
+    static constexpr int OFF_JOBS = OFF_QI + 3 * 6 * kFragBytes;
+    static constexpr int TABLE_BYTES = OFF_JOBS + NJOBS * 64;
+    static_assert(Q <= 96 && 2 * QH <= 96 && QH <= 48, "q stage fits 96-wide tiles");
+    static_assert(KP <= 64 && KP % 16 == 0, "p stage fits two 32-wide tiles");
+    static_assert(UROWS % J2 == 0 && UROWS % 32 == 0 && (NG * J2) % UROWS == 0, "in-place units hold whole groups");
+    static_assert(LDS_HALFS * 2 <= 160 * 1024 - 64, "LDS");
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+// Row of the span that holds sample j of the even-first / odd-reversed ordering of an n-point sequence.
+__device__ __forceinline__ int makhoul_row(int j, int n) { return j < n / 2 ? 2 * j : 2 * (n - 1 - j) + 1; }
+
+// dump: diagnostic only.  When not null, workgroup 0 copies its LDS there after phase `stop` (1 load ...
+// 6 stage Q') and every workgroup returns without writing the cache.
+template <class Cfg>
+__global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables,
+                                                 float rest_scale, float* __restrict__ tap,
+                                                 _Float16* __restrict__ dump, int stop)
+{
+    constexpr int P = Cfg::P, Q = Cfg::Q, J2 = Cfg::J2, QH = Cfg::QH, N = Cfg::N, n = Cfg::n, Lc = Cfg::Lc;
+    constexpr int GH = Cfg::GH;
+    __shared__ __attribute__((aligned(1024))) _Float16 lds[Cfg::LDS_HALFS];
+    __shared__ uint32_t red[4];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    // blockIdx -> task (8 consecutive virtual columns).  Workgroups are dealt round-robin to the 8 XCDs;
+    // the d/8 tasks of one head-tensor take consecutive slots of ONE XCD, so that the 16-byte pieces they
+    // read of the same 256-byte rows, and the pieces they write, meet in that XCD's L2.
+    int task;
+    {
+        const int tph = g.d / 8;                       // tasks per head-tensor
+        const int hts = g.ncols / g.d;
+        const int bid = blockIdx.x;
+        const int full = hts / 8;                      // groups of 8 head-tensors
+        const int per_group = 8 * tph;
+        if (bid < full * per_group) {
+            const int grp = bid / per_group, local = bid - grp * per_group;
+            const int xcd = local & 7, slot = local >> 3;
+            task = (grp * 8 + xcd) * tph + slot;
+        } else {
+            task = bid;
+        }
+    }
+    int ht;
+    char* base = column_base(tab, g, task * 8, 2, &ht);
+    const int c0 = task * 8 - ht * g.d;
+    const long long rowb = g.stride_token * 2;
+    base += (long long)g.S * rowb;
+
+    // diagnostic: stop == 8 runs everything and leaves the shader-clock reading after each phase in dump
+    const bool stamp = dump && stop == 8;
+    long long ts[9];
+    ts[0] = stamp ? (long long)clock64() : 0;
+
+    // ---- phase 0: clear LDS (pad positions must hold finite values: they meet zero matrix entries)
+    {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        u32x4* l4 = (u32x4*)lds;
+        for (int i = tid; i < Cfg::LDS_HALFS / 8; i += 256) l4[i] = z;
+    }
+
+    // ---- phase 1: load.  Lane handles positions pos = tid + 256 i of the p x q grid; all 4 x NIT row pieces
+    // are requested before the first is used.
+    constexpr int NIT = (Cfg::NPOS + 255) / 256;
+    u32x4 raw[NIT][4];
+    static_for<NIT>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        int pos = tid + 256 * i;
+        if (pos >= Cfg::NPOS) pos = 0;
+        const int j2 = pos / Q, j3 = pos - j2 * Q;
+        const int jb = (j2 * (4 * Q) + j3 * (4 * P)) % n;
+        static_for<4>([&](auto jc) {
+            constexpr int j1 = decltype(jc)::value;
+            int j = jb + j1 * N;
+            if (j >= n) j -= n;
+            raw[i][j1] = *(const u32x4*)(base + (long long)makhoul_row(j, n) * rowb);
+        });
+    });
+    // largest magnitude of the slice (bf16 bit patterns compare like their magnitudes)
+    uint32_t amax;
+    {
+        u16x2 m = {0, 0};
+        static_for<NIT>([&](auto ic) {
+            static_for<4>([&](auto jc) {
+                static_for<4>([&](auto wc) {
+                    uint32_t w = raw[decltype(ic)::value][decltype(jc)::value][decltype(wc)::value] & 0x7fff7fffu;
+                    m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, w));
+                });
+            });
+        });
+        amax = m[0] > m[1] ? m[0] : m[1];
+        for (int off = 1; off < 64; off <<= 1) {
+            uint32_t o = (uint32_t)__shfl_xor((int)amax, off);
+            amax = o > amax ? o : amax;
+        }
+        if (lane == 0) red[wave] = amax;
+    }
+    __syncthreads();                                   // LDS cleared, red[] complete
+    {
+        uint32_t a = red[0];
+        a = red[1] > a ? red[1] : a;
+        a = red[2] > a ? red[2] : a;
+        a = red[3] > a ? red[3] : a;
+        amax = a;
+    }
+    // 2^e brings the largest magnitude into [256, 512): the transforms amplify a constant sequence by at most
+    // 2 sqrt(pq) < 128, so every intermediate stays below the fp16 limit, and 2^-e undoes it exactly at the end
+    int e = 0;
+    {
+        const int E = (int)(amax >> 7);                // exponent field of the largest magnitude
+        if (E > 0 && E < 255) e = 135 - E;
+        if (e > 120) e = 120;
+    }
+    const float sc = 0.5f * __uint_as_float((uint32_t)(e + 127) << 23);
+    const float unsc = rest_scale * __uint_as_float((uint32_t)(127 - e) << 23);
+
+    static_for<NIT>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        const int pos = tid + 256 * i;
+        if (pos < Cfg::NPOS) {
+            const int j2 = pos / Q, j3 = pos - j2 * Q;
+            _Float16* dst = lds + j2 * 96 + j3;
+            static_for<4>([&](auto wc) {
+                constexpr int w = decltype(wc)::value;
+                static_for<2>([&](auto hc) {
+                    constexpr int hf = decltype(hc)::value;
+                    constexpr int ch = 2 * w + hf;
+                    const float a0 = hf ? bf16_hi(raw[i][0][w]) : bf16_lo(raw[i][0][w]);
+                    const float a1 = hf ? bf16_hi(raw[i][1][w]) : bf16_lo(raw[i][1][w]);
+                    const float a2 = hf ? bf16_hi(raw[i][2][w]) : bf16_lo(raw[i][2][w]);
+                    const float a3 = hf ? bf16_hi(raw[i][3][w]) : bf16_lo(raw[i][3][w]);
+                    const float s02 = a0 + a2, d02 = a0 - a2, s13 = a1 + a3, d13 = a3 - a1;
+                    dst[(0 * 8 + ch) * GH] = (_Float16)((s02 + s13) * sc);
+                    dst[(1 * 8 + ch) * GH] = (_Float16)((s02 - s13) * sc);
+                    dst[(2 * 8 + ch) * GH] = (_Float16)(d02 * sc);
+                    dst[(3 * 8 + ch) * GH] = (_Float16)(d13 * sc);
+                });
+            });
+        }
+    });
+    __syncthreads();
+    ts[1] = stamp ? (long long)clock64() : 0;
+    auto dump_and_stop = [&](int phase) -> bool {
+        if (!dump || stop != phase) return false;
+        if (blockIdx.x == 0)
+            for (int i = tid; i < Cfg::LDS_HALFS; i += 256) dump[i] = lds[i];
+        return true;
+    };
+    if (dump_and_stop(1)) return;
+
+    // ---- phase 2: stage Q.  Rows (g, j2) x contraction j3 (96) -> f (96); a wave owns whole units of UROWS
+    // rows, reads all of a unit, then overwrites it with the transposed result [g][f][j2].
+    {
+        half8 bq[3][6];
+        const half8* tq = (const half8*)(tables + Cfg::OFF_Q) + lane;
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { bq[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
+        });
+        for (int u = wave; u < Cfg::NUNITS; u += 4) {
+            f32x16 acc[Cfg::RT][3];
+            static_for<Cfg::RT>([&](auto rt) {
+                static_for<3>([&](auto ct) {
+                    static_for<16>([&](auto r) { acc[rt.value][ct.value][r.value] = 0.f; });
+                });
+            });
+            const _Float16* src = lds + (u * Cfg::UROWS + l32) * 96 + 8 * lhi;
+            static_for<6>([&](auto ks) {
+                static_for<Cfg::RT>([&](auto rt) {
+                    const half8 a = *(const half8*)(src + rt.value * 32 * 96 + ks.value * 16);
+                    static_for<3>([&](auto ct) {
+                        acc[rt.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            a, bq[ct.value][ks.value], acc[rt.value][ct.value], 0, 0, 0);
+                    });
+                });
+            });
+            static_for<Cfg::RT>([&](auto rt) {
+                static_for<4>([&](auto r4) {
+                    const int row = u * Cfg::UROWS + rt.value * 32 + 8 * r4.value + 4 * lhi;   // first of 4 rows
+                    const int grp = row / J2, j2 = row - grp * J2;
+                    static_for<3>([&](auto ct) {
+                        const int f = ct.value * 32 + l32;
+                        half4 o;
+                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[rt.value][ct.value][4 * r4.value + k.value]; });
+                        *(half4*)(lds + grp * GH + f * J2 + j2) = o;
+                    });
+                });
+            });
+        }
+    }
+    __syncthreads();
+    ts[2] = stamp ? (long long)clock64() : 0;
+    if (dump_and_stop(2)) return;
+
+    // ---- phase 3: stage P.  Columns m' = (g, f3) x contraction (part, j2) -> (part', f2); the data are the
+    // second operand, so a lane keeps one column and gets 4 consecutive f2: written back in place.
+    {
+        half8 ap[Cfg::NTP][Cfg::KSP];
+        const half8* tp = (const half8*)(tables + Cfg::OFF_P) + lane;
+        static_for<Cfg::NTP>([&](auto nt) {
+            static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = tp[(nt.value * Cfg::KSP + ks.value) * 64]; });
+        });
+        for (int t = wave; t < QH; t += 4) {           // 32 QH columns = QH tiles of 32
+            const int mp = t * 32 + l32;
+            const int grp = mp / QH, f3 = mp - grp * QH;
+            _Float16* col = lds + grp * GH + f3 * J2;
+            f32x16 acc[Cfg::NTP];
+            static_for<Cfg::NTP>([&](auto nt) { static_for<16>([&](auto r) { acc[nt.value][r.value] = 0.f; }); });
+            static_for<Cfg::KSP>([&](auto ks) {
+                const int k = ks.value * 16 + 8 * lhi;
+                const int part = k / J2, j2c = k - part * J2;
+                const half8 b = *(const half8*)(col + part * QH * J2 + j2c);
+                static_for<Cfg::NTP>([&](auto nt) {
+                    acc[nt.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ap[nt.value][ks.value], b, acc[nt.value], 0, 0, 0);
+                });
+            });
+            static_for<Cfg::NTP>([&](auto nt) {
+                static_for<4>([&](auto r4) {
+                    const int n0 = nt.value * 32 + 8 * r4.value + 4 * lhi;
+                    if (n0 < Cfg::KP) {
+                        const int part = n0 / J2, f2 = n0 - part * J2;
+                        half4 o;
+                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[nt.value][4 * r4.value + k.value]; });
+                        *(half4*)(col + part * QH * J2 + f2) = o;
+                    }
+                });
+            });
+        }
+    }
+    __syncthreads();
+    ts[3] = stamp ? (long long)clock64() : 0;
+    if (dump_and_stop(3)) return;
+
+    // ---- phase 4: middle.  Lane takes jobs (k2, k3) and, per channel, the four arrays' coefficients there:
+    // (F0, F2) give U of the even k with these residues, (Fr, Fi) of the odd k; both land in place.
+    {
+        constexpr int NJI = (Cfg::NJOBS + 255) / 256;
+        for (int i = 0; i < NJI; ++i) {
+            const int jb = tid + 256 * i;
+            if (jb >= Cfg::NJOBS) break;
+            const int k3 = jb / P, k2 = jb - k3 * P;
+            const f32x4* T = (const f32x4*)(tables + Cfg::OFF_JOBS) + jb * 4;
+            const f32x4 t0 = T[0], t1 = T[1], t2 = T[2], t3 = T[3];
+            _Float16* re = lds + k3 * J2 + k2;
+            _Float16* im = re + QH * J2;
+#pragma unroll
+            for (int ch = 0; ch < 8; ++ch) {
+                const float ar = (float)re[(0 * 8 + ch) * GH], ai = (float)im[(0 * 8 + ch) * GH];
+                const float br = (float)re[(1 * 8 + ch) * GH], bi = (float)im[(1 * 8 + ch) * GH];
+                const float cr = (float)re[(2 * 8 + ch) * GH], ci = (float)im[(2 * 8 + ch) * GH];
+                const float dr = (float)re[(3 * 8 + ch) * GH], di = (float)im[(3 * 8 + ch) * GH];
+                const float er = t0[0] * ar + t0[1] * ai + t0[2] * br + t0[3] * bi;
+                const float ei = t1[0] * ar + t1[1] * ai + t1[2] * br + t1[3] * bi;
+                const float orr = t2[0] * cr + t2[1] * ci + t2[2] * dr + t2[3] * di;
+                const float oi = t3[0] * cr + t3[1] * ci + t3[2] * dr + t3[3] * di;
+                re[(0 * 8 + ch) * GH] = (_Float16)er;  im[(0 * 8 + ch) * GH] = (_Float16)ei;
+                re[(1 * 8 + ch) * GH] = (_Float16)orr; im[(1 * 8 + ch) * GH] = (_Float16)oi;
+            }
+        }
+    }
+    __syncthreads();
+    ts[4] = stamp ? (long long)clock64() : 0;
+    if (dump_and_stop(4)) return;
+
+    // ---- phase 5: stage P'.  Rows m' = (g', k3 padded to 48), g' = (k1, ch) < 16, x contraction (part, k2)
+    // -> (part', m2); results go to the other half of LDS as E[(k1, m2, ch)][part' 48 + k3].
+    constexpr int Y0 = 16 * GH;
+    {
+        half8 bp[Cfg::NTP][Cfg::KSP];
+        const half8* tp = (const half8*)(tables + Cfg::OFF_PI) + lane;
+        static_for<Cfg::NTP>([&](auto ct) {
+            static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = tp[(ct.value * Cfg::KSP + ks.value) * 64]; });
+        });
+        for (int t = wave; t < 24; t += 4) {           // 16 x 48 rows
+            const int mp = t * 32 + l32;
+            const int grp = mp / 48;
+            int k3 = mp - grp * 48;
+            if (k3 > QH - 1) k3 = QH - 1;              // pad rows: any finite data, their results meet zeros
+            const _Float16* rowp = lds + grp * GH + k3 * J2;
+            f32x16 acc[Cfg::NTP];
+            static_for<Cfg::NTP>([&](auto ct) { static_for<16>([&](auto r) { acc[ct.value][r.value] = 0.f; }); });
+            static_for<Cfg::KSP>([&](auto ks) {
+                const int k = ks.value * 16 + 8 * lhi;
+                const int part = k / J2, k2c = k - part * J2;
+                const half8 a = *(const half8*)(rowp + part * QH * J2 + k2c);
+                static_for<Cfg::NTP>([&](auto ct) {
+                    acc[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bp[ct.value][ks.value], acc[ct.value], 0, 0, 0);
+                });
+            });
+            static_for<Cfg::NTP>([&](auto ct) {
+                const int nn = ct.value * 32 + l32;
+                if (nn < Cfg::KP) {
+                    const int part = nn / J2, m2 = nn - part * J2;
+                    static_for<4>([&](auto r4) {
+                        const int m0 = t * 32 + 8 * r4.value + 4 * lhi;       // first of 4 rows, same g'
+                        const int g2 = m0 / 48, k30 = m0 - g2 * 48;
+                        const int k1 = g2 >> 3, ch = g2 & 7;
+                        half4 o;
+                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[ct.value][4 * r4.value + k.value]; });
+                        *(half4*)(lds + Y0 + ((k1 * J2 + m2) * 8 + ch) * 96 + part * 48 + k30) = o;
+                    });
+                }
+            });
+        }
+    }
+    __syncthreads();
+    ts[5] = stamp ? (long long)clock64() : 0;
+    if (dump_and_stop(5)) return;
+
+    // ---- phase 6: stage Q'.  Rows (k1, m2, ch) x contraction (Re | Im of k3, 96) -> m3; 4 consecutive rows of a
+    // lane are 4 channels: u[(k1, m2)][m3][ch] into the first half of LDS.
+    {
+        half8 bq[3][6];
+        const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { bq[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
+        });
+        constexpr int NT6 = 16 * J2 / 32;
+        for (int t = wave; t < NT6; t += 4) {
+            const _Float16* src = lds + Y0 + (t * 32 + l32) * 96 + 8 * lhi;
+            f32x16 acc[3];
+            static_for<3>([&](auto ct) { static_for<16>([&](auto r) { acc[ct.value][r.value] = 0.f; }); });
+            static_for<6>([&](auto ks) {
+                const half8 a = *(const half8*)(src + ks.value * 16);
+                static_for<3>([&](auto ct) {
+                    acc[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq[ct.value][ks.value], acc[ct.value], 0, 0, 0);
+                });
+            });
+            static_for<3>([&](auto ct) {
+                const int m3 = ct.value * 32 + l32;
+                if (m3 < Q) {
+                    static_for<4>([&](auto r4) {
+                        const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) 8 + ch, ch = 0 or 4
+                        half4 o;
+                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[ct.value][4 * r4.value + k.value]; });
+                        *(half4*)(lds + ((v0 >> 3) * 96 + m3) * 8 + (v0 & 7)) = o;
+                    });
+                }
+            });
+        }
+    }
+    __syncthreads();
+    ts[6] = stamp ? (long long)clock64() : 0;
+    if (dump_and_stop(6)) return;
+    if (dump && !stamp) return;
+
+    // ---- phase 7: store
+    {
+        float* tp = nullptr;
+        if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
+        for (int i = 0; i < NIT; ++i) {
+            const int pos = tid + 256 * i;
+            if (pos >= Cfg::NPOS) break;
+            const int m2 = pos / Q, m3 = pos - m2 * Q;
+            const half8 g0 = *(const half8*)(lds + ((0 * J2 + m2) * 96 + m3) * 8);
+            const half8 g1 = *(const half8*)(lds + ((1 * J2 + m2) * 96 + m3) * 8);
+            int ma = (m2 * (2 * Q) + m3 * (2 * P)) % Lc;
+            int mb = ma + N;
+            if (mb >= Lc) mb -= Lc;
+            const int ra = makhoul_row(ma, Lc), rb = makhoul_row(mb, Lc);
+            float va[8], vb[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const float a = (float)g0[c], b = (float)g1[c];
+                va[c] = (a + b) * unsc;
+                vb[c] = (a - b) * unsc;
+            }
+            u32x4 pa, pb;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                pa[c] = pack_bf16x2(va[2 * c], va[2 * c + 1]);
+                pb[c] = pack_bf16x2(vb[2 * c], vb[2 * c + 1]);
+            }
+            *(u32x4*)(base + (long long)ra * rowb) = pa;
+            *(u32x4*)(base + (long long)rb * rowb) = pb;
+            if (tp) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    tp[(long long)ra * g.d + c] = va[c];
+                    tp[(long long)rb * g.d + c] = vb[c];
+                }
+            }
+        }
+    }
+    if (stamp) {
+        __syncthreads();
+        ts[7] = (long long)clock64();
+        if (tid == 0) {
+            long long* o = (long long*)dump + (long long)blockIdx.x * 8;
+            for (int i = 0; i < 8; ++i) o[i] = ts[i];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host: tables in fp64, rounded once
+// ------------------------------------------------------------------------------------------
+
+const double kPi = 3.14159265358979323846;
+
+// Fragment order of a matrix M[k][idx] for v_mfma_f32_32x32x16_f16: tile t, step ks, lane l, element i hold
+// M[ks*16 + 8*(l/32) + i][t*32 + l%32] (the same order serves as first or as second operand).
+template <class F>
+void fill_frags(_Float16* out, int tiles, int ksteps, F&& mat)
+{
+    for (int t = 0; t < tiles; ++t)
+        for (int ks = 0; ks < ksteps; ++ks)
+            for (int l = 0; l < 64; ++l)
+                for (int i = 0; i < 8; ++i)
+                    out[(((size_t)t * ksteps + ks) * 64 + l) * 8 + i] =
+                        (_Float16)mat(ks * 16 + 8 * (l / 32) + i, t * 32 + l % 32);
+}
+
+long long mod_inverse(long long a, long long m)
+{
+    long long t = 0, nt = 1, r = m, nr = ((a % m) + m) % m;
+    while (nr) {
+        long long qq = r / nr;
+        long long tmp = t - qq * nt; t = nt; nt = tmp;
+        tmp = r - qq * nr; r = nr; nr = tmp;
+    }
+    return ((t % m) + m) % m;
+}
+
+template <class Cfg>
+void build_tables(char* out)
+{
+    constexpr int P = Cfg::P, Q = Cfg::Q, J2 = Cfg::J2, QH = Cfg::QH, N = Cfg::N, n = Cfg::n, Lc = Cfg::Lc;
+    const double sq = 1.0 / std::sqrt((double)Q), sp = 1.0 / std::sqrt((double)P);
+    // stage Q: k = j3, idx = f (Re f3 | Im QH + f3)
+    fill_frags((_Float16*)(out + Cfg::OFF_Q), 3, 6, [&](int k, int f) -> double {
+        if (k >= Q || f >= 2 * QH) return 0.0;
+        const int f3 = f < QH ? f : f - QH;
+        const double a = 2.0 * kPi * (double)((long long)k * f3 % Q) / Q;
+        return f < QH ? std::cos(a) * sq : -std::sin(a) * sq;
+    });
+    // stage P (forward, e^{-i}): k = (part, j2), idx = (part', f2)
+    auto pmat = [&](int k, int idx, double sign) -> double {
+        if (k >= 2 * J2 || idx >= 2 * J2) return 0.0;
+        const int pk = k / J2, j2 = k % J2, pi = idx / J2, f2 = idx % J2;
+        if (j2 >= P || f2 >= P) return 0.0;
+        const double a = 2.0 * kPi * (double)(j2 * f2 % P) / P;
+        // (re + i im)(cos - i sign sin): re' = re cos + sign im sin, im' = im cos - sign re sin
+        if (pk == 0 && pi == 0) return std::cos(a) * sp;
+        if (pk == 1 && pi == 0) return sign * std::sin(a) * sp;
+        if (pk == 0 && pi == 1) return -sign * std::sin(a) * sp;
+        return std::cos(a) * sp;
+    };
+    fill_frags((_Float16*)(out + Cfg::OFF_P), Cfg::NTP, Cfg::KSP, [&](int k, int idx) { return pmat(k, idx, 1.0); });
+    fill_frags((_Float16*)(out + Cfg::OFF_PI), Cfg::NTP, Cfg::KSP, [&](int k, int idx) { return pmat(k, idx, -1.0); });
+    // stage Q' : k = part' 48 + k3, idx = m3;  u = E_0 + 2 Re sum_{k3 >= 1} E_k3 e^{+2 pi i k3 m3 / q}
+    fill_frags((_Float16*)(out + Cfg::OFF_QI), 3, 6, [&](int k, int m3) -> double {
+        const int part = k / 48, k3 = k % 48;
+        if (k3 >= QH || m3 >= Q) return 0.0;
+        const double w = k3 == 0 ? 1.0 : 2.0;
+        const double a = 2.0 * kPi * (double)((long long)k3 * m3 % Q) / Q;
+        return part == 0 ? w * std::cos(a) * sq : -w * std::sin(a) * sq;
+    });
+    // middle: per (k2, k3) the 2x4 maps (F0, F2) -> U of the even k and (Fr, Fi) -> U of the odd k
+    const long long e2 = (long long)Q * mod_inverse(Q, P) % N, e3 = (long long)P * mod_inverse(P, Q) % N;
+    float* jobs = (float*)(out + Cfg::OFF_JOBS);
+    for (int k3 = 0; k3 < QH; ++k3) {
+        for (int k2 = 0; k2 < P; ++k2) {
+            const long long tau = (k2 * e2 + k3 * e3) % N, taup = N - tau;
+            const long long kk[4] = {tau, tau + N, taup, taup + N};       // a, b (these residues); c, d (negated)
+            double T[2][2][8];                                             // [parity of k][re|im][input]
+            for (int in = 0; in < 8; ++in) {
+                double x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                x[in] = 1.0;
+                // inputs: F0 (re, im), F2, Fr, Fi at (k2, k3); at the negated residues each is conjugated
+                auto V = [&](long long k, bool neg, double* vr, double* vi) {
+                    const double s = neg ? -1.0 : 1.0;
+                    const double ar = x[0], ai = s * x[1], br = x[2], bi = s * x[3];
+                    const double cr = x[4], ci = s * x[5], dr = x[6], di = s * x[7];
+                    switch (k % 4) {
+                        case 0: *vr = ar; *vi = ai; break;
+                        case 1: *vr = cr - di; *vi = ci + dr; break;          // Fr + i Fi
+                        case 2: *vr = br; *vi = bi; break;
+                        default: *vr = cr + di; *vi = ci - dr; break;         // Fr - i Fi
+                    }
+                };
+                double C[4];
+                for (int w = 0; w < 4; ++w) {
+                    if (kk[w] >= Lc) { C[w] = 0.0; continue; }                // the coefficient that is not kept
+                    double vr, vi;
+                    V(kk[w], w >= 2, &vr, &vi);
+                    const double th = kPi * (double)kk[w] / (2.0 * n);
+                    C[w] = std::cos(th) * vr + std::sin(th) * vi;             // Re(e^{-i th} V)
+                }
+                // U_a = e^{i pi ka / 2Lc} (C_a - i C_d),  U_b = e^{i pi kb / 2Lc} (C_b - i C_c)
+                const double ta = kPi * (double)kk[0] / (2.0 * Lc), tb = kPi * (double)kk[1] / (2.0 * Lc);
+                const double uar = std::cos(ta) * C[0] + std::sin(ta) * C[3], uai = std::sin(ta) * C[0] - std::cos(ta) * C[3];
+                const double ubr = std::cos(tb) * C[1] + std::sin(tb) * C[2], ubi = std::sin(tb) * C[1] - std::cos(tb) * C[2];
+                const int pa = (int)(kk[0] & 1), pb = (int)(kk[1] & 1);
+                T[pa][0][in] = uar; T[pa][1][in] = uai;
+                T[pb][0][in] = ubr; T[pb][1][in] = ubi;
+            }
+            float* o = jobs + ((size_t)k3 * P + k2) * 16;
+            for (int r = 0; r < 2; ++r)
+                for (int in = 0; in < 4; ++in) {
+                    o[r * 4 + in] = (float)T[0][r][in];            // even k: from (F0, F2)
+                    o[8 + r * 4 + in] = (float)T[1][r][4 + in];    // odd k: from (Fr, Fi)
+                }
+        }
+    }
+}
+
+template <class Cfg>
+hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
+                      _Float16* dump, int stop, hipStream_t st)
+{
+    const unsigned tasks = (unsigned)(g.ncols / 8);
+    hipLaunchKernelGGL((k_fast<Cfg>), dim3(tasks), dim3(256), 0, st, tab, g, (const char*)tables, rest_scale, tap,
+                       dump, stop);
+    return hipGetLastError();
+}
+
+// the factorizations with compiled kernels: the paper's two windows and two small ones for tests
+typedef FastCfg<23, 89> Cfg8188;
+typedef FastCfg<11, 93> Cfg4092;
+typedef FastCfg<7, 45> Cfg1260;
+typedef FastCfg<5, 7> Cfg140;
+
+}  // namespace
+
+bool fast_supported(int n, int Lc, int* p, int* q)
+{
+    int pp = 0, qq = 0;
+    if (n == Cfg8188::n) { pp = 23; qq = 89; }
+    else if (n == Cfg4092::n) { pp = 11; qq = 93; }
+    else if (n == Cfg1260::n) { pp = 7; qq = 45; }
+    else if (n == Cfg140::n) { pp = 5; qq = 7; }
+    else return false;
+    if (Lc * 2 != n) return false;
+    if (p) *p = pp;
+    if (q) *q = qq;
+    return true;
+}
+
+size_t fast_table_bytes(int n)
+{
+    switch (n) {
+        case Cfg8188::n: return Cfg8188::TABLE_BYTES;
+        case Cfg4092::n: return Cfg4092::TABLE_BYTES;
+        case Cfg1260::n: return Cfg1260::TABLE_BYTES;
+        case Cfg140::n: return Cfg140::TABLE_BYTES;
+    }
+    return 0;
+}
+
+size_t fast_lds_halfs(int n)
+{
+    switch (n) {
+        case Cfg8188::n: return Cfg8188::LDS_HALFS;
+        case Cfg4092::n: return Cfg4092::LDS_HALFS;
+        case Cfg1260::n: return Cfg1260::LDS_HALFS;
+        case Cfg140::n: return Cfg140::LDS_HALFS;
+    }
+    return 0;
+}
+
+void fast_build_tables_host(int n, char* out)
+{
+    switch (n) {
+        case Cfg8188::n: build_tables<Cfg8188>(out); break;
+        case Cfg4092::n: build_tables<Cfg4092>(out); break;
+        case Cfg1260::n: build_tables<Cfg1260>(out); break;
+        case Cfg140::n: build_tables<Cfg140>(out); break;
+    }
+}
+
+hipError_t launch_fast(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
+                       _Float16* dump, int stop, hipStream_t st)
+{
+    if (g.ncols % 8 || g.d % 8) return hipErrorInvalidValue;
+    switch (g.n) {
+        case Cfg8188::n: return launch_cfg<Cfg8188>(tab, g, tables, rest_scale, tap, dump, stop, st);
+        case Cfg4092::n: return launch_cfg<Cfg4092>(tab, g, tables, rest_scale, tap, dump, stop, st);
+        case Cfg1260::n: return launch_cfg<Cfg1260>(tab, g, tables, rest_scale, tap, dump, stop, st);
+        case Cfg140::n: return launch_cfg<Cfg140>(tab, g, tables, rest_scale, tap, dump, stop, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace freqkv

@@ -61,7 +61,22 @@ struct Geom {
     long long tap_slab0; // index of this pass's first slab in the caller's [2][n_layers] order
 };
 
-enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4, kFold2F16 = 5 };
+// Byte address of (token 0, channel c) of the head-tensor that owns virtual column vcol.
+__device__ __forceinline__ char* column_base(const SlabTable& tab, const Geom& g, int vcol,
+                                             int elem_bytes, int* ht_out)
+{
+    int ht   = vcol / g.d;
+    int c    = vcol - ht * g.d;
+    int slab = ht / g.hts_per_slab;
+    int r    = ht - slab * g.hts_per_slab;
+    int b    = r / g.n_heads;
+    int h    = r - b * g.n_heads;
+    if (ht_out) *ht_out = ht;
+    long long off = (long long)b * g.stride_batch + (long long)h * g.stride_head + c;
+    return tab.base[slab] + off * elem_bytes;
+}
+
+enum Variant { kNone = 0, kFoldF16 = 1, kPlainF16 = 2, kF32 = 3, kDrop = 4, kFold2F16 = 5, kFast = 6 };
 
 // ---- basis construction (fp64 closed form, rounded once) -------------------------
 // G: [Kpad/8][Grows][8] fp16.  Folded: rows [0,Mpad) even part, rows [Mpad,2Mpad) odd part.
@@ -83,6 +98,17 @@ hipError_t launch_fill_zero(float* p, size_t count, hipStream_t st);
 hipError_t launch_prepare_f32(const SlabTable& tab, const Geom& g, float* ws, hipStream_t st);
 hipError_t launch_contract_f32(const SlabTable& tab, const Geom& g, const float* Mf,
                                const float* ws, float* tap, hipStream_t st);
+
+// ---- factored transform (spans n = 4pq, Lc = n/2, bf16 caches): one kernel, no workspace ------------------
+// Is there a compiled kernel for this span?  (p, q) are the coprime odd factors of n/4.
+bool fast_supported(int n, int Lc, int* p, int* q);
+size_t fast_table_bytes(int n);                       // stage matrices in fragment order + the middle step's maps
+size_t fast_lds_halfs(int n);                         // fp16 values of one workgroup's LDS image (diagnostics)
+void fast_build_tables_host(int n, char* out);        // fp64, rounded once; `out` is host memory
+// rest_scale: what is left of the operator's 1/n after the scaled stages (1/2; sqrt(n/Lc)/2 without the
+// rescale of Eq. 3).  dump/stop: diagnostic, see the kernel; pass nullptr, 0.
+hipError_t launch_fast(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
+                       _Float16* dump, int stop, hipStream_t st);
 
 // ---- tail move: rows [src, src+rows) -> [dst, dst+rows) of every head-tensor; ranges must not overlap
 hipError_t launch_move_rows(const SlabTable& tab, const Geom& g, int elem_bytes, int src_row,

@@ -49,21 +49,6 @@ __device__ __forceinline__ void static_for(F&& f)
 // addressing helpers
 // ------------------------------------------------------------------------------------------
 
-// Byte address of (token 0, channel c) of the head-tensor that owns virtual column vcol.
-__device__ __forceinline__ char* column_base(const SlabTable& tab, const Geom& g, int vcol,
-                                             int elem_bytes, int* ht_out)
-{
-    int ht   = vcol / g.d;
-    int c    = vcol - ht * g.d;
-    int slab = ht / g.hts_per_slab;
-    int r    = ht - slab * g.hts_per_slab;
-    int b    = r / g.n_heads;
-    int h    = r - b * g.n_heads;
-    if (ht_out) *ht_out = ht;
-    long long off = (long long)b * g.stride_batch + (long long)h * g.stride_head + c;
-    return tab.base[slab] + off * elem_bytes;
-}
-
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 // two floats -> packed bfloat16 pair, round-to-nearest-even (gfx950's v_cvt_pk_bf16_f32)

@@ -79,6 +79,19 @@ def test_plan_matches_paper_integers():
     assert p.head_tensors == 2 * 32 * 32
     # LLaMA-3 window
     rc, p = fk.plan(_layout(), 8, 128, 8192, 8192, 4, 0.5)
+    # 8188 = 4 * 23 * 89, ratio 1/2: the factored transform, no workspace, tables of about 113 KiB
+    assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 6)
+    assert p.workspace_bytes == 0 and p.workspace_min_bytes == 0
+    assert p.basis_bytes == 2 * 18 * 1024 + 2 * 6 * 1024 + 23 * 45 * 64
+    assert p.flops_dense == pytest.approx(2.0 * 4094 * 8188 * 128 * 512)
+    assert p.bytes_algorithmic == pytest.approx((8188 + 4094) * 128 * 2 * 512)
+    per_channel = 2.0 * (4 * 23 * 89 * 90 + 4 * 45 * 4 * 23 * 23 + 16 * 23 * 45 + 2 * 45 * 4 * 23 * 23 + 2 * 23 * 90 * 89)
+    assert p.flops_executed == pytest.approx(per_channel * 128 * 512)
+    assert p.flops_executed < p.flops_dense / 15
+    # the matrix form on request
+    Ld = _layout()
+    Ld.flags = fk.FLAG_DENSE
+    rc, p = fk.plan(Ld, 8, 128, 8192, 8192, 4, 0.5)
     assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 5)
     assert p.flops_dense == pytest.approx(2.0 * 4094 * 8188 * 128 * 512)
     assert p.flops_executed == pytest.approx(p.flops_dense * 3 / 8)       # two-level even/odd fold
@@ -105,6 +118,8 @@ def test_plan_agrees_with_oracle_rules(window, sink, ratio, cur):
     assert p.new_len == orc.new_len(cur, window, sink, ratio)
     if ratio == 1.0:
         assert p.variant == 0 and p.workspace_bytes == 0
+    elif window - sink in (8188, 4092, 1260, 140) and p.retained_len * 2 == window - sink:
+        assert p.variant == 6 and p.workspace_bytes == 0
     elif (window - sink) % 4 == 0 and p.retained_len % 2 == 0 and window - sink >= 2048:
         assert p.variant == 5                     # 32 layers x 8 heads: enough head-tensors for the two-level fold
     elif (window - sink) % 2 == 0 and p.retained_len % 2 == 0:
@@ -175,7 +190,8 @@ def test_compress_validates_before_touching_the_device():
     # null / misaligned cache pointers
     assert fk.compress(None, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_INVALID
     assert fk.compress(fake + 2, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_INVALID
-    # missing / small / misaligned workspace
+    # missing / small / misaligned workspace (the matrix forms need one; the factored form does not)
+    L.flags = fk.FLAG_DENSE
     assert fk.compress(fake, fake, L, 8, 128, 8192, 8192, 4, 0.5, check=False) == binding.E_WORKSPACE
     _, p = fk.plan(L, 8, 128, 8192, 8192, 4, 0.5)
     L.workspace, L.workspace_bytes = fake, p.workspace_min_bytes - 1

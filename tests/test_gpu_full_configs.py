@@ -77,14 +77,16 @@ def _check_sample(wl, before, after, tap, p, picks, tol=TOL_BF16, n_cols=None):
     return worst_raw, worst_floor
 
 
-def _one_trigger_full(wl, n_pick, seed, with_tap, extra_picks=(), expect=None):
+def _one_trigger_full(wl, n_pick, seed, with_tap, extra_picks=(), expect=None, flags=0, variant=None):
     k, v = synth.empty_cache(wl, DEV)
     synth.KVSource(wl, seed, DEV).fill(k, v, 0, wl.window)
-    L = binding.layout_for(k)
+    L = binding.layout_for(k, flags=flags)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
+    if variant is not None:
+        assert p.variant == variant
     if expect is not None:
         assert (p.span_len, p.retained_len, p.head_tensors) == expect
-    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(p.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
     tapt = None
     if with_tap:
@@ -115,7 +117,7 @@ def test_llama2_7b_one_layer_full():
     synth.KVSource(wl, 0, DEV).fill(k, v, 0, wl.window)
     L = binding.layout_for(k)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
-    assert (p.span_len, p.retained_len, p.head_tensors, p.variant) == (4092, 2046, 64, 1)
+    assert (p.span_len, p.retained_len, p.head_tensors, p.variant) == (4092, 2046, 64, 6)
     ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
     tapt = torch.empty(2, 1, 1, 32, p.retained_len, 128, dtype=torch.float32, device=DEV)
     L.workspace, L.workspace_bytes, L.tap_f32 = ws.data_ptr(), p.workspace_bytes, tapt.data_ptr()
@@ -129,30 +131,38 @@ def test_llama2_7b_one_layer_full():
     _check_sample(wl, before, after, tap, p, picks)
 
 
-def test_llama3_8b_gqa_full_size_trigger():
+# the full-size triggers run twice: the factored transform (the default for these spans) and the matrix form
+FORMS = [pytest.param(0, 6, id="factored"), pytest.param(binding.FLAG_DENSE, 5, id="matrix")]
+
+
+@pytest.mark.parametrize("flags,variant", FORMS)
+def test_llama3_8b_gqa_full_size_trigger(flags, variant):
     """Config 4 at full size (the launch configuration bench.py times): 512 head-tensors, span 8188."""
     wl = synth.WORKLOADS["llama3_8b_128k"]
-    _say(f"config 4 {wl.name} (one full-size trigger)")
-    _one_trigger_full(wl, n_pick=16, seed=4, with_tap=True)
+    _say(f"config 4 {wl.name} (one full-size trigger, variant {variant})")
+    _one_trigger_full(wl, n_pick=16, seed=4, with_tap=True, flags=flags, variant=variant)
 
 
-def test_llama2_7b_full_model_trigger():
+@pytest.mark.parametrize("flags,variant", FORMS)
+def test_llama2_7b_full_model_trigger(flags, variant):
     """Config 3 at full size: 32 layers x 32 heads, 2048 head-tensors, span 4092."""
     wl = synth.WORKLOADS["llama2_7b_32k"]
-    _say(f"config 3 {wl.name} (one full-size trigger)")
-    _one_trigger_full(wl, n_pick=32, seed=3, with_tap=False)
+    _say(f"config 3 {wl.name} (one full-size trigger, variant {variant})")
+    _one_trigger_full(wl, n_pick=32, seed=3, with_tap=False, flags=flags, variant=variant)
 
 
-def test_decode_b8_full_size_trigger():
+@pytest.mark.parametrize("flags,variant", FORMS)
+def test_decode_b8_full_size_trigger(flags, variant):
     """Config 5 at full size (the launch `bench.py --workload decode_b8_256k` times): batch 8 x 32 layers x
     32 heads = 16384 head-tensors of span 4092 in one call, 17.2 GB of cache and 8.6 GB of workspace.
     20 whole head-tensors against the oracle (first and last layer, first and last sequence of the
     batch, K heads with their outlier channels), sinks of the whole cache bit for bit."""
     wl = synth.WORKLOADS["decode_b8_256k"]
-    _say(f"config 5 {wl.name} (one full-size trigger)")
+    _say(f"config 5 {wl.name} (one full-size trigger, variant {variant})")
     extra = [(0, wl.n_layers - 1, wl.batch - 1, 5), (0, 0, wl.batch - 1, wl.n_heads - 1), (1, 0, 0, 0),
              (0, 17, 3, 11)]
-    _one_trigger_full(wl, n_pick=16, seed=5, with_tap=False, extra_picks=extra, expect=(4092, 2046, 16384))
+    _one_trigger_full(wl, n_pick=16, seed=5, with_tap=False, extra_picks=extra, expect=(4092, 2046, 16384),
+                      flags=flags, variant=variant)
 
 
 def _iterative(wl, seed, picks_per_trigger, max_triggers=None, n_cols=None):

@@ -68,7 +68,7 @@ def _check_all_heads(wl, k0, v0, k1, v1, tap, p, cur_len, tol, rescale=True):
                     # rows beyond the old cur_len: untouched
                     assert torch.equal(got[cur_len:], before[l, b, h, cur_len:])
                     yref = ref[S:S + lc]
-                    rms = math.sqrt(float((yref ** 2).mean()))
+                    rms = max(math.sqrt(float((yref ** 2).mean())), 1e-300)      # an all-zero head must come out all zero
                     ygot = f64(got[S:S + lc])
                     if tap is not None:
                         yt = f64(tap[kv, l, b, h])
