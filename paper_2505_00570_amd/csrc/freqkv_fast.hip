@@ -44,6 +44,7 @@ namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -79,14 +80,14 @@ struct FastCfg {
     static constexpr int RT = UROWS / 32;
     static constexpr int NUNITS = NG * J2 / UROWS;
     static constexpr int NPOS = P * Q;
-    static constexpr int NJOBS = P * QH;
+    static constexpr int NPJ = QH * (J2 / 2);         // middle step: jobs of two neighbouring k2 each
     // table offsets (bytes)
     static constexpr int OFF_Q = 0;
     static constexpr int OFF_P = OFF_Q + 3 * 6 * kFragBytes;
     static constexpr int OFF_PI = OFF_P + NTP * KSP * kFragBytes;
     static constexpr int OFF_QI = OFF_PI + NTP * KSP * kFragBytes;
     static constexpr int OFF_JOBS = OFF_QI + 3 * 6 * kFragBytes;
-    static constexpr int TABLE_BYTES = OFF_JOBS + NJOBS * 64;
+    static constexpr int TABLE_BYTES = OFF_JOBS + NPJ * 64;
     static_assert(Q <= 96 && 2 * QH <= 96 && QH <= 48, "q stage fits 96-wide tiles");
     static_assert(KP <= 64 && KP % 16 == 0, "p stage fits two 32-wide tiles");
     static_assert(UROWS % J2 == 0 && UROWS % 32 == 0 && (NG * J2) % UROWS == 0, "in-place units hold whole groups");
@@ -103,20 +104,29 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, b);
 }
 
+// Rows of 96 halfs are kept as 12 chunks of 8 halfs (16 bytes), rotated by a row-dependent number of chunks:
+// with rows 192 bytes apart, the 16-byte fragment reads of 16 consecutive rows would otherwise fall on 4 bank
+// groups only.  rot2: the X image of the load stage (quads of rows get 0, 2, 1, 3).  rot12: the E image of stage P',
+// where rows 8 apart (consecutive m2) are also written together and must spread as well.
+__device__ __forceinline__ int rot2(int row) { return ((row >> 1) & 2) | ((row >> 3) & 1); }
+__device__ __forceinline__ int rot12(int row) { return ((row >> 3) + 2 * ((row >> 2) & 1)) % 12; }
+__device__ __forceinline__ int wrap12(int c) { return c >= 12 ? c - 12 : c; }
+
 // Row of the span that holds sample j of the even-first / odd-reversed ordering of an n-point sequence.
 __device__ __forceinline__ int makhoul_row(int j, int n) { return j < n / 2 ? 2 * j : 2 * (n - 1 - j) + 1; }
 
 // dump: diagnostic only.  When not null, workgroup 0 copies its LDS there after phase `stop` (1 load ...
 // 6 stage Q') and every workgroup returns without writing the cache.
-template <class Cfg>
-__global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables,
+template <class Cfg, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables,
                                                  float rest_scale, float* __restrict__ tap,
                                                  _Float16* __restrict__ dump, int stop)
 {
     constexpr int P = Cfg::P, Q = Cfg::Q, J2 = Cfg::J2, QH = Cfg::QH, N = Cfg::N, n = Cfg::n, Lc = Cfg::Lc;
     constexpr int GH = Cfg::GH;
+    constexpr int NT = NW * 64;                        // threads
     __shared__ __attribute__((aligned(1024))) _Float16 lds[Cfg::LDS_HALFS];
-    __shared__ uint32_t red[4];
+    __shared__ uint32_t red[NW];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -148,23 +158,16 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
 
     // diagnostic: stop == 8 runs everything and leaves the shader-clock reading after each phase in dump
     const bool stamp = dump && stop == 8;
-    long long ts[9];
+    long long ts[10];
     ts[0] = stamp ? (long long)clock64() : 0;
 
-    // ---- phase 0: clear LDS (pad positions must hold finite values: they meet zero matrix entries)
-    {
-        u32x4 z = {0u, 0u, 0u, 0u};
-        u32x4* l4 = (u32x4*)lds;
-        for (int i = tid; i < Cfg::LDS_HALFS / 8; i += 256) l4[i] = z;
-    }
-
-    // ---- phase 1: load.  Lane handles positions pos = tid + 256 i of the p x q grid; all 4 x NIT row pieces
+    // ---- phase 1: load.  Lane handles positions pos = tid + NT i of the p x q grid; all 4 x NIT row pieces
     // are requested before the first is used.
-    constexpr int NIT = (Cfg::NPOS + 255) / 256;
+    constexpr int NIT = (Cfg::NPOS + NT - 1) / NT;
     u32x4 raw[NIT][4];
     static_for<NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        int pos = tid + 256 * i;
+        int pos = tid + NT * i;
         if (pos >= Cfg::NPOS) pos = 0;
         const int j2 = pos / Q, j3 = pos - j2 * Q;
         const int jb = (j2 * (4 * Q) + j3 * (4 * P)) % n;
@@ -175,6 +178,13 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
             raw[i][j1] = *(const u32x4*)(base + (long long)makhoul_row(j, n) * rowb);
         });
     });
+    // ---- clear LDS while the rows are on their way (pad positions must hold finite values: they meet zero matrix entries)
+    {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        u32x4* l4 = (u32x4*)lds;
+        for (int i = tid; i < Cfg::LDS_HALFS / 8; i += NT) l4[i] = z;
+    }
+
     // largest magnitude of the slice (bf16 bit patterns compare like their magnitudes)
     uint32_t amax;
     {
@@ -195,11 +205,10 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
         if (lane == 0) red[wave] = amax;
     }
     __syncthreads();                                   // LDS cleared, red[] complete
+    ts[8] = stamp ? (long long)clock64() : 0;
     {
         uint32_t a = red[0];
-        a = red[1] > a ? red[1] : a;
-        a = red[2] > a ? red[2] : a;
-        a = red[3] > a ? red[3] : a;
+        static_for<NW - 1>([&](auto w) { a = red[w.value + 1] > a ? red[w.value + 1] : a; });
         amax = a;
     }
     // 2^e brings the largest magnitude into [256, 512): the transforms amplify a constant sequence by at most
@@ -215,10 +224,13 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
 
     static_for<NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        const int pos = tid + 256 * i;
+        const int pos = tid + NT * i;
         if (pos < Cfg::NPOS) {
             const int j2 = pos / Q, j3 = pos - j2 * Q;
-            _Float16* dst = lds + j2 * 96 + j3;
+            // row = g J2 + j2, and g J2 is a multiple of 8: the rotation depends on g only through bit 3 of g J2
+            const int c = j3 >> 3;
+            const int off0 = j2 * 96 + wrap12(c + rot2(j2)) * 8 + (j3 & 7);
+            const int off8 = j2 * 96 + wrap12(c + rot2(j2 + 8)) * 8 + (j3 & 7);
             static_for<4>([&](auto wc) {
                 constexpr int w = decltype(wc)::value;
                 static_for<2>([&](auto hc) {
@@ -229,10 +241,11 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
                     const float a2 = hf ? bf16_hi(raw[i][2][w]) : bf16_lo(raw[i][2][w]);
                     const float a3 = hf ? bf16_hi(raw[i][3][w]) : bf16_lo(raw[i][3][w]);
                     const float s02 = a0 + a2, d02 = a0 - a2, s13 = a1 + a3, d13 = a3 - a1;
-                    dst[(0 * 8 + ch) * GH] = (_Float16)((s02 + s13) * sc);
-                    dst[(1 * 8 + ch) * GH] = (_Float16)((s02 - s13) * sc);
-                    dst[(2 * 8 + ch) * GH] = (_Float16)(d02 * sc);
-                    dst[(3 * 8 + ch) * GH] = (_Float16)(d13 * sc);
+                    const float xv[4] = {(s02 + s13) * sc, (s02 - s13) * sc, d02 * sc, d13 * sc};
+                    static_for<4>([&](auto xc) {
+                        constexpr int gq = decltype(xc)::value * 8 + ch;
+                        lds[gq * GH + (((gq * J2) & 8) ? off8 : off0)] = (_Float16)xv[xc.value];
+                    });
                 });
             });
         }
@@ -242,36 +255,47 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
     auto dump_and_stop = [&](int phase) -> bool {
         if (!dump || stop != phase) return false;
         if (blockIdx.x == 0)
-            for (int i = tid; i < Cfg::LDS_HALFS; i += 256) dump[i] = lds[i];
+            for (int i = tid; i < Cfg::LDS_HALFS; i += NT) dump[i] = lds[i];
         return true;
     };
     if (dump_and_stop(1)) return;
 
     // ---- phase 2: stage Q.  Rows (g, j2) x contraction j3 (96) -> f (96); a wave owns whole units of UROWS
-    // rows, reads all of a unit, then overwrites it with the transposed result [g][f][j2].
+    // rows, reads all of a unit, then overwrites it with the transposed result [g][f][j2].  The units of a
+    // wave run side by side, so that the fragment reads of one overlap the matrix instructions of the other.
     {
         half8 bq[3][6];
         const half8* tq = (const half8*)(tables + Cfg::OFF_Q) + lane;
         static_for<3>([&](auto ct) {
             static_for<6>([&](auto ks) { bq[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
         });
-        for (int u = wave; u < Cfg::NUNITS; u += 4) {
-            f32x16 acc[Cfg::RT][3];
+        constexpr int UU = Cfg::NUNITS / NW;           // units per wave
+        static_assert(Cfg::NUNITS % NW == 0 && UU * Cfg::RT * NW <= 24, "units of a wave fit the register file");
+        f32x16 acc[UU][Cfg::RT][3];
+        static_for<UU>([&](auto uu) {
             static_for<Cfg::RT>([&](auto rt) {
                 static_for<3>([&](auto ct) {
-                    static_for<16>([&](auto r) { acc[rt.value][ct.value][r.value] = 0.f; });
+                    static_for<16>([&](auto r) { acc[uu.value][rt.value][ct.value][r.value] = 0.f; });
                 });
             });
-            const _Float16* src = lds + (u * Cfg::UROWS + l32) * 96 + 8 * lhi;
-            static_for<6>([&](auto ks) {
+        });
+        // every tile of 32 rows starts at a multiple of 32: the rotation of a lane's row is the same in all of them
+        const int rot = rot2(l32);
+        static_for<6>([&](auto ks) {
+            const int coff = wrap12(ks.value * 2 + lhi + rot) * 8;
+            static_for<UU>([&](auto uu) {
+                const _Float16* src = lds + ((wave + NW * uu.value) * Cfg::UROWS + l32) * 96 + coff;
                 static_for<Cfg::RT>([&](auto rt) {
-                    const half8 a = *(const half8*)(src + rt.value * 32 * 96 + ks.value * 16);
+                    const half8 a = *(const half8*)(src + rt.value * 32 * 96);
                     static_for<3>([&](auto ct) {
-                        acc[rt.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            a, bq[ct.value][ks.value], acc[rt.value][ct.value], 0, 0, 0);
+                        acc[uu.value][rt.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            a, bq[ct.value][ks.value], acc[uu.value][rt.value][ct.value], 0, 0, 0);
                     });
                 });
             });
+        });
+        static_for<UU>([&](auto uu) {
+            const int u = wave + NW * uu.value;
             static_for<Cfg::RT>([&](auto rt) {
                 static_for<4>([&](auto r4) {
                     const int row = u * Cfg::UROWS + rt.value * 32 + 8 * r4.value + 4 * lhi;   // first of 4 rows
@@ -279,49 +303,71 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
                     static_for<3>([&](auto ct) {
                         const int f = ct.value * 32 + l32;
                         half4 o;
-                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[rt.value][ct.value][4 * r4.value + k.value]; });
+                        static_for<4>([&](auto k) {
+                            o[k.value] = (_Float16)acc[uu.value][rt.value][ct.value][4 * r4.value + k.value];
+                        });
                         *(half4*)(lds + grp * GH + f * J2 + j2) = o;
                     });
                 });
             });
-        }
+        });
     }
     __syncthreads();
     ts[2] = stamp ? (long long)clock64() : 0;
     if (dump_and_stop(2)) return;
 
     // ---- phase 3: stage P.  Columns m' = (g, f3) x contraction (part, j2) -> (part', f2); the data are the
-    // second operand, so a lane keeps one column and gets 4 consecutive f2: written back in place.
+    // second operand, so a lane keeps one column and gets 4 consecutive f2: written back in place.  TU tiles of
+    // 32 columns are in flight per wave.
     {
         half8 ap[Cfg::NTP][Cfg::KSP];
         const half8* tp = (const half8*)(tables + Cfg::OFF_P) + lane;
         static_for<Cfg::NTP>([&](auto nt) {
             static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = tp[(nt.value * Cfg::KSP + ks.value) * 64]; });
         });
-        for (int t = wave; t < QH; t += 4) {           // 32 QH columns = QH tiles of 32
-            const int mp = t * 32 + l32;
-            const int grp = mp / QH, f3 = mp - grp * QH;
-            _Float16* col = lds + grp * GH + f3 * J2;
-            f32x16 acc[Cfg::NTP];
-            static_for<Cfg::NTP>([&](auto nt) { static_for<16>([&](auto r) { acc[nt.value][r.value] = 0.f; }); });
-            static_for<Cfg::KSP>([&](auto ks) {
-                const int k = ks.value * 16 + 8 * lhi;
-                const int part = k / J2, j2c = k - part * J2;
-                const half8 b = *(const half8*)(col + part * QH * J2 + j2c);
-                static_for<Cfg::NTP>([&](auto nt) {
-                    acc[nt.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ap[nt.value][ks.value], b, acc[nt.value], 0, 0, 0);
+        constexpr int TU = NW == 8 ? 3 : 4;
+        for (int t0 = wave; t0 < QH; t0 += NW * TU) {  // 32 QH columns = QH tiles of 32
+            _Float16* col[TU];
+            half8 b[TU][Cfg::KSP];
+            static_for<TU>([&](auto tu) {
+                int t = t0 + NW * tu.value;
+                if (t > QH - 1) t = QH - 1;            // a tile past the end repeats the last one and is not written
+                const int mp = t * 32 + l32;
+                const int grp = mp / QH, f3 = mp - grp * QH;
+                col[tu.value] = lds + grp * GH + f3 * J2;
+                static_for<Cfg::KSP>([&](auto ks) {
+                    constexpr int k = ks.value * 16;
+                    const int kk = k + 8 * lhi;
+                    const int part = kk / J2, j2c = kk - part * J2;
+                    b[tu.value][ks.value] = *(const half8*)(col[tu.value] + part * QH * J2 + j2c);
                 });
             });
-            static_for<Cfg::NTP>([&](auto nt) {
-                static_for<4>([&](auto r4) {
-                    const int n0 = nt.value * 32 + 8 * r4.value + 4 * lhi;
-                    if (n0 < Cfg::KP) {
-                        const int part = n0 / J2, f2 = n0 - part * J2;
-                        half4 o;
-                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[nt.value][4 * r4.value + k.value]; });
-                        *(half4*)(col + part * QH * J2 + f2) = o;
-                    }
+            f32x16 acc[TU][Cfg::NTP];
+            static_for<TU>([&](auto tu) {
+                static_for<Cfg::NTP>([&](auto nt) { static_for<16>([&](auto r) { acc[tu.value][nt.value][r.value] = 0.f; }); });
+            });
+            static_for<Cfg::KSP>([&](auto ks) {
+                static_for<TU>([&](auto tu) {
+                    static_for<Cfg::NTP>([&](auto nt) {
+                        acc[tu.value][nt.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            ap[nt.value][ks.value], b[tu.value][ks.value], acc[tu.value][nt.value], 0, 0, 0);
+                    });
                 });
+            });
+            static_for<TU>([&](auto tu) {
+                if (t0 + NW * tu.value < QH) {
+                    static_for<Cfg::NTP>([&](auto nt) {
+                        static_for<4>([&](auto r4) {
+                            const int n0 = nt.value * 32 + 8 * r4.value + 4 * lhi;
+                            if (n0 < Cfg::KP) {
+                                const int part = n0 / J2, f2 = n0 - part * J2;
+                                half4 o;
+                                static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][nt.value][4 * r4.value + k.value]; });
+                                *(half4*)(col[tu.value] + part * QH * J2 + f2) = o;
+                            }
+                        });
+                    });
+                }
             });
         }
     }
@@ -329,31 +375,47 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
     ts[3] = stamp ? (long long)clock64() : 0;
     if (dump_and_stop(3)) return;
 
-    // ---- phase 4: middle.  Lane takes jobs (k2, k3) and, per channel, the four arrays' coefficients there:
-    // (F0, F2) give U of the even k with these residues, (Fr, Fi) of the odd k; both land in place.
+    // ---- phase 4: middle.  An item is two neighbouring k2 of one k3 (one dword per array and part) and four
+    // channels; per channel the four arrays' coefficients there give, through a 2x4 real map each,
+    // U of the even k with these residues (from F0, F2) and of the odd k (from Fr, Fi); both land in place
+    // of F0 and F2.  Packed fp16 arithmetic: both k2 of the pair at once.
     {
-        constexpr int NJI = (Cfg::NJOBS + 255) / 256;
-        for (int i = 0; i < NJI; ++i) {
-            const int jb = tid + 256 * i;
-            if (jb >= Cfg::NJOBS) break;
-            const int k3 = jb / P, k2 = jb - k3 * P;
-            const f32x4* T = (const f32x4*)(tables + Cfg::OFF_JOBS) + jb * 4;
-            const f32x4 t0 = T[0], t1 = T[1], t2 = T[2], t3 = T[3];
-            _Float16* re = lds + k3 * J2 + k2;
-            _Float16* im = re + QH * J2;
-#pragma unroll
-            for (int ch = 0; ch < 8; ++ch) {
-                const float ar = (float)re[(0 * 8 + ch) * GH], ai = (float)im[(0 * 8 + ch) * GH];
-                const float br = (float)re[(1 * 8 + ch) * GH], bi = (float)im[(1 * 8 + ch) * GH];
-                const float cr = (float)re[(2 * 8 + ch) * GH], ci = (float)im[(2 * 8 + ch) * GH];
-                const float dr = (float)re[(3 * 8 + ch) * GH], di = (float)im[(3 * 8 + ch) * GH];
-                const float er = t0[0] * ar + t0[1] * ai + t0[2] * br + t0[3] * bi;
-                const float ei = t1[0] * ar + t1[1] * ai + t1[2] * br + t1[3] * bi;
-                const float orr = t2[0] * cr + t2[1] * ci + t2[2] * dr + t2[3] * di;
-                const float oi = t3[0] * cr + t3[1] * ci + t3[2] * dr + t3[3] * di;
-                re[(0 * 8 + ch) * GH] = (_Float16)er;  im[(0 * 8 + ch) * GH] = (_Float16)ei;
-                re[(1 * 8 + ch) * GH] = (_Float16)orr; im[(1 * 8 + ch) * GH] = (_Float16)oi;
-            }
+        constexpr int NITEMS = 2 * Cfg::NPJ;
+        constexpr int NR = (NITEMS + NT - 1) / NT;
+        uint32_t* lds32 = (uint32_t*)lds;
+        for (int r = 0; r < NR; ++r) {
+            const int it = tid + NT * r;
+            if (it >= NITEMS) break;
+            const int half = it >= Cfg::NPJ ? 1 : 0;
+            const int pj = it - half * Cfg::NPJ;
+            const int k3 = pj / (J2 / 2), kp = pj - k3 * (J2 / 2);
+            const u32x4* T = (const u32x4*)(tables + Cfg::OFF_JOBS) + pj * 4;
+            const u32x4 q0 = T[0], q1 = T[1], q2 = T[2], q3 = T[3];
+            half2v t[16];
+            static_for<4>([&](auto i) {
+                // (a bit cast straight from a vector ELEMENT reads element 0 whatever the index: copy first)
+                const uint32_t w0 = q0[i.value], w1 = q1[i.value], w2 = q2[i.value], w3 = q3[i.value];
+                t[i.value] = __builtin_bit_cast(half2v, w0);
+                t[4 + i.value] = __builtin_bit_cast(half2v, w1);
+                t[8 + i.value] = __builtin_bit_cast(half2v, w2);
+                t[12 + i.value] = __builtin_bit_cast(half2v, w3);
+            });
+            uint32_t* re = lds32 + (k3 * J2) / 2 + kp;
+            uint32_t* im = re + (QH * J2) / 2;
+            static_for<4>([&](auto cc) {
+                const int ch = half * 4 + cc.value;
+                auto ld = [&](uint32_t* p, int xa) { return __builtin_bit_cast(half2v, p[(xa * 8 + ch) * (GH / 2)]); };
+                const half2v ar = ld(re, 0), ai = ld(im, 0), br = ld(re, 1), bi = ld(im, 1);
+                const half2v cr = ld(re, 2), ci = ld(im, 2), dr = ld(re, 3), di = ld(im, 3);
+                const half2v er = t[0] * ar + t[1] * ai + t[2] * br + t[3] * bi;
+                const half2v ei = t[4] * ar + t[5] * ai + t[6] * br + t[7] * bi;
+                const half2v orr = t[8] * cr + t[9] * ci + t[10] * dr + t[11] * di;
+                const half2v oi = t[12] * cr + t[13] * ci + t[14] * dr + t[15] * di;
+                re[(0 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, er);
+                im[(0 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, ei);
+                re[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, orr);
+                im[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, oi);
+            });
         }
     }
     __syncthreads();
@@ -369,35 +431,51 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
         static_for<Cfg::NTP>([&](auto ct) {
             static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = tp[(ct.value * Cfg::KSP + ks.value) * 64]; });
         });
-        for (int t = wave; t < 24; t += 4) {           // 16 x 48 rows
-            const int mp = t * 32 + l32;
-            const int grp = mp / 48;
-            int k3 = mp - grp * 48;
-            if (k3 > QH - 1) k3 = QH - 1;              // pad rows: any finite data, their results meet zeros
-            const _Float16* rowp = lds + grp * GH + k3 * J2;
-            f32x16 acc[Cfg::NTP];
-            static_for<Cfg::NTP>([&](auto ct) { static_for<16>([&](auto r) { acc[ct.value][r.value] = 0.f; }); });
-            static_for<Cfg::KSP>([&](auto ks) {
-                const int k = ks.value * 16 + 8 * lhi;
-                const int part = k / J2, k2c = k - part * J2;
-                const half8 a = *(const half8*)(rowp + part * QH * J2 + k2c);
-                static_for<Cfg::NTP>([&](auto ct) {
-                    acc[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bp[ct.value][ks.value], acc[ct.value], 0, 0, 0);
+        constexpr int TU = 3;                          // 16 x 48 rows = 24 tiles
+        for (int t0 = wave; t0 < 24; t0 += NW * TU) {
+            half8 a[TU][Cfg::KSP];
+            static_for<TU>([&](auto tu) {
+                const int mp = (t0 + NW * tu.value) * 32 + l32;
+                const int grp = mp / 48;
+                int k3 = mp - grp * 48;
+                if (k3 > QH - 1) k3 = QH - 1;          // pad rows: any finite data, their results meet zeros
+                const _Float16* rowp = lds + grp * GH + k3 * J2;
+                static_for<Cfg::KSP>([&](auto ks) {
+                    const int kk = ks.value * 16 + 8 * lhi;
+                    const int part = kk / J2, k2c = kk - part * J2;
+                    a[tu.value][ks.value] = *(const half8*)(rowp + part * QH * J2 + k2c);
                 });
             });
-            static_for<Cfg::NTP>([&](auto ct) {
-                const int nn = ct.value * 32 + l32;
-                if (nn < Cfg::KP) {
-                    const int part = nn / J2, m2 = nn - part * J2;
-                    static_for<4>([&](auto r4) {
-                        const int m0 = t * 32 + 8 * r4.value + 4 * lhi;       // first of 4 rows, same g'
-                        const int g2 = m0 / 48, k30 = m0 - g2 * 48;
-                        const int k1 = g2 >> 3, ch = g2 & 7;
-                        half4 o;
-                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[ct.value][4 * r4.value + k.value]; });
-                        *(half4*)(lds + Y0 + ((k1 * J2 + m2) * 8 + ch) * 96 + part * 48 + k30) = o;
+            f32x16 acc[TU][Cfg::NTP];
+            static_for<TU>([&](auto tu) {
+                static_for<Cfg::NTP>([&](auto ct) { static_for<16>([&](auto r) { acc[tu.value][ct.value][r.value] = 0.f; }); });
+            });
+            static_for<Cfg::KSP>([&](auto ks) {
+                static_for<TU>([&](auto tu) {
+                    static_for<Cfg::NTP>([&](auto ct) {
+                        acc[tu.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            a[tu.value][ks.value], bp[ct.value][ks.value], acc[tu.value][ct.value], 0, 0, 0);
                     });
-                }
+                });
+            });
+            static_for<TU>([&](auto tu) {
+                const int t = t0 + NW * tu.value;
+                static_for<Cfg::NTP>([&](auto ct) {
+                    const int nn = ct.value * 32 + l32;
+                    if (nn < Cfg::KP) {
+                        const int part = nn / J2, m2 = nn - part * J2;
+                        static_for<4>([&](auto r4) {
+                            const int m0 = t * 32 + 8 * r4.value + 4 * lhi;       // first of 4 rows, same g'
+                            const int g2 = m0 / 48, k30 = m0 - g2 * 48;
+                            const int k1 = g2 >> 3, ch = g2 & 7;
+                            const int row = (k1 * J2 + m2) * 8 + ch;
+                            const int c = part * 6 + (k30 >> 3);
+                            half4 o;
+                            static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][ct.value][4 * r4.value + k.value]; });
+                            *(half4*)(lds + Y0 + row * 96 + wrap12(c + rot12(row)) * 8 + (k30 & 7)) = o;
+                        });
+                    }
+                });
             });
         }
     }
@@ -414,26 +492,44 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
             static_for<6>([&](auto ks) { bq[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
         });
         constexpr int NT6 = 16 * J2 / 32;
-        for (int t = wave; t < NT6; t += 4) {
-            const _Float16* src = lds + Y0 + (t * 32 + l32) * 96 + 8 * lhi;
-            f32x16 acc[3];
-            static_for<3>([&](auto ct) { static_for<16>([&](auto r) { acc[ct.value][r.value] = 0.f; }); });
+        constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
+        static_assert(TU <= 3, "tiles of a wave fit the register file");
+        for (int t0 = wave; t0 < NT6; t0 += NW * TU) {
+            f32x16 acc[TU][3];
+            static_for<TU>([&](auto tu) {
+                static_for<3>([&](auto ct) { static_for<16>([&](auto r) { acc[tu.value][ct.value][r.value] = 0.f; }); });
+            });
+            const _Float16* src[TU];
+            int rot[TU];
+            static_for<TU>([&](auto tu) {
+                int t = t0 + NW * tu.value;
+                if (t > NT6 - 1) t = NT6 - 1;          // a tile past the end repeats the last one and is not written
+                const int row = t * 32 + l32;
+                src[tu.value] = lds + Y0 + row * 96;
+                rot[tu.value] = rot12(row) + lhi;
+            });
             static_for<6>([&](auto ks) {
-                const half8 a = *(const half8*)(src + ks.value * 16);
-                static_for<3>([&](auto ct) {
-                    acc[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bq[ct.value][ks.value], acc[ct.value], 0, 0, 0);
+                static_for<TU>([&](auto tu) {
+                    const half8 a = *(const half8*)(src[tu.value] + wrap12(wrap12(ks.value * 2 + rot[tu.value])) * 8);
+                    static_for<3>([&](auto ct) {
+                        acc[tu.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                            a, bq[ct.value][ks.value], acc[tu.value][ct.value], 0, 0, 0);
+                    });
                 });
             });
-            static_for<3>([&](auto ct) {
-                const int m3 = ct.value * 32 + l32;
-                if (m3 < Q) {
-                    static_for<4>([&](auto r4) {
-                        const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) 8 + ch, ch = 0 or 4
-                        half4 o;
-                        static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[ct.value][4 * r4.value + k.value]; });
-                        *(half4*)(lds + ((v0 >> 3) * 96 + m3) * 8 + (v0 & 7)) = o;
-                    });
-                }
+            static_for<TU>([&](auto tu) {
+                const int t = t0 + NW * tu.value;
+                static_for<3>([&](auto ct) {
+                    const int m3 = ct.value * 32 + l32;
+                    if (m3 < Q && t < NT6) {
+                        static_for<4>([&](auto r4) {
+                            const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) 8 + ch, ch = 0 or 4
+                            half4 o;
+                            static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][ct.value][4 * r4.value + k.value]; });
+                            *(half4*)(lds + ((v0 >> 3) * 96 + m3) * 8 + (v0 & 7)) = o;
+                        });
+                    }
+                });
             });
         }
     }
@@ -447,7 +543,7 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
         for (int i = 0; i < NIT; ++i) {
-            const int pos = tid + 256 * i;
+            const int pos = tid + NT * i;
             if (pos >= Cfg::NPOS) break;
             const int m2 = pos / Q, m3 = pos - m2 * Q;
             const half8 g0 = *(const half8*)(lds + ((0 * J2 + m2) * 96 + m3) * 8);
@@ -484,8 +580,8 @@ __global__ __launch_bounds__(256, 1) void k_fast(SlabTable tab, Geom g, const ch
         __syncthreads();
         ts[7] = (long long)clock64();
         if (tid == 0) {
-            long long* o = (long long*)dump + (long long)blockIdx.x * 8;
-            for (int i = 0; i < 8; ++i) o[i] = ts[i];
+            long long* o = (long long*)dump + (long long)blockIdx.x * 9;
+            for (int i = 0; i < 9; ++i) o[i] = ts[i];
         }
     }
 }
@@ -556,48 +652,51 @@ void build_tables(char* out)
     });
     // middle: per (k2, k3) the 2x4 maps (F0, F2) -> U of the even k and (Fr, Fi) -> U of the odd k
     const long long e2 = (long long)Q * mod_inverse(Q, P) % N, e3 = (long long)P * mod_inverse(P, Q) % N;
-    float* jobs = (float*)(out + Cfg::OFF_JOBS);
+    _Float16* jobs = (_Float16*)(out + Cfg::OFF_JOBS);     // [k3][k2 / 2][16 coefficients][k2 & 1]
     for (int k3 = 0; k3 < QH; ++k3) {
-        for (int k2 = 0; k2 < P; ++k2) {
-            const long long tau = (k2 * e2 + k3 * e3) % N, taup = N - tau;
-            const long long kk[4] = {tau, tau + N, taup, taup + N};       // a, b (these residues); c, d (negated)
+        for (int k2 = 0; k2 < J2; ++k2) {
             double T[2][2][8];                                             // [parity of k][re|im][input]
-            for (int in = 0; in < 8; ++in) {
-                double x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-                x[in] = 1.0;
-                // inputs: F0 (re, im), F2, Fr, Fi at (k2, k3); at the negated residues each is conjugated
-                auto V = [&](long long k, bool neg, double* vr, double* vi) {
-                    const double s = neg ? -1.0 : 1.0;
-                    const double ar = x[0], ai = s * x[1], br = x[2], bi = s * x[3];
-                    const double cr = x[4], ci = s * x[5], dr = x[6], di = s * x[7];
-                    switch (k % 4) {
-                        case 0: *vr = ar; *vi = ai; break;
-                        case 1: *vr = cr - di; *vi = ci + dr; break;          // Fr + i Fi
-                        case 2: *vr = br; *vi = bi; break;
-                        default: *vr = cr + di; *vi = ci - dr; break;         // Fr - i Fi
+            for (int a = 0; a < 2; ++a) for (int b = 0; b < 2; ++b) for (int c = 0; c < 8; ++c) T[a][b][c] = 0.0;
+            if (k2 < P) {
+                const long long tau = (k2 * e2 + k3 * e3) % N, taup = N - tau;
+                const long long kk[4] = {tau, tau + N, taup, taup + N};   // a, b (these residues); c, d (negated)
+                for (int in = 0; in < 8; ++in) {
+                    double x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                    x[in] = 1.0;
+                    // inputs: F0 (re, im), F2, Fr, Fi at (k2, k3); at the negated residues each is conjugated
+                    auto V = [&](long long k, bool neg, double* vr, double* vi) {
+                        const double sg = neg ? -1.0 : 1.0;
+                        const double ar = x[0], ai = sg * x[1], br = x[2], bi = sg * x[3];
+                        const double cr = x[4], ci = sg * x[5], dr = x[6], di = sg * x[7];
+                        switch (k % 4) {
+                            case 0: *vr = ar; *vi = ai; break;
+                            case 1: *vr = cr - di; *vi = ci + dr; break;          // Fr + i Fi
+                            case 2: *vr = br; *vi = bi; break;
+                            default: *vr = cr + di; *vi = ci - dr; break;         // Fr - i Fi
+                        }
+                    };
+                    double C[4];
+                    for (int w = 0; w < 4; ++w) {
+                        if (kk[w] >= Lc) { C[w] = 0.0; continue; }                // the coefficient that is not kept
+                        double vr, vi;
+                        V(kk[w], w >= 2, &vr, &vi);
+                        const double th = kPi * (double)kk[w] / (2.0 * n);
+                        C[w] = std::cos(th) * vr + std::sin(th) * vi;             // Re(e^{-i th} V)
                     }
-                };
-                double C[4];
-                for (int w = 0; w < 4; ++w) {
-                    if (kk[w] >= Lc) { C[w] = 0.0; continue; }                // the coefficient that is not kept
-                    double vr, vi;
-                    V(kk[w], w >= 2, &vr, &vi);
-                    const double th = kPi * (double)kk[w] / (2.0 * n);
-                    C[w] = std::cos(th) * vr + std::sin(th) * vi;             // Re(e^{-i th} V)
+                    // U_a = e^{i pi ka / 2Lc} (C_a - i C_d),  U_b = e^{i pi kb / 2Lc} (C_b - i C_c)
+                    const double ta = kPi * (double)kk[0] / (2.0 * Lc), tb = kPi * (double)kk[1] / (2.0 * Lc);
+                    const double uar = std::cos(ta) * C[0] + std::sin(ta) * C[3], uai = std::sin(ta) * C[0] - std::cos(ta) * C[3];
+                    const double ubr = std::cos(tb) * C[1] + std::sin(tb) * C[2], ubi = std::sin(tb) * C[1] - std::cos(tb) * C[2];
+                    const int pa = (int)(kk[0] & 1), pb = (int)(kk[1] & 1);
+                    T[pa][0][in] = uar; T[pa][1][in] = uai;
+                    T[pb][0][in] = ubr; T[pb][1][in] = ubi;
                 }
-                // U_a = e^{i pi ka / 2Lc} (C_a - i C_d),  U_b = e^{i pi kb / 2Lc} (C_b - i C_c)
-                const double ta = kPi * (double)kk[0] / (2.0 * Lc), tb = kPi * (double)kk[1] / (2.0 * Lc);
-                const double uar = std::cos(ta) * C[0] + std::sin(ta) * C[3], uai = std::sin(ta) * C[0] - std::cos(ta) * C[3];
-                const double ubr = std::cos(tb) * C[1] + std::sin(tb) * C[2], ubi = std::sin(tb) * C[1] - std::cos(tb) * C[2];
-                const int pa = (int)(kk[0] & 1), pb = (int)(kk[1] & 1);
-                T[pa][0][in] = uar; T[pa][1][in] = uai;
-                T[pb][0][in] = ubr; T[pb][1][in] = ubi;
             }
-            float* o = jobs + ((size_t)k3 * P + k2) * 16;
+            _Float16* o = jobs + ((size_t)k3 * (J2 / 2) + k2 / 2) * 32 + (k2 & 1);
             for (int r = 0; r < 2; ++r)
                 for (int in = 0; in < 4; ++in) {
-                    o[r * 4 + in] = (float)T[0][r][in];            // even k: from (F0, F2)
-                    o[8 + r * 4 + in] = (float)T[1][r][4 + in];    // odd k: from (Fr, Fi)
+                    o[(r * 4 + in) * 2] = (_Float16)T[0][r][in];            // even k: from (F0, F2)
+                    o[(8 + r * 4 + in) * 2] = (_Float16)T[1][r][4 + in];    // odd k: from (Fr, Fi)
                 }
         }
     }
@@ -608,7 +707,8 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
                       _Float16* dump, int stop, hipStream_t st)
 {
     const unsigned tasks = (unsigned)(g.ncols / 8);
-    hipLaunchKernelGGL((k_fast<Cfg>), dim3(tasks), dim3(256), 0, st, tab, g, (const char*)tables, rest_scale, tap,
+    constexpr int NW = 8;          // two waves per SIMD: one wave's LDS traffic and conversions overlap the other's matrix work
+    hipLaunchKernelGGL((k_fast<Cfg, NW>), dim3(tasks), dim3(NW * 64), 0, st, tab, g, (const char*)tables, rest_scale, tap,
                        dump, stop);
     return hipGetLastError();
 }

@@ -82,7 +82,7 @@ def test_plan_matches_paper_integers():
     # 8188 = 4 * 23 * 89, ratio 1/2: the factored transform, no workspace, tables of about 113 KiB
     assert (p.span_len, p.retained_len, p.new_len, p.head_tensors, p.variant) == (8188, 4094, 4098, 512, 6)
     assert p.workspace_bytes == 0 and p.workspace_min_bytes == 0
-    assert p.basis_bytes == 2 * 18 * 1024 + 2 * 6 * 1024 + 23 * 45 * 64
+    assert p.basis_bytes == 2 * 18 * 1024 + 2 * 6 * 1024 + 45 * 12 * 64
     assert p.flops_dense == pytest.approx(2.0 * 4094 * 8188 * 128 * 512)
     assert p.bytes_algorithmic == pytest.approx((8188 + 4094) * 128 * 2 * 512)
     per_channel = 2.0 * (4 * 23 * 89 * 90 + 4 * 45 * 4 * 23 * 23 + 16 * 23 * 45 + 2 * 45 * 4 * 23 * 23 + 2 * 23 * 90 * 89)

@@ -153,7 +153,8 @@ def test_large_and_tiny_values_keep_the_tolerance(flags):
 def test_fast_stage_one_image_is_the_length_four_butterfly():
     """The diagnostic entry point's image after the load stage: four real p x q arrays per channel --
     sum, alternating sum, and the two differences of the samples j1 = 0..3 of the reordered span --
-    times half the power of two that brings the slice's largest magnitude into [256, 512)."""
+    times half the power of two that brings the slice's largest magnitude into [256, 512), rows of 96 values
+    with their 16-byte chunks rotated against LDS bank conflicts."""
     import ctypes as C
     p_, q_ = 7, 45
     N, n = p_ * q_, 4 * p_ * q_
@@ -173,7 +174,14 @@ def test_fast_stage_one_image_is_the_length_four_butterfly():
     assert torch.equal(k, k_before)                      # the diagnostic writes nothing to the cache
     x = f64(k[0, 0, 0, 4:, :8])
     e = 8 - math.floor(math.log2(np.abs(x).max()))
-    img = dump.double().cpu().numpy().reshape(4, 8, J2, 96)
+    phys = dump.double().cpu().numpy().reshape(32 * J2, 12, 8)
+    # a row's 12 chunks of 8 values are stored rotated by rot(row) = 2 * bit 2 of the row + bit 3 of the row
+    img = np.empty_like(phys)
+    for row in range(32 * J2):
+        rot = ((row >> 1) & 2) | ((row >> 3) & 1)
+        for c in range(12):
+            img[row, c] = phys[row, (c + rot) % 12]
+    img = img.reshape(4, 8, J2, 96)
     for j2 in range(p_):
         for j3 in range(q_):
             a = []
