@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the FreqKV compression hot path on one MI355X.
 
-A step = one compression trigger over the whole cache of the workload (all layers' K and V:
-fold/convert -> contraction -> in-place write) through the C ABI, inputs resident in HBM.
+A step = one compression trigger over the whole cache of the workload (all layers' K and V: DCT -> keep the
+low half -> inverse -> in-place write, as one factored transform kernel, or fold/convert -> contraction with
+--dense) through the C ABI, inputs resident in HBM.
 Default workload: the LLaMA-3-8B GQA cache of the 128K iterative prefill (32 layers x 8 KV heads
 x head_dim 128, bf16, window 8192, 4 sinks, ratio 0.5): 512 head-tensors, span 8188 -> 4094.
 
@@ -27,6 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # kernel (profiles/contract_llama3_8b_128k_pmc.txt).
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.244e5 + 9.187e5) + 1.0 * (2.62e5 + 5.24e5)) * 1024}
 TRAFFIC_BYTES_SINGLE_FOLD = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
+# the same for the factored transform's single kernel (profiles/fast_llama3_8b_128k_pmc.txt)
+FAST_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.376e5 + 1.0 * 5.24e5) * 1024}
 # the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
 ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
 # the same for k_attend_prefill (profiles/prefill_llama3_8b_128k.txt)
@@ -374,6 +377,12 @@ def main():
                     help="use the one-level even/odd fold where the two-level fold would be chosen (comparison)")
     ap.add_argument("--two-level", action="store_true",
                     help="use the two-level fold wherever it applies, also for spans below its default threshold")
+    ap.add_argument("--dense", action="store_true",
+                    help="use the matrix form (fp16 MFMA contraction) where the factored transform would be chosen (comparison)")
+    ap.add_argument("--stream", action="store_true",
+                    help="run the workload's whole trigger schedule (total_tokens through the window), every trigger timed")
+    ap.add_argument("--sustain-seconds", type=float, default=2.0,
+                    help="length of the sustained loop (triggers with the cache refilled in between); 0 skips it")
     ap.add_argument("--dropping", action="store_true",
                     help="time the Dropping variant (row moves only): the memcpy-roofline reference of the write-back step")
     args = ap.parse_args()
@@ -406,24 +415,45 @@ def main():
     # synthetic cache, resident in HBM
     k, v = synth.empty_cache(wl, dev)
     synth.KVSource(wl, seed=0, device=dev).fill(k, v, 0, wl.window)
-    L = binding.layout_for(k, flags=fk.FLAG_DROPPING if args.dropping else (fk.FLAG_SINGLE_FOLD if args.single_fold else (fk.FLAG_TWO_LEVEL_FOLD if args.two_level else 0)))
+    flags = 0
+    if args.dropping:
+        flags = fk.FLAG_DROPPING
+    elif args.single_fold:
+        flags = fk.FLAG_SINGLE_FOLD
+    elif args.two_level:
+        flags = fk.FLAG_TWO_LEVEL_FOLD
+    elif args.dense:
+        flags = fk.FLAG_DENSE
+    L = binding.layout_for(k, flags=flags)
     _, p = fk.plan(L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio)
-    ws = torch.empty(max(p.workspace_bytes, 1 << 30 if args.dropping else 256), dtype=torch.uint8, device=dev)
+    ws = torch.empty(max(p.workspace_bytes, 1 << 30), dtype=torch.uint8, device=dev)     # also the calibration copy's buffer
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
     stream = torch.cuda.current_stream()
+    H, d, W, S = wl.n_heads, wl.head_dim, wl.window, wl.n_sink
 
     def step():
-        fk.compress(k, v, L, wl.n_heads, wl.head_dim, wl.window, wl.window, wl.n_sink, wl.retain_ratio, stream)
+        fk.compress(k, v, L, H, d, W, W, S, wl.retain_ratio, stream)
+
+    if args.stream:
+        return bench_stream(args, wl, k, v, L, p, step)
 
     cpu = None
     if not args.no_cpu_baseline and wl.dtype == torch.bfloat16 and not args.dropping:
         cores = min(16, os.cpu_count() or 1)
         cpu = cpu_baseline(wl, k, cores)
 
+    # the rows a caller appends between two triggers (Sec. 3.4: window - n_sink - Lc new tokens), generated once
+    chunk_k, chunk_v = k[:, :, :, p.new_len:W].clone(), v[:, :, :, p.new_len:W].clone()
+
+    def refill():
+        k[:, :, :, p.new_len:W].copy_(chunk_k)
+        v[:, :, :, p.new_len:W].copy_(chunk_v)
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
+    # ---- the timed region: K back-to-back triggers on a full cache, inputs resident in HBM
     fk.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -434,10 +464,36 @@ def main():
     prof = fk.profile_read()
     fk.profile_enable(False)
 
+    # ---- sustained: at least args.sustain_seconds of triggers, the cache refilled with the pre-generated rows
+    # between them (the refill is the caller's work: each trigger is timed by its own pair of events)
+    sustained = None
+    if args.sustain_seconds > 0 and not args.dropping:
+        fk.profile_enable(True)
+        evs = []
+        t_end = time.perf_counter() + args.sustain_seconds
+        while time.perf_counter() < t_end or len(evs) < 8:
+            for _ in range(32):
+                refill()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                step()
+                b.record(stream)
+                evs.append((a, b))
+            torch.cuda.synchronize()
+        times = sorted(a.elapsed_time(b) for a, b in evs)
+        sprof = fk.profile_read()
+        fk.profile_enable(False)
+        s_launches = max(int(sprof.launches_contract), 1)
+        sustained = {"triggers": len(times), "seconds_of_triggers": sum(times) * 1e-3,
+                     "ms_per_step": sum(times) / len(times), "ms_median": times[len(times) // 2],
+                     "ms_p10": times[len(times) // 10], "ms_p90": times[len(times) * 9 // 10],
+                     "ms_main_kernel_per_trigger": sprof.ms_contract / len(times),
+                     "ms_prepare_kernel_per_trigger": sprof.ms_prepare / len(times),
+                     "launches_per_trigger": s_launches / len(times)}
+
     # what this device sustains: plain copy (read+write) and a register-only fp16 MFMA loop on random operands
-    calib_n = min(ws.numel() // 2, 1 << 30) // 16 * 16
-    wsv = ws.view(torch.uint8)
-    copy_gbs = fk.calibrate_copy(wsv[calib_n:].data_ptr(), wsv.data_ptr(), calib_n, 10, stream) if calib_n >= 1 << 20 else None
+    calib_n = 1 << 29
+    copy_gbs = fk.calibrate_copy(ws[calib_n:].data_ptr(), ws.data_ptr(), calib_n, 10, stream)
     mfma_tflops = fk.calibrate_mfma(20000, stream)
 
     ms_per_step = dt / args.steps * 1e3
@@ -447,10 +503,12 @@ def main():
     value = bytes_in / (dt / args.steps) / 1e9
 
     launches = max(int(prof.launches_contract), 1)
+    per_trigger = launches / args.steps
     ms_contract = prof.ms_contract / launches
     ms_prepare = prof.ms_prepare / max(int(prof.launches_prepare), 1)
     flops_launch = p.flops_executed * args.steps / launches
     achieved = flops_launch / max(ms_contract * 1e-3, 1e-12) / 1e12
+    variant = int(p.variant)
     if args.dropping:
         # the whole step is k_move_rows launches (timed as one span per call by the library)
         ms_move = prof.ms_tail / max(int(prof.calls), 1)
@@ -459,14 +517,40 @@ def main():
                 "frac": gbs / HBM_PEAK_GBS, "traffic": None, "ms_per_launch": ms_move,
                 "bytes_per_launch": p.bytes_algorithmic, "measured_copy_gbs": copy_gbs,
                 "frac_of_measured_copy": gbs / copy_gbs if copy_gbs else None}
+    elif variant == 6:
+        # the factored transform: one kernel per trigger that reads the span and writes the retained rows; its
+        # matrix work is a small fraction of the dense count, so HBM is the roofline it is held against
+        bytes_launch = p.bytes_algorithmic / per_trigger
+        gbs = bytes_launch / (ms_contract * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "k_fast", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbs / HBM_PEAK_GBS, "traffic": FAST_TRAFFIC_BYTES_PER_LAUNCH.get(args.workload),
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this kernel (profiles/), "
+                                  "not measured by this run",
+                "launches_per_trigger": per_trigger, "ms_per_launch": ms_contract, "bytes_per_launch": bytes_launch,
+                "measured_copy_gbs": copy_gbs, "frac_of_measured_copy": gbs / copy_gbs,
+                "executed_tflops": flops_launch / (ms_contract * 1e-3) / 1e12,
+                "sustained_frac": (p.bytes_algorithmic / (sustained["ms_main_kernel_per_trigger"] * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                if sustained else None}
     else:
+        # the matrix forms: ms_contract is the span of the contraction launches of one pass; the fraction over the
+        # whole trigger (prepare pass included) is frac_whole_trigger
+        ms_trigger_kernels = (prof.ms_contract + prof.ms_prepare + prof.ms_tail) / args.steps
         roof = {"bound": "mfma", "kernel": "k_contract_f16", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                "frac_whole_trigger": p.flops_executed / (ms_trigger_kernels * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS,
                 "traffic": (TRAFFIC_BYTES_SINGLE_FOLD if args.single_fold else TRAFFIC_BYTES_PER_LAUNCH).get(args.workload),
-                "launches_per_trigger": 2 if int(p.variant) == 5 else 1,
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run (profiles/), not measured by this run",
+                "launches_per_trigger": 2 if variant == 5 else 1,
                 "ms_per_launch": ms_contract, "flops_per_launch": flops_launch,
-                "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops}
+                "measured_mfma_loop_tflops": mfma_tflops, "frac_of_measured_mfma_loop": achieved / mfma_tflops,
+                "sustained_frac": (p.flops_executed / (sustained["ms_main_kernel_per_trigger"] * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS)
+                if sustained else None}
+    if sustained:
+        sustained["value"] = bytes_in / (sustained["ms_per_step"] * 1e-3) / 1e9
+        sustained["gbs_algorithmic"] = p.bytes_algorithmic / (sustained["ms_per_step"] * 1e-3) / 1e9
 
+    names = {1: "one-level folded matrix form", 2: "plain matrix form", 3: "fp32 matrix form", 4: "dropping",
+             5: "two-level folded matrix form", 6: "factored transform"}
     out = {
         "metric": "KV compression throughput (GB/s KV in)",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -478,7 +562,8 @@ def main():
                                f"head_dim {wl.head_dim}, window {wl.window}, {wl.n_sink} sinks, ratio "
                                f"{wl.retain_ratio}; span {n} -> {p.retained_len}; {p.head_tensors} head-tensors "
                                f"per trigger; one trigger per step",
-                   "variant": int(p.variant), "operator": "dropping" if args.dropping else "freqkv"},
+                   "variant": variant, "form": names.get(variant, "?"),
+                   "operator": "dropping" if args.dropping else "freqkv"},
         "tflops_executed": p.flops_executed / (dt / args.steps) / 1e12,
         "tflops_dense_equivalent": p.flops_dense / (dt / args.steps) / 1e12,
         "gbs_algorithmic": p.bytes_algorithmic / (dt / args.steps) / 1e9,
@@ -486,9 +571,57 @@ def main():
         "ms_prepare_kernel": ms_prepare, "ms_contract_kernel": ms_contract,
         "measured_copy_gbs": copy_gbs,
         "roofline": roof,
+        "sustained": sustained,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def bench_stream(args, wl, k, v, L, p, step):
+    """The whole schedule of the workload (Sec. 3.4): total_tokens streamed through the cache, one trigger each
+    time it is full and more tokens arrive; between two triggers the window - n_sink - Lc new rows are written
+    from pre-generated rows (they stand for that many decode steps or one prefill chunk).  Every trigger is
+    timed by its own pair of events; the refill is not part of the path."""
+    import torch
+    W, S = wl.window, wl.n_sink
+    stream = torch.cuda.current_stream()
+    chunk_k, chunk_v = k[:, :, :, p.new_len:W].clone(), v[:, :, :, p.new_len:W].clone()
+    free = W - p.new_len
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = []
+    fed = W
+    while fed < wl.total_tokens:
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        step()
+        b.record(stream)
+        evs.append((a, b))
+        take = min(free, wl.total_tokens - fed)
+        k[:, :, :, p.new_len:p.new_len + take].copy_(chunk_k[:, :, :, :take])
+        v[:, :, :, p.new_len:p.new_len + take].copy_(chunk_v[:, :, :, :take])
+        fed += take
+    torch.cuda.synchronize()
+    times = sorted(a.elapsed_time(b) for a, b in evs)
+    assert len(times) == -(-(wl.total_tokens - W) // free)      # one trigger per refill of the window
+    elem = 2 if wl.dtype == torch.bfloat16 else 4
+    bytes_in = p.head_tensors * p.span_len * wl.head_dim * elem
+    total_ms = sum(times)
+    print(json.dumps({
+        "metric": "KV compression throughput over the whole schedule (GB/s KV in)",
+        "value": bytes_in * len(times) / (total_ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": len(times),
+        "warmup": args.warmup, "ms_per_step": total_ms / len(times), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.total_tokens} tokens per sequence through a window of {W} "
+                               f"({wl.n_layers} layers x {wl.batch} x {wl.n_heads} KV heads x head_dim {wl.head_dim}): "
+                               f"{len(times)} triggers of {p.head_tensors} head-tensors, span {p.span_len} -> {p.retained_len}",
+                   "variant": int(p.variant), "operator": "freqkv, whole schedule"},
+        "triggers": len(times), "ms_median": times[len(times) // 2], "ms_p10": times[len(times) // 10],
+        "ms_p90": times[len(times) * 9 // 10], "ms_min": times[0], "ms_max": times[-1],
+        "gbs_algorithmic": p.bytes_algorithmic * len(times) / (total_ms * 1e-3) / 1e9,
+        "frac_hbm_roofline": p.bytes_algorithmic * len(times) / (total_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "seconds_of_triggers": total_ms * 1e-3, "roofline": None, "cpu_baseline": None}))
 
 
 if __name__ == "__main__":

@@ -223,3 +223,76 @@ def test_decode_batch8_stream():
     assert cache.triggers == 12
     assert orc.trigger_count(262144, 4096, 4, 0.5) == 127
     _say(f"  worst raw stored err/rms {worst:.3e}")
+
+
+# ------------------------------------------------------------------------------------------
+# free-running drift over the whole schedules: two head-tensors carried in fp64 on the host
+# ------------------------------------------------------------------------------------------
+
+def _free_running(wl, seed, n_cols=16):
+    """Stream wl.total_tokens through the cache.  Two head-tensors (a K head with its outlier channels, a V
+    head of the last layer) are carried on the host in fp64 through EVERY trigger without ever seeing the
+    GPU's rows again (free running), on n_cols channels.  The operator has spectral norm sqrt(Lc/n) < 1
+    (it keeps Lc of n orthonormal directions and rescales), so with r_T the teacher-forced error of trigger T
+    (GPU result minus the oracle on the GPU's own pre-trigger bits) the drift D_T = GPU - free-running obeys
+    ||D_T|| <= sqrt(Lc/n) ||D_{T-1}|| + ||r_T||  (Frobenius norm over the retained block): asserted at every
+    trigger.  Returns (triggers, worst max-abs drift / RMS, last bound / norm of the block)."""
+    W, S = wl.window, wl.n_sink
+    cache = CompressedKVCache(wl.n_layers, wl.batch, wl.n_heads, wl.head_dim, W, S, wl.retain_ratio, wl.dtype, DEV)
+    src = synth.KVSource(wl, seed, DEV)
+    lc = cache.plan.retained_len
+    gain = math.sqrt(lc / (W - S))
+    picks = [(0, 0, 0, 0), (1, wl.n_layers - 1, wl.batch - 1, wl.n_heads - 1)]
+    cols, free, bound = {}, {}, {key: 0.0 for key in picks}
+    fed, worst_rel, last = 0, 0.0, 0.0
+    while fed < wl.total_tokens:
+        kv = (cache.k, cache.v)
+        if cache.cur_len >= W:
+            before = {key: f64(kv[key[0]][key[1], key[2], key[3], :W])[:, cols[key]] for key in picks}
+            assert cache.compress() == 0
+            torch.cuda.synchronize()
+            for key in picks:
+                got = f64(kv[key[0]][key[1], key[2], key[3], S:S + lc])[:, cols[key]]
+                teacher = orc.compress_head(before[key], W, W, S, wl.retain_ratio)[S:]
+                free[key] = orc.compress_head(free[key], W, W, S, wl.retain_ratio)
+                r = float(np.linalg.norm(got - teacher))
+                drift = got - free[key][S:]
+                bound[key] = gain * bound[key] + r
+                dn = float(np.linalg.norm(drift))
+                assert dn <= bound[key] * (1 + 1e-9) + 1e-9, (key, cache.triggers, dn, bound[key])
+                rms = math.sqrt(float((free[key][S:] ** 2).mean()))
+                rel = float(np.abs(drift).max()) / rms
+                # element-wise: every trigger adds at most the tolerance plus half a bf16 step of the largest
+                # retained value, and earlier errors shrink by sqrt(Lc/n) per trigger (a geometric series)
+                floor = 0.5 * float(bf16_ulp(np.abs(free[key][S:]).max())) / rms
+                assert rel <= (TOL_BF16 + floor) / (1.0 - gain), (key, cache.triggers, rel, floor)
+                worst_rel = max(worst_rel, rel)
+                last = bound[key] / float(np.linalg.norm(free[key][S:]))
+        take = min(wl.total_tokens - fed, W - cache.cur_len)
+        kn = torch.empty(wl.n_layers, wl.batch, wl.n_heads, take, wl.head_dim, dtype=wl.dtype, device=DEV)
+        vn = torch.empty_like(kn)
+        src.fill(kn, vn, 0, take)
+        new = (kn, vn)
+        for key in picks:
+            rows = f64(new[key[0]][key[1], key[2], key[3]])
+            if key not in cols:
+                # the channels with the largest RMS first (K: the outlier channels), then seeded others
+                order = np.argsort(-np.sqrt((rows ** 2).mean(axis=0)))
+                rest = np.random.default_rng(seed).permutation(order[4:])[:n_cols - 4]
+                cols[key] = np.sort(np.concatenate([order[:4], rest]))
+                free[key] = np.empty((0, n_cols))
+            free[key] = np.concatenate([free[key], rows[:, cols[key]]], axis=0)
+        cache.append(kn, vn)
+        fed += take
+    return cache.triggers, worst_rel, last
+
+
+@pytest.mark.parametrize("name,layers,count", [("llama2_7b_32k", 2, 15), ("llama3_8b_128k", 2, 31),
+                                               ("decode_b8_256k", 1, 127)])
+def test_free_running_drift_over_the_whole_schedule(name, layers, count):
+    """Configs 3, 4, 5: all 15 / 31 / 127 triggers of the schedule, two head-tensors free running in fp64."""
+    wl = synth.small(synth.WORKLOADS[name], n_layers=layers)
+    triggers, worst, bound_rel = _free_running(wl, seed=90 + count)
+    assert triggers == count == orc.trigger_count(wl.total_tokens, wl.window, wl.n_sink, wl.retain_ratio)
+    _say(f"free running {name}: {triggers} triggers, worst max-abs drift / RMS {worst:.3e}; "
+         f"||drift|| bound from the teacher-forced errors and the gain sqrt(Lc/n): {bound_rel:.3e} of the block norm")
