@@ -169,6 +169,13 @@ FREQKV_API freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_head
  *            synchronise the device and never reads results back.  The first call for a new
  *            (device, n, Lc, dtype, flags) builds and caches the basis table (one allocation).
  * retain_ratio == 1 (Lc == n) is the identity and enqueues nothing (FREQKV_OK).
+ * Value range (bf16 caches): the matrix cores take fp16 operands, whose range is narrower than bfloat16's.
+ * Every head-tensor (every 8-channel slice of one in the factored form) is therefore scaled by an exact
+ * power of two, chosen from the largest magnitude of its span, on its way in and back on its way out, so
+ * finite cache values of any magnitude neither overflow nor sink into fp16 subnormals; only values more
+ * than 2^24 times smaller than the largest of their head-tensor lose precision.  inf / nan rows give
+ * inf / nan results in their channels.  Basis entries below 6e-5 are fp16 subnormals (absolute error
+ * 2^-25, far below the tolerance).
  * On a negative status no device memory has been written.
  */
 FREQKV_API freqkv_status_t freqkv_compress(void* k, void* v, const freqkv_layout_t* layout,
@@ -276,7 +283,8 @@ FREQKV_API freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void
  *   out   DEVICE array [2 (K,V)][n_layers][n_heads][n_rows] fp32, 16-byte aligned; overwritten
  *   layout.workspace   as for a trigger with window - n_sink = n_rows (freqkv_plan reports it for
  *                      n_sink = row0, window = row0 + n_rows, any retain_ratio < 1)
- * bf16 caches only (FREQKV_E_UNSUPPORTED otherwise); n_rows >= 2.  fp16 operands put a noise floor of
+ * bf16 caches only (FREQKV_E_UNSUPPORTED otherwise); n_rows >= 2.  No range guard here: cache values must
+ * stay below 32752 in magnitude (the folded span is an fp16 operand).  fp16 operands put a noise floor of
  * about 2e-7 of the average line under every line.  The sums are accumulated with fp32 atomics, so the
  * last bits can differ from call to call.  The first call for a new (device, n_rows) builds and caches the
  * transform matrix (one allocation of about n_rows^2 bytes).
@@ -323,8 +331,9 @@ FREQKV_API freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, c
  * 6 q-point inverse stage), copies the fp16 LDS image of the workgroup that owns channels 0..7 of the first
  * head-tensor to `dump` (device memory, dump_bytes >= what the span needs, at most 160 KiB) and writes
  * nothing to the cache.  stop = 8 instead runs the whole transform on the K cache of layer 0 (the cache IS
- * written) and leaves, per workgroup, 8 int64 shader-clock readings in dump (start, then after each of the
- * stages above and after the store; dump_bytes >= 64 * batch * n_heads * head_dim / 8).
+ * written) and leaves, per workgroup, 9 int64 shader-clock readings in dump (start, then after each of the
+ * stages above and after the store, then the moment the rows had arrived inside stage 1;
+ * dump_bytes >= 72 * batch * n_heads * head_dim / 8).
  * retain_ratio is 0.5.  FREQKV_E_UNSUPPORTED when the span has no factored form.
  */
 FREQKV_API freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t* layout, int n_heads,

@@ -77,6 +77,7 @@ Geom make_geom(const Shape& sh, const freqkv_layout_t& L, int slabs, int slab0)
     }
     g.Kpad = (int)round_up(g.Kh, kKStage);
     g.nkstages = g.Kpad / kKStage;
+    g.n0 = sh.n; g.Lc0 = sh.Lc;
     g.stride_batch = L.stride_batch; g.stride_head = L.stride_head; g.stride_token = L.stride_token;
     g.tap_slab0 = slab0;
     return g;
@@ -154,8 +155,8 @@ size_t basis_bytes(const Shape& sh, const Geom& g)
     return (size_t)(g.Kpad / 8) * g.Grows * 16;
 }
 
-// Workspace bytes for a pass over `slabs` slabs.
-size_t pass_workspace(const Shape& sh, int slabs)
+// Workspace bytes of a pass over `slabs` slabs without the range guard's table.
+size_t pass_workspace_core(const Shape& sh, int slabs)
 {
     if (sh.variant == kFast) return 0;
     if (sh.variant == kFold2F16) return l2_slices(sh, slabs).total;
@@ -166,6 +167,18 @@ size_t pass_workspace(const Shape& sh, int slabs)
     long long nks = round_up(Kh, kKStage) / kKStage;
     long long ncoltiles = (ncols + kColTile - 1) / kColTile;
     return (size_t)ncoltiles * nks * P * 8192;
+}
+
+// The fp16 forms keep, behind everything else, one 32-bit word per head-tensor of the pass: the largest
+// magnitude of its span, from which the power-of-two scale of the range guard is derived.
+bool has_range_guard(const Shape& sh) { return sh.variant == kFoldF16 || sh.variant == kPlainF16 || sh.variant == kFold2F16; }
+
+// Workspace bytes for a pass over `slabs` slabs.
+size_t pass_workspace(const Shape& sh, int slabs)
+{
+    size_t core = (size_t)round_up((long long)pass_workspace_core(sh, slabs), 256);
+    if (!has_range_guard(sh)) return core;
+    return core + (size_t)round_up((long long)slabs * sh.hts_per_slab * 4, 256);
 }
 
 // The two-level fold saves a quarter of the multiply-adds but runs two shorter launches and moves the even
@@ -664,11 +677,15 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
             // the E buffer is indexed like a tap of this pass alone
             gA.tap_slab0 = 0;
             gB.ebuf = ebuf;
+            uint32_t* hmax = (uint32_t*)((char*)L.workspace + round_up((long long)pass_workspace_core(sh, slabs), 256));
+            gA.hmax = gB.hmax = hmax;
             SlabTable tab;
             memset(&tab, 0, sizeof(tab));
             for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
             ProfSpan sp;
             HIP_TRY(prof_begin(st, 0, &sp));
+            HIP_TRY(launch_fill_zero((float*)hmax, (size_t)slabs * sh.hts_per_slab, st));
+            HIP_TRY(launch_absmax_bf16(tab, gA, hmax, st));
             HIP_TRY(launch_prepare_bf16_l2(tab, gA, wsA, wsB, st));
             HIP_TRY(prof_end(st, &sp));
             if (sh.tail > 0) {
@@ -698,10 +715,17 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
         for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
 
         ProfSpan sp;
-        // 1. span -> workspace (fold + convert, or copy)
+        // 1. span -> workspace (fold + convert, or copy); fp16 forms: first the largest magnitude per head-tensor
         HIP_TRY(prof_begin(st, 0, &sp));
-        if (sh.variant == kF32) HIP_TRY(launch_prepare_f32(tab, g, (float*)L.workspace, st));
-        else                    HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st));
+        if (sh.variant == kF32) {
+            HIP_TRY(launch_prepare_f32(tab, g, (float*)L.workspace, st));
+        } else {
+            uint32_t* hmax = (uint32_t*)((char*)L.workspace + round_up((long long)pass_workspace_core(sh, slabs), 256));
+            g.hmax = hmax;
+            HIP_TRY(launch_fill_zero((float*)hmax, (size_t)slabs * sh.hts_per_slab, st));
+            HIP_TRY(launch_absmax_bf16(tab, g, hmax, st));
+            HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st));
+        }
         HIP_TRY(prof_end(st, &sp));
 
         // 2. recent tail: rows [W, cur_len) -> [S+Lc, ...).  The span has been copied out, so the

@@ -50,6 +50,8 @@ struct Geom {
     int n0, Lc0;         // span and retained length of the full problem
     int H;               // n0/4 rounded up to a pipeline stage: half the contraction length of the odd part
     const _Float16* ebuf; // odd part: fp16 even part E[head-tensor][Lc0/2][d] written by the first launch
+    const uint32_t* hmax; // per head-tensor of this pass: largest bf16 magnitude (bit pattern) of its span, or null:
+                          // the span is scaled by a power of two on its way into the fp16 workspace (range guard)
     int Kh;              // contraction length: n/2 (fold) or n
     int Kpad;            // Kh rounded up to kKStage
     int nkstages;        // Kpad / kKStage
@@ -84,7 +86,21 @@ hipError_t launch_basis_f16(_Float16* G, const Geom& g, int rescale, hipStream_t
 // Mf: [Lc][n] fp32 row-major.
 hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hipStream_t st);
 
-// ---- bf16 cache: fold/convert the span into the workspace, then contract ------------
+// Power of two that brings a head-tensor whose largest bf16 magnitude has the bit pattern `amax` into
+// [2^11, 2^12): sums of four such values stay far below the fp16 limit, and nothing but values 2^-25 of the
+// largest falls into fp16's subnormal range.  Returns the exponent e (scale 2^e); 0 for all-zero, inf or nan.
+__device__ __forceinline__ int guard_exponent(uint32_t amax)
+{
+    const int E = (int)(amax >> 7) & 0xff;
+    if (E == 0 || E == 255) return 0;
+    int e = 138 - E;
+    return e > 120 ? 120 : e;
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }
+
+// ---- bf16 cache: largest magnitude per head-tensor (zero hmax first), fold/convert the span, contract
+hipError_t launch_absmax_bf16(const SlabTable& tab, const Geom& g, uint32_t* hmax, hipStream_t st);
+
 hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
 // mode 0: rows into the cache; 1: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (atomics);
 // 2: even part of the two-level fold, fp16 rows into the buffer passed as tap, nothing else; 3: odd part, combined with g.ebuf into the cache

@@ -205,6 +205,44 @@ hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hip
 // the order the contraction's LDS fragments are read.
 // ------------------------------------------------------------------------------------------
 
+// Largest magnitude of the span of every head-tensor (range guard of the fp16 operands): a thread scans
+// rows j = blockIdx.y*4 + wave, +4*gridDim.y, ... of two adjacent channels; bf16 bit patterns without their
+// sign compare like the magnitudes.  hmax must be zero before the launch.
+__global__ __launch_bounds__(256) void k_absmax_bf16(SlabTable tab, Geom g, uint32_t* __restrict__ hmax)
+{
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const int ct = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int vcol = ct * kColTile + lane * 2;
+    if (vcol >= g.ncols) return;
+    int ht;
+    const char* base = column_base(tab, g, vcol, 2, &ht);
+    const long long rowb = g.stride_token * 2;
+    u16x2 m = {0, 0};
+    for (int j = blockIdx.y * 4 + wave; j < g.n0; j += 4 * gridDim.y) {
+        const uint32_t w = *(const uint32_t*)(base + (long long)(g.S + j) * rowb) & 0x7fff7fffu;
+        m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, w));
+    }
+    uint32_t a = m[0] > m[1] ? m[0] : m[1];
+    if (g.d % kColTile == 0) {
+        // the 128 columns of the wave belong to one head-tensor
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)a, off);
+            a = o > a ? o : a;
+        }
+        if (lane == 0) atomicMax(hmax + ht, a);
+    } else {
+        atomicMax(hmax + ht, a);
+    }
+}
+
+hipError_t launch_absmax_bf16(const SlabTable& tab, const Geom& g, uint32_t* hmax, hipStream_t st)
+{
+    // g.n0: rows of the span (set by the caller for every variant)
+    dim3 grid(g.ncoltiles, 32);
+    hipLaunchKernelGGL(k_absmax_bf16, grid, dim3(256), 0, st, tab, g, hmax);
+    return hipGetLastError();
+}
+
 template <bool FOLD>
 __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Float16* __restrict__ ws)
 {
@@ -219,7 +257,9 @@ __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Fl
 
     uint32_t a[8], b[8];
     const bool colok = vcol < g.ncols;
-    const char* base = colok ? column_base(tab, g, vcol, 2, nullptr) : nullptr;
+    int ht = 0;
+    const char* base = colok ? column_base(tab, g, vcol, 2, &ht) : nullptr;
+    const float sc = (colok && g.hmax) ? pow2f(guard_exponent(g.hmax[ht])) : 1.0f;
     const long long rowb = g.stride_token * 2;   // bytes per token row
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -231,9 +271,9 @@ __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Fl
     half8 e0, e1, o0, o1;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        float a0 = bf16_to_f32(a[i] & 0xffffu), a1 = bf16_to_f32(a[i] >> 16);
+        float a0 = bf16_to_f32(a[i] & 0xffffu) * sc, a1 = bf16_to_f32(a[i] >> 16) * sc;
         if (FOLD) {
-            float b0 = bf16_to_f32(b[i] & 0xffffu), b1 = bf16_to_f32(b[i] >> 16);
+            float b0 = bf16_to_f32(b[i] & 0xffffu) * sc, b1 = bf16_to_f32(b[i] >> 16) * sc;
             e0[i] = (_Float16)(a0 + b0); e1[i] = (_Float16)(a1 + b1);
             o0[i] = (_Float16)(a0 - b0); o1[i] = (_Float16)(a1 - b1);
         } else {
@@ -271,7 +311,9 @@ __global__ __launch_bounds__(256) void k_prepare_bf16_l2(SlabTable tab, Geom g, 
     const int n = g.n0, n2 = n / 2, n4 = n / 4;
 
     const bool colok = vcol < g.ncols;
-    const char* base = colok ? column_base(tab, g, vcol, 2, nullptr) : nullptr;
+    int ht = 0;
+    const char* base = colok ? column_base(tab, g, vcol, 2, &ht) : nullptr;
+    const float sc = (colok && g.hmax) ? pow2f(guard_exponent(g.hmax[ht])) : 1.0f;
     const long long rowb = g.stride_token * 2;
     half8 ee0, ee1, eo0, eo1, od0, od1, om0, om1;
 #pragma unroll
@@ -285,10 +327,10 @@ __global__ __launch_bounds__(256) void k_prepare_bf16_l2(SlabTable tab, Geom g, 
             c = *(const uint32_t*)(base + (long long)(g.S + n2 + j) * rowb);
             d = *(const uint32_t*)(base + (long long)(g.S + n - 1 - j) * rowb);
         }
-        const float a0 = bf16_to_f32(a & 0xffffu), a1 = bf16_to_f32(a >> 16);
-        const float b0 = bf16_to_f32(b & 0xffffu), b1 = bf16_to_f32(b >> 16);
-        const float c0 = bf16_to_f32(c & 0xffffu), c1 = bf16_to_f32(c >> 16);
-        const float d0 = bf16_to_f32(d & 0xffffu), d1 = bf16_to_f32(d >> 16);
+        const float a0 = bf16_to_f32(a & 0xffffu) * sc, a1 = bf16_to_f32(a >> 16) * sc;
+        const float b0 = bf16_to_f32(b & 0xffffu) * sc, b1 = bf16_to_f32(b >> 16) * sc;
+        const float c0 = bf16_to_f32(c & 0xffffu) * sc, c1 = bf16_to_f32(c >> 16) * sc;
+        const float d0 = bf16_to_f32(d & 0xffffu) * sc, d1 = bf16_to_f32(d >> 16) * sc;
         ee0[i] = (_Float16)((a0 + d0) + (b0 + c0)); ee1[i] = (_Float16)((a1 + d1) + (b1 + c1));
         eo0[i] = (_Float16)((a0 + d0) - (b0 + c0)); eo1[i] = (_Float16)((a1 + d1) - (b1 + c1));
         od0[i] = (_Float16)(a0 - d0);               od1[i] = (_Float16)(a1 - d1);
@@ -541,10 +583,13 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
     float* tp = nullptr;
     const _Float16* ep = nullptr;   // MODE 3: the even part of this thread's columns (fp16 buffer)
     _Float16* hp = nullptr;         // MODE 2: where this thread's columns of the even part go
+    float unsc = 1.0f;              // undoes the power-of-two scale of the span (not for the fp16 even part,
+                                    // which stays in the scaled domain until the odd part is combined with it)
     if (col_ok) {
         int ht;
         base = column_base(tab, g, vcol, 2, &ht);
         const int c = vcol - ht * g.d;
+        if (g.hmax && MODE != 2) unsc = pow2f(-guard_exponent(g.hmax[ht]));
         if constexpr (MODE == 1) {
             const int slab = ht / g.hts_per_slab;
             const int h = (ht - slab * g.hts_per_slab) % g.n_heads;
@@ -624,7 +669,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                 return;
             }
             if (!col_ok) return;
-            float va[8], vb[8];
+            float va[8], vb[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             int row_a, row_b = -1;
             if constexpr (FOLD) {
                 // w = row sub-tile; E from wave (parity 0, w), O from wave (parity 1, w)
@@ -664,6 +709,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_contract_f16(SlabTable tab, Geom
                     va[i] = e + va[i];
                 }
             }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { va[i] *= unsc; vb[i] *= unsc; }
             u32x4 pk;
 #pragma unroll
             for (int i = 0; i < 4; ++i)

@@ -127,7 +127,7 @@ def test_fast_token_major_strides_and_pointer_table():
     _check_all_heads(wl, kk.cpu(), vv.cpu(), torch.cat(ks).cpu(), torch.cat(vs).cpu(), None, p, W, TOL_BF16)
 
 
-@pytest.mark.parametrize("flags", [0])
+@pytest.mark.parametrize("flags", [0, binding.FLAG_DENSE, binding.FLAG_SINGLE_FOLD])
 def test_large_and_tiny_values_keep_the_tolerance(flags):
     """Cache values far outside the fp16 range of the matrix-core operands: a K head whose outlier channels
     reach 6e4, a head of magnitude 1e-6, a head of magnitude 3e37 and an all-zero head.  Every head-tensor is
