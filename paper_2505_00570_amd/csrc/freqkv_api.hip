@@ -228,7 +228,8 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
     else if (!sh.high && !(L->flags & (FREQKV_FLAG_DENSE | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD)) &&
-             fast_supported(sh.n, sh.Lc, nullptr, nullptr))
+             fast_supported(sh.n, sh.Lc, nullptr, nullptr) &&
+             (long long)window * L->stride_token * 2 < (1LL << 32))       // its rows are addressed by 32-bit byte offsets
         sh.variant = kFast;
     else if (sh.n % 4 == 0 && sh.Lc % 2 == 0 && !(L->flags & FREQKV_FLAG_SINGLE_FOLD)) {
         // workgroups of the even-part launch over all slabs: column tiles x row tiles of 256 rows per parity

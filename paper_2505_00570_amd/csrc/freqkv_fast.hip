@@ -91,7 +91,7 @@ struct FastCfg {
     static_assert(Q <= 96 && 2 * QH <= 96 && QH <= 48, "q stage fits 96-wide tiles");
     static_assert(KP <= 64 && KP % 16 == 0, "p stage fits two 32-wide tiles");
     static_assert(UROWS % J2 == 0 && UROWS % 32 == 0 && (NG * J2) % UROWS == 0, "in-place units hold whole groups");
-    static_assert(LDS_HALFS * 2 <= 160 * 1024 - 64, "LDS");
+    static_assert(LDS_HALFS * 2 + 2 * NTP * KSP * kFragBytes <= 160 * 1024 - 256, "LDS");
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -112,13 +112,16 @@ __device__ __forceinline__ int rot2(int row) { return ((row >> 1) & 2) | ((row >
 __device__ __forceinline__ int rot12(int row) { return ((row >> 3) + 2 * ((row >> 2) & 1)) % 12; }
 __device__ __forceinline__ int wrap12(int c) { return c >= 12 ? c - 12 : c; }
 
+// Makes the compiler materialise a value at this point of the program (no instruction is emitted).
+__device__ __forceinline__ void pin(half8& v) { asm volatile("" : "+v"(v)); }
+
 // Row of the span that holds sample j of the even-first / odd-reversed ordering of an n-point sequence.
 __device__ __forceinline__ int makhoul_row(int j, int n) { return j < n / 2 ? 2 * j : 2 * (n - 1 - j) + 1; }
 
 // dump: diagnostic only.  When not null, workgroup 0 copies its LDS there after phase `stop` (1 load ...
 // 6 stage Q') and every workgroup returns without writing the cache.
-template <class Cfg, int NW>
-__global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables,
+template <class Cfg, int NW, bool DIAG>
+__global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables_arg,
                                                  float rest_scale, float* __restrict__ tap,
                                                  _Float16* __restrict__ dump, int stop)
 {
@@ -127,57 +130,88 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     constexpr int NT = NW * 64;                        // threads
     __shared__ __attribute__((aligned(1024))) _Float16 lds[Cfg::LDS_HALFS];
     __shared__ uint32_t red[NW];
+    // fragments of the two p-stage matrices, copied once per workgroup: register room for the prefetched rows
+    __shared__ __attribute__((aligned(16))) half8 ptab[2][Cfg::NTP * Cfg::KSP][64];
 
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int l32 = lane & 31, lhi = lane >> 5;
+    const int tid0 = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
 
-    // blockIdx -> task (8 consecutive virtual columns).  Workgroups are dealt round-robin to the 8 XCDs;
-    // the d/8 tasks of one head-tensor take consecutive slots of ONE XCD, so that the 16-byte pieces they
-    // read of the same 256-byte rows, and the pieces they write, meet in that XCD's L2.
-    int task;
-    {
+    // Virtual block index -> task (8 consecutive virtual columns).  Workgroups are dealt round-robin to the 8
+    // XCDs; the d/8 tasks of one head-tensor take consecutive slots of ONE XCD, so that the 16-byte pieces they
+    // read of the same 256-byte rows, and the pieces they write, meet in that XCD's L2.  The grid is persistent:
+    // a workgroup takes the virtual indices blockIdx.x, blockIdx.x + gridDim.x, ... (gridDim.x is a multiple
+    // of 8 whenever it is smaller than the number of tasks, so the XCD of a virtual index is the workgroup's).
+    const int ntasks = g.ncols / 8;
+    const long long rowb = g.stride_token * 2;
+    const uint32_t rowb32 = (uint32_t)rowb;            // the host checked that a head-tensor's span stays below 4 GiB
+    auto map_task = [&](int vb, char** base_out, int* ht_out, int* c0_out) {
         const int tph = g.d / 8;                       // tasks per head-tensor
         const int hts = g.ncols / g.d;
-        const int bid = blockIdx.x;
         const int full = hts / 8;                      // groups of 8 head-tensors
         const int per_group = 8 * tph;
-        if (bid < full * per_group) {
-            const int grp = bid / per_group, local = bid - grp * per_group;
+        int task = vb;
+        if (vb < full * per_group) {
+            const int grp = vb / per_group, local = vb - grp * per_group;
             const int xcd = local & 7, slot = local >> 3;
             task = (grp * 8 + xcd) * tph + slot;
-        } else {
-            task = bid;
         }
-    }
-    int ht;
-    char* base = column_base(tab, g, task * 8, 2, &ht);
-    const int c0 = task * 8 - ht * g.d;
-    const long long rowb = g.stride_token * 2;
-    base += (long long)g.S * rowb;
+        int ht;
+        char* b = column_base(tab, g, task * 8, 2, &ht);
+        *base_out = b + (long long)g.S * rowb;
+        *ht_out = ht;
+        *c0_out = task * 8 - ht * g.d;
+    };
 
     // diagnostic: stop == 8 runs everything and leaves the shader-clock reading after each phase in dump
-    const bool stamp = dump && stop == 8;
-    long long ts[10];
-    ts[0] = stamp ? (long long)clock64() : 0;
+    const bool stamp = DIAG && dump && stop == 8;
+    long long ts[DIAG ? 10 : 1];
+    auto take_stamp = [&](auto ic) {
+        if constexpr (DIAG) ts[decltype(ic)::value] = stamp ? (long long)clock64() : 0;
+    };
+    take_stamp(IC<0>{});
 
-    // ---- phase 1: load.  Lane handles positions pos = tid + NT i of the p x q grid; all 4 x NIT row pieces
-    // are requested before the first is used.
+    // Lane handles positions pos = tid + NT i of the p x q grid: the 4 x NIT row pieces of a task are requested
+    // in one go, for the first task here and for every later one in the middle of the task before it.
     constexpr int NIT = (Cfg::NPOS + NT - 1) / NT;
     u32x4 raw[NIT][4];
-    static_for<NIT>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        int pos = tid + NT * i;
-        if (pos >= Cfg::NPOS) pos = 0;
-        const int j2 = pos / Q, j3 = pos - j2 * Q;
-        const int jb = (j2 * (4 * Q) + j3 * (4 * P)) % n;
-        static_for<4>([&](auto jc) {
-            constexpr int j1 = decltype(jc)::value;
-            int j = jb + j1 * N;
-            if (j >= n) j -= n;
-            raw[i][j1] = *(const u32x4*)(base + (long long)makhoul_row(j, n) * rowb);
+    // part 0 / 1: the first / second half of the lane's positions (the prefetch is issued in two parts)
+    auto issue_loads = [&](const char* bp, int tid, auto part) {
+        constexpr int I0 = decltype(part)::value == 1 ? NIT / 2 : 0;
+        constexpr int I1 = decltype(part)::value == 0 ? NIT / 2 : NIT;
+        static_for<I1 - I0>([&](auto ic) {
+            constexpr int i = I0 + decltype(ic)::value;
+            int pos = tid + NT * i;
+            if (pos >= Cfg::NPOS) pos = 0;
+            const int j2 = pos / Q, j3 = pos - j2 * Q;
+            const int jb = (j2 * (4 * Q) + j3 * (4 * P)) % n;
+            static_for<4>([&](auto jc) {
+                constexpr int j1 = decltype(jc)::value;
+                int j = jb + j1 * N;
+                if (j >= n) j -= n;
+                raw[i][j1] = *(const u32x4*)(bp + (uint32_t)makhoul_row(j, n) * rowb32);
+            });
         });
-    });
+    };
+    int vbid = blockIdx.x;
+    char* base;
+    int ht, c0;
+    map_task(vbid, &base, &ht, &c0);
+    issue_loads(base, tid0, IC<0>{});
+    issue_loads(base, tid0, IC<1>{});
+    {
+        const half8* tp = (const half8*)(tables_arg + Cfg::OFF_P);   // the forward and the inverse table are adjacent
+        for (int i = tid0; i < 2 * Cfg::NTP * Cfg::KSP * 64; i += NT) (&ptab[0][0][0])[i] = tp[i];
+    }
+
+  for (;;) {                                           // one task per iteration
+    // Everything a lane derives from its index is recomputed in every iteration: kept alive across the whole
+    // loop instead, these per-lane constants would not fit the register file next to the prefetched rows.
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
+    // likewise the stage tables: read where they are used, in every iteration, not hoisted out of the loop
+    const char* tables = tables_arg;
+    asm volatile("" : "+s"(tables));
     // ---- clear LDS while the rows are on their way (pad positions must hold finite values: they meet zero matrix entries)
     {
         u32x4 z = {0u, 0u, 0u, 0u};
@@ -205,7 +239,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         if (lane == 0) red[wave] = amax;
     }
     __syncthreads();                                   // LDS cleared, red[] complete
-    ts[8] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<8>{});
     {
         uint32_t a = red[0];
         static_for<NW - 1>([&](auto w) { a = red[w.value + 1] > a ? red[w.value + 1] : a; });
@@ -251,9 +285,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         }
     });
     __syncthreads();
-    ts[1] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<1>{});
     auto dump_and_stop = [&](int phase) -> bool {
-        if (!dump || stop != phase) return false;
+        if (!DIAG || !dump || stop != phase) return false;
         if (blockIdx.x == 0)
             for (int i = tid; i < Cfg::LDS_HALFS; i += NT) dump[i] = lds[i];
         return true;
@@ -313,7 +347,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         });
     }
     __syncthreads();
-    ts[2] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<2>{});
     if (dump_and_stop(2)) return;
 
     // ---- phase 3: stage P.  Columns m' = (g, f3) x contraction (part, j2) -> (part', f2); the data are the
@@ -321,9 +355,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // 32 columns are in flight per wave.
     {
         half8 ap[Cfg::NTP][Cfg::KSP];
-        const half8* tp = (const half8*)(tables + Cfg::OFF_P) + lane;
         static_for<Cfg::NTP>([&](auto nt) {
-            static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = tp[(nt.value * Cfg::KSP + ks.value) * 64]; });
+            static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = ptab[0][nt.value * Cfg::KSP + ks.value][lane]; });
         });
         constexpr int TU = NW == 8 ? 3 : 4;
         for (int t0 = wave; t0 < QH; t0 += NW * TU) {  // 32 QH columns = QH tiles of 32
@@ -372,7 +405,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         }
     }
     __syncthreads();
-    ts[3] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<3>{});
     if (dump_and_stop(3)) return;
 
     // ---- phase 4: middle.  An item is two neighbouring k2 of one k3 (one dword per array and part) and four
@@ -419,19 +452,48 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         }
     }
     __syncthreads();
-    ts[4] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<4>{});
     if (dump_and_stop(4)) return;
+
+    // Tables of the two remaining matrix stages first, then the rows of this workgroup's next task: they arrive
+    // while stages P', Q' and the store run (loads return in order, so nothing issued later may be waited for
+    // before them: the store stage needs no loads at all).
+    half8 bqi[3][6];
+    {
+        const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { bqi[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
+        });
+        // pin the order: these loads are issued here, ahead of the prefetch (the scheduler would otherwise sink
+        // them towards their first use, behind it)
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
+        });
+    }
+    const int next_vbid = vbid + (int)gridDim.x;
+    const bool has_next = !DIAG && next_vbid < ntasks;
+    char* next_base = base;
+    int next_ht = ht, next_c0 = c0;
+    if (has_next) {
+        map_task(next_vbid, &next_base, &next_ht, &next_c0);
+        issue_loads(next_base, tid, IC<0>{});          // the other half follows when stage Q' has released its table
+    } else {
+        // no next task: give the row registers a fresh value all the same, or the rows just consumed would count
+        // as alive from the load stage up to here and crowd the register file of stages Q and P
+        static_for<NIT>([&](auto ic) {
+            static_for<4>([&](auto jc) { raw[ic.value][jc.value] = u32x4{0u, 0u, 0u, 0u}; });
+        });
+    }
 
     // ---- phase 5: stage P'.  Rows m' = (g', k3 padded to 48), g' = (k1, ch) < 16, x contraction (part, k2)
     // -> (part', m2); results go to the other half of LDS as E[(k1, m2, ch)][part' 48 + k3].
     constexpr int Y0 = 16 * GH;
     {
         half8 bp[Cfg::NTP][Cfg::KSP];
-        const half8* tp = (const half8*)(tables + Cfg::OFF_PI) + lane;
         static_for<Cfg::NTP>([&](auto ct) {
-            static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = tp[(ct.value * Cfg::KSP + ks.value) * 64]; });
+            static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = ptab[1][ct.value * Cfg::KSP + ks.value][lane]; });
         });
-        constexpr int TU = 3;                          // 16 x 48 rows = 24 tiles
+        constexpr int TU = NW == 8 ? 1 : 3;            // 16 x 48 rows = 24 tiles; the prefetched rows hold registers now
         for (int t0 = wave; t0 < 24; t0 += NW * TU) {
             half8 a[TU][Cfg::KSP];
             static_for<TU>([&](auto tu) {
@@ -480,19 +542,14 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         }
     }
     __syncthreads();
-    ts[5] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<5>{});
     if (dump_and_stop(5)) return;
 
     // ---- phase 6: stage Q'.  Rows (k1, m2, ch) x contraction (Re | Im of k3, 96) -> m3; 4 consecutive rows of a
     // lane are 4 channels: u[(k1, m2)][m3][ch] into the first half of LDS.
     {
-        half8 bq[3][6];
-        const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
-        static_for<3>([&](auto ct) {
-            static_for<6>([&](auto ks) { bq[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
-        });
         constexpr int NT6 = 16 * J2 / 32;
-        constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
+        constexpr int TU = NW == 8 ? 1 : (NT6 + NW - 1) / NW;   // tiles of a wave in flight together; the prefetched rows hold registers now
         static_assert(TU <= 3, "tiles of a wave fit the register file");
         for (int t0 = wave; t0 < NT6; t0 += NW * TU) {
             f32x16 acc[TU][3];
@@ -513,7 +570,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     const half8 a = *(const half8*)(src[tu.value] + wrap12(wrap12(ks.value * 2 + rot[tu.value])) * 8);
                     static_for<3>([&](auto ct) {
                         acc[tu.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            a, bq[ct.value][ks.value], acc[tu.value][ct.value], 0, 0, 0);
+                            a, bqi[ct.value][ks.value], acc[tu.value][ct.value], 0, 0, 0);
                     });
                 });
             });
@@ -534,11 +591,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         }
     }
     __syncthreads();
-    ts[6] = stamp ? (long long)clock64() : 0;
+    take_stamp(IC<6>{});
     if (dump_and_stop(6)) return;
-    if (dump && !stamp) return;
+    if (DIAG && dump && !stamp) return;
 
     // ---- phase 7: store
+    if (has_next) issue_loads(next_base, tid, IC<1>{});
     {
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
@@ -565,8 +623,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 pa[c] = pack_bf16x2(va[2 * c], va[2 * c + 1]);
                 pb[c] = pack_bf16x2(vb[2 * c], vb[2 * c + 1]);
             }
-            *(u32x4*)(base + (long long)ra * rowb) = pa;
-            *(u32x4*)(base + (long long)rb * rowb) = pb;
+            *(u32x4*)(base + (uint32_t)ra * rowb32) = pa;
+            *(u32x4*)(base + (uint32_t)rb * rowb32) = pb;
             if (tp) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
@@ -576,7 +634,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             }
         }
     }
-    if (stamp) {
+    if constexpr (DIAG) if (stamp) {
         __syncthreads();
         ts[7] = (long long)clock64();
         if (tid == 0) {
@@ -584,6 +642,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             for (int i = 0; i < 9; ++i) o[i] = ts[i];
         }
     }
+    if (!has_next) break;
+    vbid = next_vbid; base = next_base; ht = next_ht; c0 = next_c0;
+    __syncthreads();                                   // every wave is done with this task's LDS image
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -706,10 +768,26 @@ template <class Cfg>
 hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
                       _Float16* dump, int stop, hipStream_t st)
 {
-    const unsigned tasks = (unsigned)(g.ncols / 8);
     constexpr int NW = 8;          // two waves per SIMD: one wave's LDS traffic and conversions overlap the other's matrix work
-    hipLaunchKernelGGL((k_fast<Cfg, NW>), dim3(tasks), dim3(NW * 64), 0, st, tab, g, (const char*)tables, rest_scale, tap,
-                       dump, stop);
+    const unsigned tasks = (unsigned)(g.ncols / 8);
+    // Persistent grid: as many workgroups as the device holds at once (LDS decides), a multiple of 8 so that a
+    // workgroup's tasks stay on its XCD.  The diagnostic modes run one task per workgroup.
+    unsigned grid = tasks;
+    if (!dump) {
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        const unsigned per_cu = (unsigned)(160 * 1024 / (Cfg::LDS_HALFS * 2 + 64));
+        const unsigned resident = (unsigned)cus * (per_cu < 1 ? 1 : per_cu) / 8 * 8;
+        if (resident >= 8 && tasks > resident) grid = resident;
+    }
+    if (dump)
+        hipLaunchKernelGGL((k_fast<Cfg, NW, true>), dim3(grid), dim3(NW * 64), 0, st, tab, g, (const char*)tables,
+                           rest_scale, tap, dump, stop);
+    else
+        hipLaunchKernelGGL((k_fast<Cfg, NW, false>), dim3(grid), dim3(NW * 64), 0, st, tab, g, (const char*)tables,
+                           rest_scale, tap, dump, stop);
     return hipGetLastError();
 }
 
