@@ -776,9 +776,9 @@ freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t*
     Shape sh;
     freqkv_status_t rc = check_shape(layout, n_heads, head_dim, window, window, n_sink, 0.5, &sh);
     if (rc < 0) return rc;
-    if (!k || !v || !dump || stop < 1 || stop > 8 || stop == 7) return FREQKV_E_INVALID;
+    if (!k || !v || !dump || stop < 1 || stop > 9 || stop == 7) return FREQKV_E_INVALID;
     if (sh.variant != kFast) return FREQKV_E_UNSUPPORTED;
-    const size_t need = stop == 8 ? (size_t)sh.hts_per_slab * sh.d / 8 * 72 : fast_lds_halfs(sh.n) * 2;
+    const size_t need = stop >= 8 ? (size_t)sh.hts_per_slab * sh.d / 8 * 72 : fast_lds_halfs(sh.n) * 2;
     if (dump_bytes < need) return FREQKV_E_WORKSPACE;
     std::vector<char*> bases;
     rc = resolve_bases(k, v, *layout, sh, 0, &bases);

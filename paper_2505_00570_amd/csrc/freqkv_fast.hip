@@ -112,6 +112,13 @@ __device__ __forceinline__ int rot2(int row) { return ((row >> 1) & 2) | ((row >
 __device__ __forceinline__ int rot12(int row) { return ((row >> 3) + 2 * ((row >> 2) & 1)) % 12; }
 __device__ __forceinline__ int wrap12(int c) { return c >= 12 ? c - 12 : c; }
 
+// Four accumulator values -> four fp16, round to nearest even, two packed conversions.
+__device__ __forceinline__ half4 cvt4(float a, float b, float c, float d)
+{
+    f32x4 v = {a, b, c, d};
+    return __builtin_convertvector(v, half4);
+}
+
 // Makes the compiler materialise a value at this point of the program (no instruction is emitted).
 __device__ __forceinline__ void pin(half8& v) { asm volatile("" : "+v"(v)); }
 
@@ -163,7 +170,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     };
 
     // diagnostic: stop == 8 runs everything and leaves the shader-clock reading after each phase in dump
-    const bool stamp = DIAG && dump && stop == 8;
+    const bool stamp = DIAG && dump && stop >= 8;       // 9: as 8, but with the persistent grid of a real call
     long long ts[DIAG ? 10 : 1];
     auto take_stamp = [&](auto ic) {
         if constexpr (DIAG) ts[decltype(ic)::value] = stamp ? (long long)clock64() : 0;
@@ -174,30 +181,30 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // in one go, for the first task here and for every later one in the middle of the task before it.
     constexpr int NIT = (Cfg::NPOS + NT - 1) / NT;
     u32x4 raw[NIT][4];
-    // part 0 / 1: the first / second half of the lane's positions (the prefetch is issued in two parts)
-    auto issue_loads = [&](const char* bp, int tid, auto part) {
-        constexpr int I0 = decltype(part)::value == 1 ? NIT / 2 : 0;
-        constexpr int I1 = decltype(part)::value == 0 ? NIT / 2 : NIT;
-        static_for<I1 - I0>([&](auto ic) {
-            constexpr int i = I0 + decltype(ic)::value;
+    // Requests pieces [F0, F1) of the lane's 4 NIT row pieces (piece f = 4 i + j1) of the task at bp into dst.
+    auto issue_loads = [&](const char* bp, int tid, u32x4 (&dst)[NIT][4], auto f0, auto f1) {
+        constexpr int F0 = decltype(f0)::value, F1 = decltype(f1)::value < 4 * NIT ? decltype(f1)::value : 4 * NIT;
+        static_for<(F1 > F0 ? F1 - F0 : 0)>([&](auto fc) {
+            constexpr int f = F0 + decltype(fc)::value;
+            constexpr int i = f / 4, j1 = f % 4;
             int pos = tid + NT * i;
             if (pos >= Cfg::NPOS) pos = 0;
             const int j2 = pos / Q, j3 = pos - j2 * Q;
-            const int jb = (j2 * (4 * Q) + j3 * (4 * P)) % n;
-            static_for<4>([&](auto jc) {
-                constexpr int j1 = decltype(jc)::value;
-                int j = jb + j1 * N;
-                if (j >= n) j -= n;
-                raw[i][j1] = *(const u32x4*)(bp + (uint32_t)makhoul_row(j, n) * rowb32);
-            });
+            int j = (j2 * (4 * Q) + j3 * (4 * P)) % n + j1 * N;
+            if (j >= n) j -= n;
+            dst[i][j1] = *(const u32x4*)(bp + (uint32_t)makhoul_row(j, n) * rowb32);
         });
     };
+    // The prefetch of the next task is spread over four of the stages that follow stage Q: PF pieces at the start
+    // of each, behind that stage's own table loads (loads return in order: a table load must not queue behind
+    // freshly requested rows).  A burst of all pieces at one point blocks every wave at it until the
+    // memory pipeline has taken them; small portions are taken at once and arrive while the stage computes.
+    constexpr int PF = (4 * NIT + 3) / 4;              // four portions: stages P, P', Q' and the store
     int vbid = blockIdx.x;
     char* base;
     int ht, c0;
     map_task(vbid, &base, &ht, &c0);
-    issue_loads(base, tid0, IC<0>{});
-    issue_loads(base, tid0, IC<1>{});
+    issue_loads(base, tid0, raw, IC<0>{}, IC<4 * NIT>{});
     {
         const half8* tp = (const half8*)(tables_arg + Cfg::OFF_P);   // the forward and the inverse table are adjacent
         for (int i = tid0; i < 2 * Cfg::NTP * Cfg::KSP * 64; i += NT) (&ptab[0][0][0])[i] = tp[i];
@@ -206,12 +213,22 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
   for (;;) {                                           // one task per iteration
     // Everything a lane derives from its index is recomputed in every iteration: kept alive across the whole
     // loop instead, these per-lane constants would not fit the register file next to the prefetched rows.
+    if constexpr (DIAG) if (vbid != (int)blockIdx.x) take_stamp(IC<0>{});
     int tid = tid0;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     // likewise the stage tables: read where they are used, in every iteration, not hoisted out of the loop
     const char* tables = tables_arg;
     asm volatile("" : "+s"(tables));
+    const int next_vbid = vbid + (int)gridDim.x;
+    const bool has_next = (!DIAG || stop == 9) && next_vbid < ntasks;
+    char* next_base = base;
+    int next_ht = ht, next_c0 = c0;
+    if (has_next) map_task(next_vbid, &next_base, &next_ht, &next_c0);
+    u32x4 nraw[NIT][4];                                // rows of the next task, requested piecewise below
+    static_for<NIT>([&](auto ic) {
+        static_for<4>([&](auto jc) { nraw[ic.value][jc.value] = u32x4{0u, 0u, 0u, 0u}; });
+    });
     // ---- clear LDS while the rows are on their way (pad positions must hold finite values: they meet zero matrix entries)
     {
         u32x4 z = {0u, 0u, 0u, 0u};
@@ -336,10 +353,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     const int grp = row / J2, j2 = row - grp * J2;
                     static_for<3>([&](auto ct) {
                         const int f = ct.value * 32 + l32;
-                        half4 o;
-                        static_for<4>([&](auto k) {
-                            o[k.value] = (_Float16)acc[uu.value][rt.value][ct.value][4 * r4.value + k.value];
-                        });
+                        const half4 o = cvt4(acc[uu.value][rt.value][ct.value][4 * r4.value], acc[uu.value][rt.value][ct.value][4 * r4.value + 1], acc[uu.value][rt.value][ct.value][4 * r4.value + 2], acc[uu.value][rt.value][ct.value][4 * r4.value + 3]);
                         *(half4*)(lds + grp * GH + f * J2 + j2) = o;
                     });
                 });
@@ -358,6 +372,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         static_for<Cfg::NTP>([&](auto nt) {
             static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = ptab[0][nt.value * Cfg::KSP + ks.value][lane]; });
         });
+        if (has_next) issue_loads(next_base, tid, nraw, IC<0>{}, IC<PF>{});
         constexpr int TU = NW == 8 ? 3 : 4;
         for (int t0 = wave; t0 < QH; t0 += NW * TU) {  // 32 QH columns = QH tiles of 32
             _Float16* col[TU];
@@ -394,8 +409,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                             const int n0 = nt.value * 32 + 8 * r4.value + 4 * lhi;
                             if (n0 < Cfg::KP) {
                                 const int part = n0 / J2, f2 = n0 - part * J2;
-                                half4 o;
-                                static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][nt.value][4 * r4.value + k.value]; });
+                                const half4 o = cvt4(acc[tu.value][nt.value][4 * r4.value], acc[tu.value][nt.value][4 * r4.value + 1], acc[tu.value][nt.value][4 * r4.value + 2], acc[tu.value][nt.value][4 * r4.value + 3]);
                                 *(half4*)(col[tu.value] + part * QH * J2 + f2) = o;
                             }
                         });
@@ -455,36 +469,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     take_stamp(IC<4>{});
     if (dump_and_stop(4)) return;
 
-    // Tables of the two remaining matrix stages first, then the rows of this workgroup's next task: they arrive
-    // while stages P', Q' and the store run (loads return in order, so nothing issued later may be waited for
-    // before them: the store stage needs no loads at all).
-    half8 bqi[3][6];
-    {
-        const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
-        static_for<3>([&](auto ct) {
-            static_for<6>([&](auto ks) { bqi[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
-        });
-        // pin the order: these loads are issued here, ahead of the prefetch (the scheduler would otherwise sink
-        // them towards their first use, behind it)
-        static_for<3>([&](auto ct) {
-            static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
-        });
-    }
-    const int next_vbid = vbid + (int)gridDim.x;
-    const bool has_next = !DIAG && next_vbid < ntasks;
-    char* next_base = base;
-    int next_ht = ht, next_c0 = c0;
-    if (has_next) {
-        map_task(next_vbid, &next_base, &next_ht, &next_c0);
-        issue_loads(next_base, tid, IC<0>{});          // the other half follows when stage Q' has released its table
-    } else {
-        // no next task: give the row registers a fresh value all the same, or the rows just consumed would count
-        // as alive from the load stage up to here and crowd the register file of stages Q and P
-        static_for<NIT>([&](auto ic) {
-            static_for<4>([&](auto jc) { raw[ic.value][jc.value] = u32x4{0u, 0u, 0u, 0u}; });
-        });
-    }
-
     // ---- phase 5: stage P'.  Rows m' = (g', k3 padded to 48), g' = (k1, ch) < 16, x contraction (part, k2)
     // -> (part', m2); results go to the other half of LDS as E[(k1, m2, ch)][part' 48 + k3].
     constexpr int Y0 = 16 * GH;
@@ -493,7 +477,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         static_for<Cfg::NTP>([&](auto ct) {
             static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = ptab[1][ct.value * Cfg::KSP + ks.value][lane]; });
         });
-        constexpr int TU = NW == 8 ? 1 : 3;            // 16 x 48 rows = 24 tiles; the prefetched rows hold registers now
+        if (has_next) issue_loads(next_base, tid, nraw, IC<PF>{}, IC<2 * PF>{});
+        constexpr int TU = 3;                          // 16 x 48 rows = 24 tiles
         for (int t0 = wave; t0 < 24; t0 += NW * TU) {
             half8 a[TU][Cfg::KSP];
             static_for<TU>([&](auto tu) {
@@ -521,20 +506,24 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 });
             });
             static_for<TU>([&](auto tu) {
-                const int t = t0 + NW * tu.value;
+                const int t = t0 + NW * tu.value;              // wave-uniform
                 static_for<Cfg::NTP>([&](auto ct) {
                     const int nn = ct.value * 32 + l32;
                     if (nn < Cfg::KP) {
                         const int part = nn / J2, m2 = nn - part * J2;
+                        const int m2r = m2 % 12;
                         static_for<4>([&](auto r4) {
-                            const int m0 = t * 32 + 8 * r4.value + 4 * lhi;       // first of 4 rows, same g'
-                            const int g2 = m0 / 48, k30 = m0 - g2 * 48;
+                            // rows m0 .. m0+3 with m0 = 32 t + 8 r4 + 4 lhi: everything but the last term is the
+                            // same for the whole wave, and 48 is a multiple of 8, so g' and the chunk of k3 are too
+                            const int mu = t * 32 + 8 * r4.value;
+                            const int g2 = mu / 48, k3u = mu - g2 * 48;         // wave-uniform
                             const int k1 = g2 >> 3, ch = g2 & 7;
-                            const int row = (k1 * J2 + m2) * 8 + ch;
-                            const int c = part * 6 + (k30 >> 3);
-                            half4 o;
-                            static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][ct.value][4 * r4.value + k.value]; });
-                            *(half4*)(lds + Y0 + row * 96 + wrap12(c + rot12(row)) * 8 + (k30 & 7)) = o;
+                            const int rotu = (k1 * J2 + 2 * (ch >> 2)) % 12;     // wave-uniform part of rot12(row)
+                            const int rowu = (k1 * J2 * 8 + ch) * 96 + (k3u & 7);
+                            const int chunk = wrap12(wrap12(m2r + rotu) + part * 6 + (k3u >> 3));
+                            const half4 o = cvt4(acc[tu.value][ct.value][4 * r4.value], acc[tu.value][ct.value][4 * r4.value + 1],
+                                                 acc[tu.value][ct.value][4 * r4.value + 2], acc[tu.value][ct.value][4 * r4.value + 3]);
+                            *(half4*)(lds + Y0 + rowu + m2 * (8 * 96) + chunk * 8 + 4 * lhi) = o;
                         });
                     }
                 });
@@ -548,8 +537,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // ---- phase 6: stage Q'.  Rows (k1, m2, ch) x contraction (Re | Im of k3, 96) -> m3; 4 consecutive rows of a
     // lane are 4 channels: u[(k1, m2)][m3][ch] into the first half of LDS.
     {
+        half8 bqi[3][6];
+        const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { bqi[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
+        });
+        // pin the order: the table is requested here, ahead of the rows (the scheduler would otherwise sink its
+        // loads towards their first use, behind them)
+        static_for<3>([&](auto ct) {
+            static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
+        });
+        if (has_next) issue_loads(next_base, tid, nraw, IC<2 * PF>{}, IC<3 * PF>{});
         constexpr int NT6 = 16 * J2 / 32;
-        constexpr int TU = NW == 8 ? 1 : (NT6 + NW - 1) / NW;   // tiles of a wave in flight together; the prefetched rows hold registers now
+        constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
         static_assert(TU <= 3, "tiles of a wave fit the register file");
         for (int t0 = wave; t0 < NT6; t0 += NW * TU) {
             f32x16 acc[TU][3];
@@ -581,8 +581,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     if (m3 < Q && t < NT6) {
                         static_for<4>([&](auto r4) {
                             const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) 8 + ch, ch = 0 or 4
-                            half4 o;
-                            static_for<4>([&](auto k) { o[k.value] = (_Float16)acc[tu.value][ct.value][4 * r4.value + k.value]; });
+                            const half4 o = cvt4(acc[tu.value][ct.value][4 * r4.value], acc[tu.value][ct.value][4 * r4.value + 1], acc[tu.value][ct.value][4 * r4.value + 2], acc[tu.value][ct.value][4 * r4.value + 3]);
                             *(half4*)(lds + ((v0 >> 3) * 96 + m3) * 8 + (v0 & 7)) = o;
                         });
                     }
@@ -596,7 +595,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     if (DIAG && dump && !stamp) return;
 
     // ---- phase 7: store
-    if (has_next) issue_loads(next_base, tid, IC<1>{});
+    if (has_next) issue_loads(next_base, tid, nraw, IC<3 * PF>{}, IC<4 * PF>{});
     {
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
@@ -638,12 +637,15 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         __syncthreads();
         ts[7] = (long long)clock64();
         if (tid == 0) {
-            long long* o = (long long*)dump + (long long)blockIdx.x * 9;
+            long long* o = (long long*)dump + (long long)vbid * 9;
             for (int i = 0; i < 9; ++i) o[i] = ts[i];
         }
     }
     if (!has_next) break;
     vbid = next_vbid; base = next_base; ht = next_ht; c0 = next_c0;
+    static_for<NIT>([&](auto ic) {
+        static_for<4>([&](auto jc) { raw[ic.value][jc.value] = nraw[ic.value][jc.value]; });
+    });
     __syncthreads();                                   // every wave is done with this task's LDS image
   }
 }
@@ -773,7 +775,7 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
     // Persistent grid: as many workgroups as the device holds at once (LDS decides), a multiple of 8 so that a
     // workgroup's tasks stay on its XCD.  The diagnostic modes run one task per workgroup.
     unsigned grid = tasks;
-    if (!dump) {
+    if (!dump || stop == 9) {
         int dev = 0, cus = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
