@@ -263,16 +263,20 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         amax = a;
     }
     // 2^e brings the largest magnitude into [256, 512): the transforms amplify a constant sequence by at most
-    // 2 sqrt(pq) < 128, so every intermediate stays below the fp16 limit, and 2^-e undoes it exactly at the end
+    // sqrt(pq) / 2 < 64 after the butterfly's 1/2, so every intermediate stays below the fp16 limit, and 2^-e undoes
+    // the scale exactly at the end
     int e = 0;
+    const bool nonfinite = (amax >> 7) == 255;         // an inf or nan somewhere in the slice: its 8 channels come out nan
     {
         const int E = (int)(amax >> 7);                // exponent field of the largest magnitude
         if (E > 0 && E < 255) e = 135 - E;
         if (e > 120) e = 120;
     }
-    const float sc = 0.5f * __uint_as_float((uint32_t)(e + 127) << 23);
     const float unsc = rest_scale * __uint_as_float((uint32_t)(127 - e) << 23);
 
+    // (A packed fp16 butterfly on integer-converted operands was measured: no faster, this stage waits for its
+    // 2-byte LDS writes, and one more rounding in the error budget.)
+    const float sc = 0.5f * __uint_as_float((uint32_t)(e + 127) << 23);
     static_for<NIT>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
         const int pos = tid + NT * i;
@@ -615,6 +619,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 const float a = (float)g0[c], b = (float)g1[c];
                 va[c] = (a + b) * unsc;
                 vb[c] = (a - b) * unsc;
+            }
+            if (nonfinite) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) va[c] = vb[c] = __builtin_nanf("");
             }
             u32x4 pa, pb;
 #pragma unroll

@@ -205,22 +205,26 @@ hipError_t launch_basis_f32(float* Mf, int n, int Lc, int rescale, int band, hip
 // the order the contraction's LDS fragments are read.
 // ------------------------------------------------------------------------------------------
 
-// Largest magnitude of the span of every head-tensor (range guard of the fp16 operands): a thread scans
-// rows j = blockIdx.y*4 + wave, +4*gridDim.y, ... of two adjacent channels; bf16 bit patterns without their
-// sign compare like the magnitudes.  hmax must be zero before the launch.
+// Largest magnitude of the span of every head-tensor (range guard of the fp16 operands).  A lane reads 16 bytes
+// (8 channels) of a row, 16 lanes a 256-byte stretch of it, so a wave scans 4 rows of a 128-column tile per step;
+// bf16 bit patterns without their sign compare like the magnitudes.  hmax must be zero before the launch.
 __global__ __launch_bounds__(256) void k_absmax_bf16(SlabTable tab, Geom g, uint32_t* __restrict__ hmax)
 {
     typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
     const int ct = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int vcol = ct * kColTile + lane * 2;
+    const int vcol = ct * kColTile + (lane & 15) * 8;
     if (vcol >= g.ncols) return;
     int ht;
     const char* base = column_base(tab, g, vcol, 2, &ht);
     const long long rowb = g.stride_token * 2;
     u16x2 m = {0, 0};
-    for (int j = blockIdx.y * 4 + wave; j < g.n0; j += 4 * gridDim.y) {
-        const uint32_t w = *(const uint32_t*)(base + (long long)(g.S + j) * rowb) & 0x7fff7fffu;
-        m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, w));
+    for (int j = (blockIdx.y * 4 + wave) * 4 + (lane >> 4); j < g.n0; j += 16 * gridDim.y) {
+        const u32x4 w = *(const u32x4*)(base + (long long)(g.S + j) * rowb);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t wi = w[i] & 0x7fff7fffu;
+            m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, wi));
+        }
     }
     uint32_t a = m[0] > m[1] ? m[0] : m[1];
     if (g.d % kColTile == 0) {
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(256) void k_absmax_bf16(SlabTable tab, Geom g, uint
 hipError_t launch_absmax_bf16(const SlabTable& tab, const Geom& g, uint32_t* hmax, hipStream_t st)
 {
     // g.n0: rows of the span (set by the caller for every variant)
-    dim3 grid(g.ncoltiles, 32);
+    dim3 grid(g.ncoltiles, 16);
     hipLaunchKernelGGL(k_absmax_bf16, grid, dim3(256), 0, st, tab, g, hmax);
     return hipGetLastError();
 }
