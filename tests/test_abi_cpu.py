@@ -318,3 +318,27 @@ def test_prefill_plan():
     assert call(33, 8, 128, 8192, 100) == -1
     L.dtype = fk.F32
     assert call(32, 8, 128, 8192, 100) == -2          # bf16 only
+
+
+def test_build_rejects_packed_fp32_in_device_code(tmp_path):
+    """The build keeps the device assembly of every file and fails on packed fp32 arithmetic.  Here: a probe
+    that the compiler turns into v_pk_fma_f32 without the feature flag and into scalar code with it (the host
+    pass of hipcc does not know the flag and says so: harmless, the device pass is what counts)."""
+    from paper_2505_00570_amd import build as hb
+    src = tmp_path / "probe.hip"
+    src.write_text("#include <hip/hip_runtime.h>\n"
+                   "__global__ void k(float2* a, const float2* b) { int i = threadIdx.x; float2 x = a[i], y = b[i];\n"
+                   "  x.x = x.x * y.x + 1.f; x.y = x.y * y.y + 1.f; a[i] = x; }\n")
+    flag = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    counts = []
+    for extra in ([], flag):
+        out = tmp_path / ("with.s" if extra else "without.s")
+        subprocess.check_call([hb.HIPCC, "--offload-arch=gfx950", "-O3", "--cuda-device-only", "-S"] + extra +
+                              [str(src), "-o", str(out)], stderr=subprocess.DEVNULL)
+        counts.append(hb.check_device_asm(str(out))[0])
+    assert counts[0] >= 1 and counts[1] == 0
+    # the library's own device code, as built: no packed fp32, no foreign use of M0
+    for name in hb.SOURCES:
+        asm = os.path.join(hb.OBJ_DIR, name.replace(".hip", "-hip-amdgcn-amd-amdhsa-gfx950.s"))
+        if os.path.exists(asm):
+            assert hb.check_device_asm(asm) == (0, 0), name
