@@ -67,7 +67,7 @@ typedef enum {
 
 #define FREQKV_FLAG_DENSE 0x20u      /* never use the factored transform (variant 6); the matrix forms (variants 1, 2, 5)
                                          run instead (SINGLE_FOLD and TWO_LEVEL_FOLD imply it).  Default: spans n = 4pq with a compiled factorization (8188 = 4*23*89,
-                                         4092 = 4*11*93, and 1260, 140 for tests) at retain_ratio 0.5 on bf16 caches take the
+                                         4092 = 4*11*93, 2044 = 4*7*73, 1020 = 4*3*85, and 1260, 140 for tests) at retain_ratio 0.5 on bf16 caches take the
                                          factored form, which needs no workspace */
 
 /*

@@ -801,70 +801,51 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
     return hipGetLastError();
 }
 
-// the factorizations with compiled kernels: the paper's two windows and two small ones for tests
-typedef FastCfg<23, 89> Cfg8188;
-typedef FastCfg<11, 93> Cfg4092;
-typedef FastCfg<7, 45> Cfg1260;
-typedef FastCfg<5, 7> Cfg140;
+// The factorizations with compiled kernels, n = 4 p q with window = n + 4 sinks: the paper's two windows (8192,
+// 4096), two shorter ones (2048, 1024) and two small spans for tests (1260, 140).
+#define FREQKV_FAST_CFGS(X) X(23, 89) X(11, 93) X(7, 73) X(3, 85) X(7, 45) X(5, 7)
 
 }  // namespace
 
 bool fast_supported(int n, int Lc, int* p, int* q)
 {
-    int pp = 0, qq = 0;
-    if (n == Cfg8188::n) { pp = 23; qq = 89; }
-    else if (n == Cfg4092::n) { pp = 11; qq = 93; }
-    else if (n == Cfg1260::n) { pp = 7; qq = 45; }
-    else if (n == Cfg140::n) { pp = 5; qq = 7; }
-    else return false;
     if (Lc * 2 != n) return false;
-    if (p) *p = pp;
-    if (q) *q = qq;
-    return true;
+#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) { if (p) *p = P_; if (q) *q = Q_; return true; }
+    FREQKV_FAST_CFGS(X)
+#undef X
+    return false;
 }
 
 size_t fast_table_bytes(int n)
 {
-    switch (n) {
-        case Cfg8188::n: return Cfg8188::TABLE_BYTES;
-        case Cfg4092::n: return Cfg4092::TABLE_BYTES;
-        case Cfg1260::n: return Cfg1260::TABLE_BYTES;
-        case Cfg140::n: return Cfg140::TABLE_BYTES;
-    }
+#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) return FastCfg<P_, Q_>::TABLE_BYTES;
+    FREQKV_FAST_CFGS(X)
+#undef X
     return 0;
 }
 
 size_t fast_lds_halfs(int n)
 {
-    switch (n) {
-        case Cfg8188::n: return Cfg8188::LDS_HALFS;
-        case Cfg4092::n: return Cfg4092::LDS_HALFS;
-        case Cfg1260::n: return Cfg1260::LDS_HALFS;
-        case Cfg140::n: return Cfg140::LDS_HALFS;
-    }
+#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) return FastCfg<P_, Q_>::LDS_HALFS;
+    FREQKV_FAST_CFGS(X)
+#undef X
     return 0;
 }
 
 void fast_build_tables_host(int n, char* out)
 {
-    switch (n) {
-        case Cfg8188::n: build_tables<Cfg8188>(out); break;
-        case Cfg4092::n: build_tables<Cfg4092>(out); break;
-        case Cfg1260::n: build_tables<Cfg1260>(out); break;
-        case Cfg140::n: build_tables<Cfg140>(out); break;
-    }
+#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) { build_tables<FastCfg<P_, Q_>>(out); return; }
+    FREQKV_FAST_CFGS(X)
+#undef X
 }
 
 hipError_t launch_fast(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
                        _Float16* dump, int stop, hipStream_t st)
 {
     if (g.ncols % 8 || g.d % 8) return hipErrorInvalidValue;
-    switch (g.n) {
-        case Cfg8188::n: return launch_cfg<Cfg8188>(tab, g, tables, rest_scale, tap, dump, stop, st);
-        case Cfg4092::n: return launch_cfg<Cfg4092>(tab, g, tables, rest_scale, tap, dump, stop, st);
-        case Cfg1260::n: return launch_cfg<Cfg1260>(tab, g, tables, rest_scale, tap, dump, stop, st);
-        case Cfg140::n: return launch_cfg<Cfg140>(tab, g, tables, rest_scale, tap, dump, stop, st);
-    }
+#define X(P_, Q_) if (g.n == FastCfg<P_, Q_>::n) return launch_cfg<FastCfg<P_, Q_>>(tab, g, tables, rest_scale, tap, dump, stop, st);
+    FREQKV_FAST_CFGS(X)
+#undef X
     return hipErrorInvalidValue;
 }
 

@@ -118,7 +118,7 @@ def test_plan_agrees_with_oracle_rules(window, sink, ratio, cur):
     assert p.new_len == orc.new_len(cur, window, sink, ratio)
     if ratio == 1.0:
         assert p.variant == 0 and p.workspace_bytes == 0
-    elif window - sink in (8188, 4092, 1260, 140) and p.retained_len * 2 == window - sink:
+    elif window - sink in (8188, 4092, 2044, 1020, 1260, 140) and p.retained_len * 2 == window - sink:
         assert p.variant == 6 and p.workspace_bytes == 0
     elif (window - sink) % 4 == 0 and p.retained_len % 2 == 0 and window - sink >= 2048:
         assert p.variant == 5                     # 32 layers x 8 heads: enough head-tensors for the two-level fold

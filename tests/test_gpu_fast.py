@@ -33,6 +33,8 @@ FAST_SMALL = [
     (1, 1, 9, 128, 140, 0),      # no sinks; 9 head-tensors per slab: the XCD-aware block map has a remainder
     (1, 1, 2, 128, 1264, 4),     # n = 1260
     (1, 2, 5, 96, 1262, 2),      # head_dim 96, 2 sinks
+    (1, 2, 2, 128, 1024, 4),     # n = 1020 = 4*3*85
+    (2, 1, 3, 128, 2048, 4),     # n = 2044 = 4*7*73
     (1, 1, 2, 128, 4096, 4),     # n = 4092
     (1, 1, 2, 128, 8192, 4),     # n = 8188
     (1, 1, 1, 256, 8196, 8),     # 8 sinks, head_dim 256
