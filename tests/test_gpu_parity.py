@@ -320,31 +320,33 @@ def test_iterative_schedule_small():
 # launch plan: more (layer, K|V) slabs than one pointer table holds; caller's stream; helpers
 # ------------------------------------------------------------------------------------------
 
-def test_many_layers_split_into_passes():
-    """100 layers = 200 slabs > 192 per launch group: the call makes two passes."""
-    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=100, n_heads=1, head_dim=64, window=132)
-    _say("100 layers x 1 head x 64, window 132")
-    k, v = _mk(wl, seed=8, capacity=140)
+@pytest.mark.parametrize("window,variant", [(132, 1), (144, 6)])
+def test_many_layers_split_into_passes(window, variant):
+    """100 layers = 200 slabs > 192 per launch group: the call makes two passes (matrix form and factored form)."""
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=100, n_heads=1, head_dim=64, window=window)
+    _say(f"100 layers x 1 head x 64, window {window}")
+    k, v = _mk(wl, seed=8, capacity=window + 8)
     k0, v0 = k.cpu().clone(), v.cpu().clone()
-    rc, p, tap = _run(k, v, wl, 132)
-    assert rc == 0 and p.head_tensors == 200
-    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, 132, TOL_BF16)
+    rc, p, tap = _run(k, v, wl, window)
+    assert rc == 0 and p.head_tensors == 200 and p.variant == variant
+    _check_all_heads(wl, k0, v0, k.cpu(), v.cpu(), tap.cpu(), p, window, TOL_BF16)
 
 
-def test_runs_on_the_callers_stream_and_prepare_is_idempotent():
-    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=516)
+@pytest.mark.parametrize("W", [516, 1264])
+def test_runs_on_the_callers_stream_and_prepare_is_idempotent(W):
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_heads=2, window=W)
     k, v = _mk(wl, seed=12)
     ka, va = k.clone(), v.clone()
-    rc, p, _ = _run(ka, va, wl, 516, tap=False)            # default stream
+    rc, p, _ = _run(ka, va, wl, W, tap=False)              # default stream
     assert rc == 0
     side = torch.cuda.Stream()
-    assert fk.prepare(fk.BF16, 0, 516, 4, 0.5, side) == 0   # basis already cached: only a stream wait
+    assert fk.prepare(fk.BF16, 0, W, 4, 0.5, side) == 0     # basis / tables already cached: only a stream wait
     L = binding.layout_for(k)
-    ws = torch.empty(p.workspace_bytes, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(p.workspace_bytes, 256), dtype=torch.uint8, device=DEV)
     L.workspace, L.workspace_bytes = ws.data_ptr(), p.workspace_bytes
     torch.cuda.synchronize()
     with torch.cuda.stream(side):
-        assert fk.compress(k, v, L, 2, 128, 516, 516, 4, 0.5, side) == 0
+        assert fk.compress(k, v, L, 2, 128, W, W, 4, 0.5, side) == 0
     side.synchronize()
     assert torch.equal(k, ka) and torch.equal(v, va)        # same bits whichever stream ran it
 
@@ -400,10 +402,12 @@ def test_dropping_variant(window, sink, ratio, extra, dtype):
 # ------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("lens,flags", [([300, 290, 307, 300], 0), ([300, 300, 301, 301], 0), ([10, 299, 0, 42], 0),
-                                        ([300, 290, 307, 300], fk.FLAG_DROPPING), ([340, 300, 300, 340], 0)])
+                                        ([300, 290, 307, 300], fk.FLAG_DROPPING), ([340, 300, 300, 340], 0),
+                                        ([144, 140, 151, 144], 0), ([184, 144, 144, 184], 0)])
 def test_ragged_batch(lens, flags):
-    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, batch=4, n_heads=2, window=300)
-    cap = 360
+    window = 144 if max(lens) < 200 else 300             # 144: span 140, the factored form
+    wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=2, batch=4, n_heads=2, window=window)
+    cap = window + 60
     _say(f"ragged compress lens={lens} flags={flags}")
     k, v = _mk(wl, seed=77, capacity=cap, cur_len=cap)
     k0, v0 = k.clone(), v.clone()
@@ -633,8 +637,10 @@ def test_power_spectrum_errors():
 # and chunk-wise attention can be captured once and replayed
 # ------------------------------------------------------------------------------------------
 
-def test_graph_capture_of_trigger_and_attention():
-    wl = synth.small(synth.WORKLOADS["llama3_8b_128k"], n_layers=2, n_heads=2, n_q_heads=8, window=516)
+@pytest.mark.parametrize("window", [516, 1264])
+def test_graph_capture_of_trigger_and_attention(window):
+    """Trigger (matrix form at 516, factored form at 1264) + decode attention + chunk attention in one HIP graph."""
+    wl = synth.small(synth.WORKLOADS["llama3_8b_128k"], n_layers=2, n_heads=2, n_q_heads=8, window=window)
     k0, v0 = _mk(wl, seed=17)
     k, v = k0.clone(), v0.clone()
     q = synth.queries(wl, 17, DEV)
