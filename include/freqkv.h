@@ -283,7 +283,7 @@ FREQKV_API freqkv_status_t freqkv_attend_decode_ragged(const void* q, const void
  *   out   DEVICE array [2 (K,V)][n_layers][n_heads][n_rows] fp32, 16-byte aligned; overwritten
  *   layout.workspace   as for a trigger with window - n_sink = n_rows (freqkv_plan reports it for
  *                      n_sink = row0, window = row0 + n_rows, any retain_ratio < 1)
- * bf16 caches only (FREQKV_E_UNSUPPORTED otherwise); n_rows >= 2.  No range guard here: cache values must
+ * bf16 and fp32 caches (both converted to fp16 operands); n_rows >= 2.  No range guard here: cache values must
  * stay below 32752 in magnitude (the folded span is an fp16 operand).  fp16 operands put a noise floor of
  * about 2e-7 of the average line under every line.  The sums are accumulated with fp32 atomics, so the
  * last bits can differ from call to call.  The first call for a new (device, n_rows) builds and caches the

@@ -1002,8 +1002,7 @@ freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, float* out, 
     Shape sh;
     freqkv_status_t rc = check_shape(layout, n_heads, head_dim, row0 + n_rows, row0 + n_rows, row0, 1.0, &sh);
     if (rc < 0) return rc;
-    if (layout->dtype != FREQKV_BF16) return FREQKV_E_UNSUPPORTED;
-    sh.variant = (sh.n % 2 == 0) ? kFoldF16 : kPlainF16;
+    sh.variant = (sh.n % 2 == 0) ? kFoldF16 : kPlainF16;        // fp32 caches too: converted to the fp16 operands
     sh.high = 2;
     const freqkv_layout_t& L = *layout;
     std::vector<char*> bases;
@@ -1031,7 +1030,7 @@ freqkv_status_t freqkv_power_spectrum(const void* k, const void* v, float* out, 
         for (int i = 0; i < slabs; ++i) tab.base[i] = bases[(size_t)s0 + i];
         ProfSpan sp;
         HIP_TRY(prof_begin(st, 0, &sp));
-        HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st));
+        HIP_TRY(launch_prepare_bf16(tab, g, (_Float16*)L.workspace, st, sh.elem));
         HIP_TRY(prof_end(st, &sp));
         HIP_TRY(prof_begin(st, 1, &sp));
         HIP_TRY(launch_contract_f16(tab, g, (const _Float16*)basis, (const _Float16*)L.workspace, out, 1, st));

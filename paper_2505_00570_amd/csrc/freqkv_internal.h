@@ -101,7 +101,8 @@ __device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t
 // ---- bf16 cache: largest magnitude per head-tensor (zero hmax first), fold/convert the span, contract
 hipError_t launch_absmax_bf16(const SlabTable& tab, const Geom& g, uint32_t* hmax, hipStream_t st);
 
-hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st);
+// elem_bytes 4: the cache holds float32 (power spectrum of fp32 caches only)
+hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st, int elem_bytes = 2);
 // mode 0: rows into the cache; 1: power-spectrum epilogue, tap = spectrum lines [slab][head][n] (atomics);
 // 2: even part of the two-level fold, fp16 rows into the buffer passed as tap, nothing else; 3: odd part, combined with g.ebuf into the cache
 hipError_t launch_contract_f16(const SlabTable& tab, const Geom& g, const _Float16* G,

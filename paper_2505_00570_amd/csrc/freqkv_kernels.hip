@@ -247,10 +247,13 @@ hipError_t launch_absmax_bf16(const SlabTable& tab, const Geom& g, uint32_t* hma
     return hipGetLastError();
 }
 
-template <bool FOLD>
+// F32: the cache holds float32 (the power-spectrum diagnostic of fp32 caches; compression of fp32 caches has
+// its own fp32 path), else bfloat16.
+template <bool FOLD, bool F32>
 __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Float16* __restrict__ ws)
 {
     constexpr int P = FOLD ? 2 : 1;
+    constexpr int EB = F32 ? 4 : 2;               // bytes per cache element
     const int ct   = blockIdx.x;
     const int ks   = blockIdx.y;
     const int kg   = threadIdx.x >> 6;        // one wave per group of 8 k
@@ -259,25 +262,35 @@ __global__ __launch_bounds__(256) void k_prepare_bf16(SlabTable tab, Geom g, _Fl
     const int vcol = ct * kColTile + col;
     const int j0   = (ks * 4 + kg) * 8;
 
-    uint32_t a[8], b[8];
+    float a0v[8], a1v[8], b0v[8], b1v[8];
     const bool colok = vcol < g.ncols;
     int ht = 0;
-    const char* base = colok ? column_base(tab, g, vcol, 2, &ht) : nullptr;
+    const char* base = colok ? column_base(tab, g, vcol, EB, &ht) : nullptr;
     const float sc = (colok && g.hmax) ? pow2f(guard_exponent(g.hmax[ht])) : 1.0f;
-    const long long rowb = g.stride_token * 2;   // bytes per token row
+    const long long rowb = g.stride_token * EB;   // bytes per token row
+    auto load2 = [&](long long row, float* x0, float* x1) {
+        if constexpr (F32) {
+            const f32x2 v = *(const f32x2*)(base + row * rowb);
+            *x0 = v[0]; *x1 = v[1];
+        } else {
+            const uint32_t w = *(const uint32_t*)(base + row * rowb);
+            *x0 = bf16_to_f32(w & 0xffffu); *x1 = bf16_to_f32(w >> 16);
+        }
+    };
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int j = j0 + i;
         bool ok = colok && j < g.Kh;
-        a[i] = ok ? *(const uint32_t*)(base + (long long)(g.S + j) * rowb) : 0u;
-        b[i] = (FOLD && ok) ? *(const uint32_t*)(base + (long long)(g.S + g.n - 1 - j) * rowb) : 0u;
+        a0v[i] = a1v[i] = b0v[i] = b1v[i] = 0.f;
+        if (ok) load2(g.S + j, &a0v[i], &a1v[i]);
+        if (FOLD && ok) load2(g.S + g.n - 1 - j, &b0v[i], &b1v[i]);
     }
     half8 e0, e1, o0, o1;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        float a0 = bf16_to_f32(a[i] & 0xffffu) * sc, a1 = bf16_to_f32(a[i] >> 16) * sc;
+        float a0 = a0v[i] * sc, a1 = a1v[i] * sc;
         if (FOLD) {
-            float b0 = bf16_to_f32(b[i] & 0xffffu) * sc, b1 = bf16_to_f32(b[i] >> 16) * sc;
+            float b0 = b0v[i] * sc, b1 = b1v[i] * sc;
             e0[i] = (_Float16)(a0 + b0); e1[i] = (_Float16)(a1 + b1);
             o0[i] = (_Float16)(a0 - b0); o1[i] = (_Float16)(a1 - b1);
         } else {
@@ -361,11 +374,16 @@ hipError_t launch_prepare_bf16_l2(const SlabTable& tab, const Geom& gA, _Float16
     return hipGetLastError();
 }
 
-hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st)
+hipError_t launch_prepare_bf16(const SlabTable& tab, const Geom& g, _Float16* ws, hipStream_t st, int elem_bytes)
 {
     dim3 grid(g.ncoltiles, g.nkstages);
-    if (g.fold) hipLaunchKernelGGL(k_prepare_bf16<true>,  grid, dim3(256), 0, st, tab, g, ws);
-    else        hipLaunchKernelGGL(k_prepare_bf16<false>, grid, dim3(256), 0, st, tab, g, ws);
+    if (elem_bytes == 4) {
+        if (g.fold) hipLaunchKernelGGL((k_prepare_bf16<true, true>),  grid, dim3(256), 0, st, tab, g, ws);
+        else        hipLaunchKernelGGL((k_prepare_bf16<false, true>), grid, dim3(256), 0, st, tab, g, ws);
+    } else {
+        if (g.fold) hipLaunchKernelGGL((k_prepare_bf16<true, false>),  grid, dim3(256), 0, st, tab, g, ws);
+        else        hipLaunchKernelGGL((k_prepare_bf16<false, false>), grid, dim3(256), 0, st, tab, g, ws);
+    }
     return hipGetLastError();
 }
 

@@ -581,10 +581,14 @@ def test_retain_high_rejects_dropping():
     (1, 1, 2, 128, 0, 701),      # odd length: plain transform
     (1, 2, 5, 96, 3, 260),       # column tiles straddle heads
     (1, 1, 2, 128, 0, 2048),     # several row tiles
+    (1, 2, 2, 64, 4, -508),      # an fp32 cache (negative n marks it): converted to the same fp16 operands
+    (1, 1, 1, 128, 0, -701),     # fp32, odd length
 ])
 def test_power_spectrum(layers, batch, heads, d, row0, n):
+    dtype = torch.float32 if n < 0 else torch.bfloat16
+    n = abs(n)
     wl = synth.small(synth.WORKLOADS["llama2_7b_layer"], n_layers=layers, batch=batch, n_heads=heads, head_dim=d,
-                     window=row0 + n)
+                     window=row0 + n, dtype=dtype)
     _say(f"power spectrum layers={layers} batch={batch} heads={heads} d={d} row0={row0} n={n}")
     k, v = _mk(wl, seed=n, capacity=row0 + n + 2, cur_len=row0 + n)
     k0, v0 = k.clone(), v.clone()
@@ -625,8 +629,8 @@ def test_power_spectrum_errors():
     f = lambda *a: fk.power_spectrum(k, v, out, L, 1, 128, *a, check=False)
     assert f(0, 128) == -3                      # no workspace
     assert f(0, 129) == -1 and f(-1, 10) == -1 and f(0, 1) == -1
-    kf = torch.zeros(1, 1, 1, 128, 128, device=DEV)
-    assert fk.power_spectrum(kf, kf, out, binding.layout_for(kf), 1, 128, 0, 128, check=False) == -2
+    kf = torch.zeros(1, 1, 1, 128, 128, device=DEV)        # fp32 caches are served too: same workspace rule
+    assert fk.power_spectrum(kf, kf, out, binding.layout_for(kf), 1, 128, 0, 128, check=False) == -3
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
 
