@@ -218,8 +218,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63, l32 = lane & 31, lhi = lane >> 5;
     // likewise the stage tables: read where they are used, in every iteration, not hoisted out of the loop
-    const char* tables = tables_arg;
-    asm volatile("" : "+s"(tables));
+    // (an opaque OFFSET, not an opaque pointer: the pointer must stay recognisably global, or its loads become
+    // flat loads, which the compiler can only wait for together with everything else in flight)
+    unsigned tables_off = 0;
+    asm volatile("" : "+s"(tables_off));
+    const char* tables = tables_arg + tables_off;
     const int next_vbid = vbid + (int)gridDim.x;
     const bool has_next = (!DIAG || stop == 9) && next_vbid < ntasks;
     char* next_base = base;
