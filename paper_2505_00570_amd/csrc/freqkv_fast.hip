@@ -195,11 +195,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             dst[i][j1] = *(const u32x4*)(bp + (uint32_t)makhoul_row(j, n) * rowb32);
         });
     };
-    // The prefetch of the next task is spread over four of the stages that follow stage Q: PF pieces at the start
-    // of each, behind that stage's own table loads (loads return in order: a table load must not queue behind
-    // freshly requested rows).  A burst of all pieces at one point blocks every wave at it until the
-    // memory pipeline has taken them; small portions are taken at once and arrive while the stage computes.
-    constexpr int PF = (4 * NIT + 3) / 4;              // four portions: stages P, P', Q' and the store
     int vbid = blockIdx.x;
     char* base;
     int ht, c0;
@@ -228,10 +223,17 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     char* next_base = base;
     int next_ht = ht, next_c0 = c0;
     if (has_next) map_task(next_vbid, &next_base, &next_ht, &next_c0);
-    u32x4 nraw[NIT][4];                                // rows of the next task, requested piecewise below
-    static_for<NIT>([&](auto ic) {
-        static_for<4>([&](auto jc) { nraw[ic.value][jc.value] = u32x4{0u, 0u, 0u, 0u}; });
-    });
+    // Rows of the next task: their 4 NIT pieces go out in 16 slots spread evenly over the whole task, one wave-wide
+    // request at a time between pieces of other work (the L1 fill path takes about one such request per 128
+    // cycles; requested in bursts they hold up the waves that issue them).  Without a next task the requests go
+    // out all the same, to this task's rows again (3 % more requests over a workgroup's 32 tasks): a branch
+    // around them would leave the compiler two possible counts of loads in flight, and it would then wait for
+    // the table loads of a stage as if nothing had been issued behind them, i.e. for the fresh rows as well.
+    u32x4 nraw[NIT][4];
+    auto pf = [&](auto kc) {
+        constexpr int k = decltype(kc)::value;
+        issue_loads(next_base, tid, nraw, IC<(k * 4 * NIT) / 16>{}, IC<((k + 1) * 4 * NIT) / 16>{});
+    };
     // ---- clear LDS while the rows are on their way (pad positions must hold finite values: they meet zero matrix entries)
     {
         u32x4 z = {0u, 0u, 0u, 0u};
@@ -260,6 +262,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     }
     __syncthreads();                                   // LDS cleared, red[] complete
     take_stamp(IC<8>{});
+    pf(IC<0>{});
     {
         uint32_t a = red[0];
         static_for<NW - 1>([&](auto w) { a = red[w.value + 1] > a ? red[w.value + 1] : a; });
@@ -308,6 +311,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             });
         }
     });
+    pf(IC<1>{});
     __syncthreads();
     take_stamp(IC<1>{});
     auto dump_and_stop = [&](int phase) -> bool {
@@ -339,7 +343,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         });
         // every tile of 32 rows starts at a multiple of 32: the rotation of a lane's row is the same in all of them
         const int rot = rot2(l32);
+        pf(IC<2>{});
         static_for<6>([&](auto ks) {
+            if constexpr (decltype(ks)::value == 2) pf(IC<3>{});
+            if constexpr (decltype(ks)::value == 4) pf(IC<4>{});
             const int coff = wrap12(ks.value * 2 + lhi + rot) * 8;
             static_for<UU>([&](auto uu) {
                 const _Float16* src = lds + ((wave + NW * uu.value) * Cfg::UROWS + l32) * 96 + coff;
@@ -352,6 +359,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 });
             });
         });
+        pf(IC<5>{});
         static_for<UU>([&](auto uu) {
             const int u = wave + NW * uu.value;
             static_for<Cfg::RT>([&](auto rt) {
@@ -379,9 +387,14 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         static_for<Cfg::NTP>([&](auto nt) {
             static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = ptab[0][nt.value * Cfg::KSP + ks.value][lane]; });
         });
-        if (has_next) issue_loads(next_base, tid, nraw, IC<0>{}, IC<PF>{});
         constexpr int TU = NW == 8 ? 3 : 4;
-        for (int t0 = wave; t0 < QH; t0 += NW * TU) {  // 32 QH columns = QH tiles of 32
+        constexpr int NIP = (QH + NW * TU - 1) / (NW * TU);       // iterations of the tile loop
+        static_for<NIP>([&](auto itc) {                 // 32 QH columns = QH tiles of 32
+            constexpr int it = decltype(itc)::value;
+            const int t0 = wave + it * NW * TU;
+            if constexpr (it == 0) pf(IC<6>{});
+            if constexpr (it == NIP - 1) pf(IC<7>{});
+            if (t0 >= QH) return;
             _Float16* col[TU];
             half8 b[TU][Cfg::KSP];
             static_for<TU>([&](auto tu) {
@@ -423,7 +436,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     });
                 }
             });
-        }
+        });
     }
     __syncthreads();
     take_stamp(IC<3>{});
@@ -437,14 +450,19 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         constexpr int NITEMS = 2 * Cfg::NPJ;
         constexpr int NR = (NITEMS + NT - 1) / NT;
         uint32_t* lds32 = (uint32_t*)lds;
-        for (int r = 0; r < NR; ++r) {
-            const int it = tid + NT * r;
-            if (it >= NITEMS) break;
+        static_for<NR>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+            const int it_raw = tid + NT * r;
+            const int it = it_raw < NITEMS ? it_raw : NITEMS - 1;     // lanes past the end read a valid table entry
             const int half = it >= Cfg::NPJ ? 1 : 0;
             const int pj = it - half * Cfg::NPJ;
             const int k3 = pj / (J2 / 2), kp = pj - k3 * (J2 / 2);
             const u32x4* T = (const u32x4*)(tables + Cfg::OFF_JOBS) + pj * 4;
             const u32x4 q0 = T[0], q1 = T[1], q2 = T[2], q3 = T[3];
+            __builtin_amdgcn_sched_barrier(0);              // the table first, the rows behind it
+            if constexpr (r == 0) pf(IC<8>{});
+            if constexpr (r == (NR > 1 ? 1 : 0)) pf(IC<9>{});
+            if (it_raw >= NITEMS) return;
             half2v t[16];
             static_for<4>([&](auto i) {
                 // (a bit cast straight from a vector ELEMENT reads element 0 whatever the index: copy first)
@@ -470,7 +488,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 re[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, orr);
                 im[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, oi);
             });
-        }
+        });
     }
     __syncthreads();
     take_stamp(IC<4>{});
@@ -484,7 +502,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         static_for<Cfg::NTP>([&](auto ct) {
             static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = ptab[1][ct.value * Cfg::KSP + ks.value][lane]; });
         });
-        if (has_next) issue_loads(next_base, tid, nraw, IC<PF>{}, IC<2 * PF>{});
+        pf(IC<10>{});
         constexpr int TU = 3;                          // 16 x 48 rows = 24 tiles
         for (int t0 = wave; t0 < 24; t0 += NW * TU) {
             half8 a[TU][Cfg::KSP];
@@ -537,6 +555,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             });
         }
     }
+    pf(IC<11>{});
     __syncthreads();
     take_stamp(IC<5>{});
     if (dump_and_stop(5)) return;
@@ -549,12 +568,12 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         static_for<3>([&](auto ct) {
             static_for<6>([&](auto ks) { bqi[ct.value][ks.value] = tq[(ct.value * 6 + ks.value) * 64]; });
         });
-        // pin the order: the table is requested here, ahead of the rows (the scheduler would otherwise sink its
-        // loads towards their first use, behind them)
+        // pin the table: it is requested AND awaited here, ahead of this stage's row requests (the scheduler would
+        // otherwise sink its loads towards their first use, behind them; a mere scheduling fence measured slower)
         static_for<3>([&](auto ct) {
             static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
         });
-        if (has_next) issue_loads(next_base, tid, nraw, IC<2 * PF>{}, IC<3 * PF>{});
+        pf(IC<12>{});
         constexpr int NT6 = 16 * J2 / 32;
         constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
         static_assert(TU <= 3, "tiles of a wave fit the register file");
@@ -596,19 +615,22 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             });
         }
     }
+    pf(IC<13>{});
     __syncthreads();
     take_stamp(IC<6>{});
     if (dump_and_stop(6)) return;
     if (DIAG && dump && !stamp) return;
 
     // ---- phase 7: store
-    if (has_next) issue_loads(next_base, tid, nraw, IC<3 * PF>{}, IC<4 * PF>{});
     {
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
-        for (int i = 0; i < NIT; ++i) {
+        static_for<NIT>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if constexpr (i == 0) pf(IC<14>{});
+            if constexpr (i == NIT / 2 && NIT > 1) pf(IC<15>{});
             const int pos = tid + NT * i;
-            if (pos >= Cfg::NPOS) break;
+            if (pos >= Cfg::NPOS) return;
             const int m2 = pos / Q, m3 = pos - m2 * Q;
             const half8 g0 = *(const half8*)(lds + ((0 * J2 + m2) * 96 + m3) * 8);
             const half8 g1 = *(const half8*)(lds + ((1 * J2 + m2) * 96 + m3) * 8);
@@ -642,7 +664,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     tp[(long long)rb * g.d + c] = vb[c];
                 }
             }
-        }
+        });
+        if constexpr (NIT == 1) pf(IC<15>{});
     }
     if constexpr (DIAG) if (stamp) {
         __syncthreads();
