@@ -508,7 +508,7 @@ const char* freqkv_status_string(freqkv_status_t s)
 
 const char* freqkv_last_error(void) { return g_last_error; }
 
-int freqkv_version(void) { return 101; }
+int freqkv_version(void) { return 200; }
 
 freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head_dim, int cur_len,
                             int window, int n_sink, double retain_ratio, freqkv_plan_t* out)
