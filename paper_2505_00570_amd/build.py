@@ -4,6 +4,7 @@ from __future__ import annotations
 import os
 import re
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
@@ -49,8 +50,7 @@ def check_device_asm(asm_path: str) -> tuple:
 def build(verbose: bool = True) -> str:
     os.makedirs(LIB_DIR, exist_ok=True)
     os.makedirs(OBJ_DIR, exist_ok=True)
-    objs = []
-    for src in SOURCES:
+    def compile_one(src: str) -> str:
         obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
         cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
@@ -61,7 +61,11 @@ def build(verbose: bool = True) -> str:
         if packed or foreign_m0:
             raise RuntimeError("%s: %d packed fp32 instructions, %d foreign uses of M0 in the device code"
                                % (src, packed, foreign_m0))
-        objs.append(obj)
+        return obj
+
+    # the files are independent: compile them side by side (hipcc itself is single-threaded per file)
+    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     if verbose:
