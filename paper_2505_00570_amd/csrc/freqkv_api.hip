@@ -151,7 +151,7 @@ size_t basis_bytes(const Shape& sh, const Geom& g)
     }
     if (sh.variant == kF32) return (size_t)sh.n * sh.Lc * sizeof(float);
     if (sh.variant == kNone) return 0;
-    if (sh.variant == kFast) return fast_table_bytes(sh.n);
+    if (sh.variant == kFast) return fast_table_bytes(sh.n, sh.d);
     return (size_t)(g.Kpad / 8) * g.Grows * 16;
 }
 
@@ -228,7 +228,7 @@ freqkv_status_t check_shape(const freqkv_layout_t* L, int n_heads, int head_dim,
     else if (L->flags & FREQKV_FLAG_DROPPING) sh.variant = kDrop;
     else if (L->dtype == FREQKV_F32) sh.variant = kF32;
     else if (!sh.high && !(L->flags & (FREQKV_FLAG_DENSE | FREQKV_FLAG_SINGLE_FOLD | FREQKV_FLAG_TWO_LEVEL_FOLD)) &&
-             fast_supported(sh.n, sh.Lc, nullptr, nullptr) &&
+             fast_supported(sh.n, sh.Lc, head_dim, nullptr, nullptr, nullptr) &&
              (long long)window * L->stride_token * 2 < (1LL << 32))       // its rows are addressed by 32-bit byte offsets
         sh.variant = kFast;
     else if (sh.n % 4 == 0 && sh.Lc % 2 == 0 && !(L->flags & FREQKV_FLAG_SINGLE_FOLD)) {
@@ -282,7 +282,7 @@ freqkv_status_t get_basis(const Shape& sh, const Geom& g, int rescale, hipStream
             // built on the host in fp64, copied from pinned memory in stream order (no synchronisation)
             err = hipHostMalloc(&e.host, e.bytes, hipHostMallocDefault);
             if (err == hipSuccess) {
-                fast_build_tables_host(sh.n, (char*)e.host);
+                fast_build_tables_host(sh.n, sh.d, (char*)e.host);
                 err = hipMemcpyAsync(e.ptr, e.host, e.bytes, hipMemcpyHostToDevice, st);
             }
         } else if (sh.variant == kF32) {
@@ -538,7 +538,7 @@ freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_heads, int head
         if (sh.variant == kFast) {
             // multiply-adds of the four matrix stages and the middle step, per channel, padding not counted
             int p = 0, q = 0;
-            fast_supported(sh.n, sh.Lc, &p, &q);
+            fast_supported(sh.n, sh.Lc, sh.d, &p, &q, nullptr);
             const double qh = (q + 1) / 2;
             const double per_channel = 2.0 * (4.0 * p * q * 2 * qh + 4.0 * qh * 4.0 * p * p + 16.0 * p * qh +
                                               2.0 * qh * 4.0 * p * p + 2.0 * p * 2 * qh * q);
@@ -562,7 +562,9 @@ freqkv_status_t freqkv_prepare(int dtype, uint32_t flags, int window, int n_sink
     if (sh.variant == kNone || sh.variant == kDrop) return FREQKV_OK;
     Geom g = make_geom(sh, L, 1, 0);
     void* basis = nullptr;
-    return get_basis(sh, g, !(flags & FREQKV_FLAG_NO_RESCALE), (hipStream_t)stream, &basis);
+    int key = !(flags & FREQKV_FLAG_NO_RESCALE);
+    if (sh.variant == kFast) fast_supported(sh.n, sh.Lc, sh.d, nullptr, nullptr, &key);   // keyed by channels per workgroup
+    return get_basis(sh, g, key, (hipStream_t)stream, &basis);
 }
 
 namespace {
@@ -622,7 +624,11 @@ freqkv_status_t compress_resolved(const std::vector<char*>& bases, const freqkv_
         void* tables = nullptr;
         {
             Geom g0 = make_geom(sh, L, 1, 0);
-            freqkv_status_t rc = get_basis(sh, g0, 1, st, &tables);       // the tables do not depend on the rescale
+            int channels = 8;
+            fast_supported(sh.n, sh.Lc, sh.d, nullptr, nullptr, &channels);
+            // the tables do not depend on the rescale; they do on the channels per workgroup (the p stage's
+            // padding differs), which takes the key's place
+            freqkv_status_t rc = get_basis(sh, g0, channels, st, &tables);
             if (rc < 0) return rc;
         }
         if (g_prof_on) { std::lock_guard<std::mutex> lock(g_mu); g_prof_acc.calls++; }
@@ -778,7 +784,9 @@ freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t*
     if (rc < 0) return rc;
     if (!k || !v || !dump || stop < 1 || stop > 9 || stop == 7) return FREQKV_E_INVALID;
     if (sh.variant != kFast) return FREQKV_E_UNSUPPORTED;
-    const size_t need = stop >= 8 ? (size_t)sh.hts_per_slab * sh.d / 8 * 72 : fast_lds_halfs(sh.n) * 2;
+    int channels = 8;
+    fast_supported(sh.n, sh.Lc, sh.d, nullptr, nullptr, &channels);
+    const size_t need = stop >= 8 ? (size_t)sh.hts_per_slab * sh.d / channels * 72 : fast_lds_halfs(sh.n, sh.d) * 2;
     if (dump_bytes < need) return FREQKV_E_WORKSPACE;
     std::vector<char*> bases;
     rc = resolve_bases(k, v, *layout, sh, 0, &bases);
@@ -786,7 +794,7 @@ freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t*
     hipStream_t st = (hipStream_t)stream;
     void* tables = nullptr;
     Geom g0 = make_geom(sh, *layout, 1, 0);
-    rc = get_basis(sh, g0, 1, st, &tables);
+    rc = get_basis(sh, g0, channels, st, &tables);
     if (rc < 0) return rc;
     SlabTable tab;
     memset(&tab, 0, sizeof(tab));

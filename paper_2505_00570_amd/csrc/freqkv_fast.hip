@@ -64,19 +64,22 @@ __device__ __forceinline__ void static_for(F&& f)
 
 constexpr int kFragBytes = 1024;          // one 32 x 16 operand fragment set: 64 lanes x 8 halfs
 
-template <int P_, int Q_>
+// C_: channels of a head-tensor that one workgroup owns (8: 16 bytes of every row; 16: 32 bytes, which halves
+// the cache lines touched per byte and is what LDS holds for the shorter spans).
+template <int P_, int Q_, int C_ = 8>
 struct FastCfg {
-    static constexpr int P = P_, Q = Q_;
-    static constexpr int J2 = (P + 7) / 8 * 8;        // p padded to whole 16-byte groups
+    static constexpr int P = P_, Q = Q_, C = C_;
+    static constexpr int CV = C / 8;                  // 16-byte pieces of a row per workgroup
+    static constexpr int J2 = C == 16 ? (P + 3) / 4 * 4 : (P + 7) / 8 * 8;   // p padded to whole 8- or 16-byte groups
     static constexpr int QH = (Q + 1) / 2;            // half-complex length of the q stage
     static constexpr int N = P * Q, n = 4 * N, Lc = 2 * N;
-    static constexpr int NG = 32;                     // (array, channel) groups
+    static constexpr int NG = 4 * C;                  // (array, channel) groups
     static constexpr int GH = 96 * J2;                // halfs per group
     static constexpr int LDS_HALFS = NG * GH;
     static constexpr int KP = 2 * J2;                 // contraction length of the complex p stage (Re | Im)
-    static constexpr int KSP = KP / 16;               // its 16-deep steps
+    static constexpr int KSP = (KP + 15) / 16;        // its 16-deep steps
     static constexpr int NTP = (KP + 31) / 32;        // its 32-wide output tiles
-    static constexpr int UROWS = (J2 % 32 == 0) ? J2 : (J2 == 24 ? 96 : (J2 == 8 ? 32 : 32));   // lcm(32, J2)
+    static constexpr int UROWS = (J2 % 32 == 0) ? J2 : ((J2 == 24 || J2 == 12) ? 96 : 32);   // lcm(32, J2)
     static constexpr int RT = UROWS / 32;
     static constexpr int NUNITS = NG * J2 / UROWS;
     static constexpr int NPOS = P * Q;
@@ -89,7 +92,15 @@ struct FastCfg {
     static constexpr int OFF_JOBS = OFF_QI + 3 * 6 * kFragBytes;
     static constexpr int TABLE_BYTES = OFF_JOBS + NPJ * 64;
     static_assert(Q <= 96 && 2 * QH <= 96 && QH <= 48, "q stage fits 96-wide tiles");
-    static_assert(KP <= 64 && KP % 16 == 0, "p stage fits two 32-wide tiles");
+    // does some group g have ((g J2) >> 2) & 3 == s?  (the load stage needs one LDS offset per such class)
+    static constexpr bool rot_class_used(int s)
+    {
+        for (int gq = 0; gq < NG; ++gq)
+            if ((((gq * J2) >> 2) & 3) == s) return true;
+        return false;
+    }
+    static_assert(C == 8 || C == 16, "8 or 16 channels per workgroup");
+    static_assert(KP <= 64 && J2 % 4 == 0, "p stage fits two 32-wide tiles");
     static_assert(UROWS % J2 == 0 && UROWS % 32 == 0 && (NG * J2) % UROWS == 0, "in-place units hold whole groups");
     static_assert(LDS_HALFS * 2 + 2 * NTP * KSP * kFragBytes <= 160 * 1024 - 256, "LDS");
 };
@@ -125,6 +136,23 @@ __device__ __forceinline__ void pin(half8& v) { asm volatile("" : "+v"(v)); }
 // Row of the span that holds sample j of the even-first / odd-reversed ordering of an n-point sequence.
 __device__ __forceinline__ int makhoul_row(int j, int n) { return j < n / 2 ? 2 * j : 2 * (n - 1 - j) + 1; }
 
+// Operand fragment of the p stages: the 8 contraction values k .. k+7, k = (part, j2) with `part` the real or
+// imaginary rows of column `col` (RS halfs apart) and J2 values per part.  J2 a multiple of 8: one 16-byte read.
+// J2 = 12: two 8-byte runs, each inside one part (4 divides 12); runs at or beyond KP = 2 J2 are zero padding.
+template <int J2>
+__device__ __forceinline__ half8 p_fragment(const _Float16* col, int RS, int k)
+{
+    if constexpr (J2 % 8 == 0) {
+        const int part = k / J2, j = k - part * J2;
+        return *(const half8*)(col + part * RS + j);
+    } else {
+        half4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+        if (k < 2 * J2) { const int part = k / J2, j = k - part * J2; lo = *(const half4*)(col + part * RS + j); }
+        if (k + 4 < 2 * J2) { const int part = (k + 4) / J2, j = k + 4 - part * J2; hi = *(const half4*)(col + part * RS + j); }
+        return half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    }
+}
+
 // dump: diagnostic only.  When not null, workgroup 0 copies its LDS there after phase `stop` (1 load ...
 // 6 stage Q') and every workgroup returns without writing the cache.
 template <class Cfg, int NW, bool DIAG>
@@ -133,7 +161,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                                                  _Float16* __restrict__ dump, int stop)
 {
     constexpr int P = Cfg::P, Q = Cfg::Q, J2 = Cfg::J2, QH = Cfg::QH, N = Cfg::N, n = Cfg::n, Lc = Cfg::Lc;
-    constexpr int GH = Cfg::GH;
+    constexpr int GH = Cfg::GH, C = Cfg::C, CV = Cfg::CV;
     constexpr int NT = NW * 64;                        // threads
     __shared__ __attribute__((aligned(1024))) _Float16 lds[Cfg::LDS_HALFS];
     __shared__ uint32_t red[NW];
@@ -148,11 +176,11 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // read of the same 256-byte rows, and the pieces they write, meet in that XCD's L2.  The grid is persistent:
     // a workgroup takes the virtual indices blockIdx.x, blockIdx.x + gridDim.x, ... (gridDim.x is a multiple
     // of 8 whenever it is smaller than the number of tasks, so the XCD of a virtual index is the workgroup's).
-    const int ntasks = g.ncols / 8;
+    const int ntasks = g.ncols / C;
     const long long rowb = g.stride_token * 2;
     const uint32_t rowb32 = (uint32_t)rowb;            // the host checked that a head-tensor's span stays below 4 GiB
     auto map_task = [&](int vb, char** base_out, int* ht_out, int* c0_out) {
-        const int tph = g.d / 8;                       // tasks per head-tensor
+        const int tph = g.d / C;                       // tasks per head-tensor
         const int hts = g.ncols / g.d;
         const int full = hts / 8;                      // groups of 8 head-tensors
         const int per_group = 8 * tph;
@@ -163,10 +191,10 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             task = (grp * 8 + xcd) * tph + slot;
         }
         int ht;
-        char* b = column_base(tab, g, task * 8, 2, &ht);
+        char* b = column_base(tab, g, task * C, 2, &ht);
         *base_out = b + (long long)g.S * rowb;
         *ht_out = ht;
-        *c0_out = task * 8 - ht * g.d;
+        *c0_out = task * C - ht * g.d;
     };
 
     // diagnostic: stop == 8 runs everything and leaves the shader-clock reading after each phase in dump
@@ -180,9 +208,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // Lane handles positions pos = tid + NT i of the p x q grid: the 4 x NIT row pieces of a task are requested
     // in one go, for the first task here and for every later one in the middle of the task before it.
     constexpr int NIT = (Cfg::NPOS + NT - 1) / NT;
-    u32x4 raw[NIT][4];
+    u32x4 raw[NIT][4][CV];
     // Requests pieces [F0, F1) of the lane's 4 NIT row pieces (piece f = 4 i + j1) of the task at bp into dst.
-    auto issue_loads = [&](const char* bp, int tid, u32x4 (&dst)[NIT][4], auto f0, auto f1) {
+    auto issue_loads = [&](const char* bp, int tid, u32x4 (&dst)[NIT][4][CV], auto f0, auto f1) {
         constexpr int F0 = decltype(f0)::value, F1 = decltype(f1)::value < 4 * NIT ? decltype(f1)::value : 4 * NIT;
         static_for<(F1 > F0 ? F1 - F0 : 0)>([&](auto fc) {
             constexpr int f = F0 + decltype(fc)::value;
@@ -192,7 +220,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             const int j2 = pos / Q, j3 = pos - j2 * Q;
             int j = (j2 * (4 * Q) + j3 * (4 * P)) % n + j1 * N;
             if (j >= n) j -= n;
-            dst[i][j1] = *(const u32x4*)(bp + (uint32_t)makhoul_row(j, n) * rowb32);
+            const char* rp = bp + (uint32_t)makhoul_row(j, n) * rowb32;
+            static_for<CV>([&](auto v) { dst[i][j1][v.value] = *(const u32x4*)(rp + 16 * v.value); });
         });
     };
     int vbid = blockIdx.x;
@@ -229,7 +258,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // out all the same, to this task's rows again (3 % more requests over a workgroup's 32 tasks): a branch
     // around them would leave the compiler two possible counts of loads in flight, and it would then wait for
     // the table loads of a stage as if nothing had been issued behind them, i.e. for the fresh rows as well.
-    u32x4 nraw[NIT][4];
+    u32x4 nraw[NIT][4][CV];
     auto pf = [&](auto kc) {
         constexpr int k = decltype(kc)::value;
         issue_loads(next_base, tid, nraw, IC<(k * 4 * NIT) / 16>{}, IC<((k + 1) * 4 * NIT) / 16>{});
@@ -247,8 +276,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         u16x2 m = {0, 0};
         static_for<NIT>([&](auto ic) {
             static_for<4>([&](auto jc) {
-                static_for<4>([&](auto wc) {
-                    uint32_t w = raw[decltype(ic)::value][decltype(jc)::value][decltype(wc)::value] & 0x7fff7fffu;
+                static_for<4 * CV>([&](auto wc) {
+                    uint32_t w = raw[decltype(ic)::value][decltype(jc)::value][decltype(wc)::value / 4][decltype(wc)::value % 4] & 0x7fff7fffu;
                     m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2, w));
                 });
             });
@@ -266,7 +295,8 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     {
         uint32_t a = red[0];
         static_for<NW - 1>([&](auto w) { a = red[w.value + 1] > a ? red[w.value + 1] : a; });
-        amax = a;
+        amax = (uint32_t)__builtin_amdgcn_readfirstlane((int)a);     // the same in every lane: keep it, and the scale
+                                                                     // derived from it, in scalar registers
     }
     // 2^e brings the largest magnitude into [256, 512): the transforms amplify a constant sequence by at most
     // sqrt(pq) / 2 < 64 after the butterfly's 1/2, so every intermediate stays below the fp16 limit, and 2^-e undoes
@@ -288,24 +318,27 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
         const int pos = tid + NT * i;
         if (pos < Cfg::NPOS) {
             const int j2 = pos / Q, j3 = pos - j2 * Q;
-            // row = g J2 + j2, and g J2 is a multiple of 8: the rotation depends on g only through bit 3 of g J2
+            // row = g J2 + j2, and g J2 is a multiple of 4: the rotation depends on g only through bits 2, 3 of g J2
             const int c = j3 >> 3;
-            const int off0 = j2 * 96 + wrap12(c + rot2(j2)) * 8 + (j3 & 7);
-            const int off8 = j2 * 96 + wrap12(c + rot2(j2 + 8)) * 8 + (j3 & 7);
-            static_for<4>([&](auto wc) {
-                constexpr int w = decltype(wc)::value;
+            int off[4] = {0, 0, 0, 0};
+            static_for<4>([&](auto sc4) {
+                constexpr int sv = decltype(sc4)::value;
+                if constexpr (Cfg::rot_class_used(sv)) off[sv] = j2 * 96 + wrap12(c + rot2(j2 + 4 * sv)) * 8 + (j3 & 7);
+            });
+            static_for<4 * CV>([&](auto wc) {
+                constexpr int v = decltype(wc)::value / 4, w = decltype(wc)::value % 4;
                 static_for<2>([&](auto hc) {
                     constexpr int hf = decltype(hc)::value;
-                    constexpr int ch = 2 * w + hf;
-                    const float a0 = hf ? bf16_hi(raw[i][0][w]) : bf16_lo(raw[i][0][w]);
-                    const float a1 = hf ? bf16_hi(raw[i][1][w]) : bf16_lo(raw[i][1][w]);
-                    const float a2 = hf ? bf16_hi(raw[i][2][w]) : bf16_lo(raw[i][2][w]);
-                    const float a3 = hf ? bf16_hi(raw[i][3][w]) : bf16_lo(raw[i][3][w]);
+                    constexpr int ch = 8 * v + 2 * w + hf;
+                    const float a0 = hf ? bf16_hi(raw[i][0][v][w]) : bf16_lo(raw[i][0][v][w]);
+                    const float a1 = hf ? bf16_hi(raw[i][1][v][w]) : bf16_lo(raw[i][1][v][w]);
+                    const float a2 = hf ? bf16_hi(raw[i][2][v][w]) : bf16_lo(raw[i][2][v][w]);
+                    const float a3 = hf ? bf16_hi(raw[i][3][v][w]) : bf16_lo(raw[i][3][v][w]);
                     const float s02 = a0 + a2, d02 = a0 - a2, s13 = a1 + a3, d13 = a3 - a1;
                     const float xv[4] = {(s02 + s13) * sc, (s02 - s13) * sc, d02 * sc, d13 * sc};
                     static_for<4>([&](auto xc) {
-                        constexpr int gq = decltype(xc)::value * 8 + ch;
-                        lds[gq * GH + (((gq * J2) & 8) ? off8 : off0)] = (_Float16)xv[xc.value];
+                        constexpr int gq = decltype(xc)::value * C + ch;
+                        lds[gq * GH + off[((gq * J2) >> 2) & 3]] = (_Float16)xv[xc.value];
                     });
                 });
             });
@@ -359,7 +392,6 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 });
             });
         });
-        pf(IC<5>{});
         static_for<UU>([&](auto uu) {
             const int u = wave + NW * uu.value;
             static_for<Cfg::RT>([&](auto rt) {
@@ -374,6 +406,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 });
             });
         });
+        pf(IC<5>{});                                    // behind the epilogue: its accumulators are free by now
     }
     __syncthreads();
     take_stamp(IC<2>{});
@@ -388,26 +421,24 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             static_for<Cfg::KSP>([&](auto ks) { ap[nt.value][ks.value] = ptab[0][nt.value * Cfg::KSP + ks.value][lane]; });
         });
         constexpr int TU = NW == 8 ? 3 : 4;
-        constexpr int NIP = (QH + NW * TU - 1) / (NW * TU);       // iterations of the tile loop
-        static_for<NIP>([&](auto itc) {                 // 32 QH columns = QH tiles of 32
+        constexpr int NTL = (Cfg::NG / 32) * QH;        // NG QH columns in tiles of 32
+        constexpr int NIP = (NTL + NW * TU - 1) / (NW * TU);      // iterations of the tile loop
+        static_for<NIP>([&](auto itc) {
             constexpr int it = decltype(itc)::value;
             const int t0 = wave + it * NW * TU;
             if constexpr (it == 0) pf(IC<6>{});
             if constexpr (it == NIP - 1) pf(IC<7>{});
-            if (t0 >= QH) return;
+            if (t0 >= NTL) return;
             _Float16* col[TU];
             half8 b[TU][Cfg::KSP];
             static_for<TU>([&](auto tu) {
                 int t = t0 + NW * tu.value;
-                if (t > QH - 1) t = QH - 1;            // a tile past the end repeats the last one and is not written
+                if (t > NTL - 1) t = NTL - 1;          // a tile past the end repeats the last one and is not written
                 const int mp = t * 32 + l32;
                 const int grp = mp / QH, f3 = mp - grp * QH;
                 col[tu.value] = lds + grp * GH + f3 * J2;
                 static_for<Cfg::KSP>([&](auto ks) {
-                    constexpr int k = ks.value * 16;
-                    const int kk = k + 8 * lhi;
-                    const int part = kk / J2, j2c = kk - part * J2;
-                    b[tu.value][ks.value] = *(const half8*)(col[tu.value] + part * QH * J2 + j2c);
+                    b[tu.value][ks.value] = p_fragment<J2>(col[tu.value], QH * J2, ks.value * 16 + 8 * lhi);
                 });
             });
             f32x16 acc[TU][Cfg::NTP];
@@ -423,7 +454,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 });
             });
             static_for<TU>([&](auto tu) {
-                if (t0 + NW * tu.value < QH) {
+                if (t0 + NW * tu.value < NTL) {
                     static_for<Cfg::NTP>([&](auto nt) {
                         static_for<4>([&](auto r4) {
                             const int n0 = nt.value * 32 + 8 * r4.value + 4 * lhi;
@@ -447,15 +478,15 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // U of the even k with these residues (from F0, F2) and of the odd k (from Fr, Fi); both land in place
     // of F0 and F2.  Packed fp16 arithmetic: both k2 of the pair at once.
     {
-        constexpr int NITEMS = 2 * Cfg::NPJ;
+        constexpr int NITEMS = (C / 4) * Cfg::NPJ;      // (pair of k2, k3) x groups of four channels
         constexpr int NR = (NITEMS + NT - 1) / NT;
         uint32_t* lds32 = (uint32_t*)lds;
         static_for<NR>([&](auto rc) {
             constexpr int r = decltype(rc)::value;
             const int it_raw = tid + NT * r;
             const int it = it_raw < NITEMS ? it_raw : NITEMS - 1;     // lanes past the end read a valid table entry
-            const int half = it >= Cfg::NPJ ? 1 : 0;
-            const int pj = it - half * Cfg::NPJ;
+            const int quarter = it / Cfg::NPJ;
+            const int pj = it - quarter * Cfg::NPJ;
             const int k3 = pj / (J2 / 2), kp = pj - k3 * (J2 / 2);
             const u32x4* T = (const u32x4*)(tables + Cfg::OFF_JOBS) + pj * 4;
             const u32x4 q0 = T[0], q1 = T[1], q2 = T[2], q3 = T[3];
@@ -475,18 +506,18 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             uint32_t* re = lds32 + (k3 * J2) / 2 + kp;
             uint32_t* im = re + (QH * J2) / 2;
             static_for<4>([&](auto cc) {
-                const int ch = half * 4 + cc.value;
-                auto ld = [&](uint32_t* p, int xa) { return __builtin_bit_cast(half2v, p[(xa * 8 + ch) * (GH / 2)]); };
+                const int ch = quarter * 4 + cc.value;
+                auto ld = [&](uint32_t* p, int xa) { return __builtin_bit_cast(half2v, p[(xa * C + ch) * (GH / 2)]); };
                 const half2v ar = ld(re, 0), ai = ld(im, 0), br = ld(re, 1), bi = ld(im, 1);
                 const half2v cr = ld(re, 2), ci = ld(im, 2), dr = ld(re, 3), di = ld(im, 3);
                 const half2v er = t[0] * ar + t[1] * ai + t[2] * br + t[3] * bi;
                 const half2v ei = t[4] * ar + t[5] * ai + t[6] * br + t[7] * bi;
                 const half2v orr = t[8] * cr + t[9] * ci + t[10] * dr + t[11] * di;
                 const half2v oi = t[12] * cr + t[13] * ci + t[14] * dr + t[15] * di;
-                re[(0 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, er);
-                im[(0 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, ei);
-                re[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, orr);
-                im[(1 * 8 + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, oi);
+                re[(0 * C + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, er);
+                im[(0 * C + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, ei);
+                re[(1 * C + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, orr);
+                im[(1 * C + ch) * (GH / 2)] = __builtin_bit_cast(uint32_t, oi);
             });
         });
     }
@@ -496,15 +527,15 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
 
     // ---- phase 5: stage P'.  Rows m' = (g', k3 padded to 48), g' = (k1, ch) < 16, x contraction (part, k2)
     // -> (part', m2); results go to the other half of LDS as E[(k1, m2, ch)][part' 48 + k3].
-    constexpr int Y0 = 16 * GH;
+    constexpr int Y0 = 2 * C * GH;
     {
         half8 bp[Cfg::NTP][Cfg::KSP];
         static_for<Cfg::NTP>([&](auto ct) {
             static_for<Cfg::KSP>([&](auto ks) { bp[ct.value][ks.value] = ptab[1][ct.value * Cfg::KSP + ks.value][lane]; });
         });
         pf(IC<10>{});
-        constexpr int TU = 3;                          // 16 x 48 rows = 24 tiles
-        for (int t0 = wave; t0 < 24; t0 += NW * TU) {
+        constexpr int TU = 3;                          // 2 C x 48 rows = 3 C tiles
+        for (int t0 = wave; t0 < 3 * C; t0 += NW * TU) {
             half8 a[TU][Cfg::KSP];
             static_for<TU>([&](auto tu) {
                 const int mp = (t0 + NW * tu.value) * 32 + l32;
@@ -513,9 +544,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                 if (k3 > QH - 1) k3 = QH - 1;          // pad rows: any finite data, their results meet zeros
                 const _Float16* rowp = lds + grp * GH + k3 * J2;
                 static_for<Cfg::KSP>([&](auto ks) {
-                    const int kk = ks.value * 16 + 8 * lhi;
-                    const int part = kk / J2, k2c = kk - part * J2;
-                    a[tu.value][ks.value] = *(const half8*)(rowp + part * QH * J2 + k2c);
+                    a[tu.value][ks.value] = p_fragment<J2>(rowp, QH * J2, ks.value * 16 + 8 * lhi);
                 });
             });
             f32x16 acc[TU][Cfg::NTP];
@@ -536,19 +565,22 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     const int nn = ct.value * 32 + l32;
                     if (nn < Cfg::KP) {
                         const int part = nn / J2, m2 = nn - part * J2;
-                        const int m2r = m2 % 12;
+                        const int m2r = (m2 * (C / 8)) % 12;
                         static_for<4>([&](auto r4) {
                             // rows m0 .. m0+3 with m0 = 32 t + 8 r4 + 4 lhi: everything but the last term is the
                             // same for the whole wave, and 48 is a multiple of 8, so g' and the chunk of k3 are too
                             const int mu = t * 32 + 8 * r4.value;
                             const int g2 = mu / 48, k3u = mu - g2 * 48;         // wave-uniform
-                            const int k1 = g2 >> 3, ch = g2 & 7;
-                            const int rotu = (k1 * J2 + 2 * (ch >> 2)) % 12;     // wave-uniform part of rot12(row)
-                            const int rowu = (k1 * J2 * 8 + ch) * 96 + (k3u & 7);
+                            const int k1 = g2 / C, ch = g2 - k1 * C;
+                            // row = (k1 J2 + m2) C + ch; m2 C is a multiple of 8, so rot12(row) splits into a
+                            // wave-uniform part and m2's
+                            const int rowq = k1 * J2 * C + ch;
+                            const int rotu = ((rowq >> 3) + 2 * ((rowq >> 2) & 1)) % 12;
+                            const int rowu = rowq * 96 + (k3u & 7);
                             const int chunk = wrap12(wrap12(m2r + rotu) + part * 6 + (k3u >> 3));
                             const half4 o = cvt4(acc[tu.value][ct.value][4 * r4.value], acc[tu.value][ct.value][4 * r4.value + 1],
                                                  acc[tu.value][ct.value][4 * r4.value + 2], acc[tu.value][ct.value][4 * r4.value + 3]);
-                            *(half4*)(lds + Y0 + rowu + m2 * (8 * 96) + chunk * 8 + 4 * lhi) = o;
+                            *(half4*)(lds + Y0 + rowu + m2 * (C * 96) + chunk * 8 + 4 * lhi) = o;
                         });
                     }
                 });
@@ -574,7 +606,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
         });
         pf(IC<12>{});
-        constexpr int NT6 = 16 * J2 / 32;
+        constexpr int NT6 = 2 * C * J2 / 32;
         constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
         static_assert(TU <= 3, "tiles of a wave fit the register file");
         for (int t0 = wave; t0 < NT6; t0 += NW * TU) {
@@ -606,9 +638,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
                     const int m3 = ct.value * 32 + l32;
                     if (m3 < Q && t < NT6) {
                         static_for<4>([&](auto r4) {
-                            const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) 8 + ch, ch = 0 or 4
+                            const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) C + ch, ch a multiple of 4
                             const half4 o = cvt4(acc[tu.value][ct.value][4 * r4.value], acc[tu.value][ct.value][4 * r4.value + 1], acc[tu.value][ct.value][4 * r4.value + 2], acc[tu.value][ct.value][4 * r4.value + 3]);
-                            *(half4*)(lds + ((v0 >> 3) * 96 + m3) * 8 + (v0 & 7)) = o;
+                            *(half4*)(lds + ((v0 / C) * 96 + m3) * C + (v0 % C)) = o;
                         });
                     }
                 });
@@ -625,45 +657,53 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     {
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
+        // positions recomputed from an opaque copy of the lane index: shared with the load stage's, the quotients
+        // would be kept alive (spilled) across all stages, and a reload queues behind the rows in flight
+        int tid_s = tid;
+        asm volatile("" : "+v"(tid_s));
         static_for<NIT>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             if constexpr (i == 0) pf(IC<14>{});
             if constexpr (i == NIT / 2 && NIT > 1) pf(IC<15>{});
-            const int pos = tid + NT * i;
+            const int pos = tid_s + NT * i;
             if (pos >= Cfg::NPOS) return;
             const int m2 = pos / Q, m3 = pos - m2 * Q;
-            const half8 g0 = *(const half8*)(lds + ((0 * J2 + m2) * 96 + m3) * 8);
-            const half8 g1 = *(const half8*)(lds + ((1 * J2 + m2) * 96 + m3) * 8);
+            const _Float16* u0 = lds + ((0 * J2 + m2) * 96 + m3) * C;
+            const _Float16* u1 = lds + ((1 * J2 + m2) * 96 + m3) * C;
             int ma = (m2 * (2 * Q) + m3 * (2 * P)) % Lc;
             int mb = ma + N;
             if (mb >= Lc) mb -= Lc;
             const int ra = makhoul_row(ma, Lc), rb = makhoul_row(mb, Lc);
-            float va[8], vb[8];
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float a = (float)g0[c], b = (float)g1[c];
-                va[c] = (a + b) * unsc;
-                vb[c] = (a - b) * unsc;
-            }
-            if (nonfinite) {
-#pragma unroll
-                for (int c = 0; c < 8; ++c) va[c] = vb[c] = __builtin_nanf("");
-            }
-            u32x4 pa, pb;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                pa[c] = pack_bf16x2(va[2 * c], va[2 * c + 1]);
-                pb[c] = pack_bf16x2(vb[2 * c], vb[2 * c + 1]);
-            }
-            *(u32x4*)(base + (uint32_t)ra * rowb32) = pa;
-            *(u32x4*)(base + (uint32_t)rb * rowb32) = pb;
-            if (tp) {
+            static_for<CV>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
+                const half8 g0 = *(const half8*)(u0 + 8 * v), g1 = *(const half8*)(u1 + 8 * v);
+                float va[8], vb[8];
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    tp[(long long)ra * g.d + c] = va[c];
-                    tp[(long long)rb * g.d + c] = vb[c];
+                    const float a = (float)g0[c], b = (float)g1[c];
+                    va[c] = (a + b) * unsc;
+                    vb[c] = (a - b) * unsc;
                 }
-            }
+                if (nonfinite) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) va[c] = vb[c] = __builtin_nanf("");
+                }
+                u32x4 pa, pb;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    pa[c] = pack_bf16x2(va[2 * c], va[2 * c + 1]);
+                    pb[c] = pack_bf16x2(vb[2 * c], vb[2 * c + 1]);
+                }
+                *(u32x4*)(base + (uint32_t)ra * rowb32 + 16 * v) = pa;
+                *(u32x4*)(base + (uint32_t)rb * rowb32 + 16 * v) = pb;
+                if (tp) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        tp[(long long)ra * g.d + 8 * v + c] = va[c];
+                        tp[(long long)rb * g.d + 8 * v + c] = vb[c];
+                    }
+                }
+            });
         });
         if constexpr (NIT == 1) pf(IC<15>{});
     }
@@ -678,7 +718,9 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     if (!has_next) break;
     vbid = next_vbid; base = next_base; ht = next_ht; c0 = next_c0;
     static_for<NIT>([&](auto ic) {
-        static_for<4>([&](auto jc) { raw[ic.value][jc.value] = nraw[ic.value][jc.value]; });
+        static_for<4>([&](auto jc) {
+            static_for<CV>([&](auto v) { raw[ic.value][jc.value][v.value] = nraw[ic.value][jc.value][v.value]; });
+        });
     });
     __syncthreads();                                   // every wave is done with this task's LDS image
   }
@@ -805,7 +847,7 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
                       _Float16* dump, int stop, hipStream_t st)
 {
     constexpr int NW = 8;          // two waves per SIMD: one wave's LDS traffic and conversions overlap the other's matrix work
-    const unsigned tasks = (unsigned)(g.ncols / 8);
+    const unsigned tasks = (unsigned)(g.ncols / Cfg::C);
     // Persistent grid: as many workgroups as the device holds at once (LDS decides), a multiple of 8 so that a
     // workgroup's tasks stay on its XCD.  The diagnostic modes run one task per workgroup.
     unsigned grid = tasks;
@@ -828,39 +870,41 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
 }
 
 // The factorizations with compiled kernels, n = 4 p q with window = n + 4 sinks: the paper's two windows (8192,
-// 4096), two shorter ones (2048, 1024) and two small spans for tests (1260, 140).
-#define FREQKV_FAST_CFGS(X) X(23, 89) X(11, 93) X(7, 73) X(3, 85) X(7, 45) X(5, 7)
+// 4096), two shorter ones (2048, 1024) and two small spans for tests (1260, 140).  The span 4092 has two: 16
+// channels per workgroup where head_dim allows (the first match in this list is taken), 8 otherwise.
+#define FREQKV_FAST_CFGS(X) X(23, 89, 8) X(11, 93, 16) X(11, 93, 8) X(7, 73, 8) X(3, 85, 8) X(7, 45, 8) X(5, 7, 8)
+#define FREQKV_FAST_MATCH(P_, Q_, C_) (n == FastCfg<P_, Q_, C_>::n && head_dim % C_ == 0)
 
 }  // namespace
 
-bool fast_supported(int n, int Lc, int* p, int* q)
+bool fast_supported(int n, int Lc, int head_dim, int* p, int* q, int* channels)
 {
     if (Lc * 2 != n) return false;
-#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) { if (p) *p = P_; if (q) *q = Q_; return true; }
+#define X(P_, Q_, C_) if (FREQKV_FAST_MATCH(P_, Q_, C_)) { if (p) *p = P_; if (q) *q = Q_; if (channels) *channels = C_; return true; }
     FREQKV_FAST_CFGS(X)
 #undef X
     return false;
 }
 
-size_t fast_table_bytes(int n)
+size_t fast_table_bytes(int n, int head_dim)
 {
-#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) return FastCfg<P_, Q_>::TABLE_BYTES;
+#define X(P_, Q_, C_) if (FREQKV_FAST_MATCH(P_, Q_, C_)) return FastCfg<P_, Q_, C_>::TABLE_BYTES;
     FREQKV_FAST_CFGS(X)
 #undef X
     return 0;
 }
 
-size_t fast_lds_halfs(int n)
+size_t fast_lds_halfs(int n, int head_dim)
 {
-#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) return FastCfg<P_, Q_>::LDS_HALFS;
+#define X(P_, Q_, C_) if (FREQKV_FAST_MATCH(P_, Q_, C_)) return FastCfg<P_, Q_, C_>::LDS_HALFS;
     FREQKV_FAST_CFGS(X)
 #undef X
     return 0;
 }
 
-void fast_build_tables_host(int n, char* out)
+void fast_build_tables_host(int n, int head_dim, char* out)
 {
-#define X(P_, Q_) if (n == FastCfg<P_, Q_>::n) { build_tables<FastCfg<P_, Q_>>(out); return; }
+#define X(P_, Q_, C_) if (FREQKV_FAST_MATCH(P_, Q_, C_)) { build_tables<FastCfg<P_, Q_, C_>>(out); return; }
     FREQKV_FAST_CFGS(X)
 #undef X
 }
@@ -868,8 +912,8 @@ void fast_build_tables_host(int n, char* out)
 hipError_t launch_fast(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
                        _Float16* dump, int stop, hipStream_t st)
 {
-    if (g.ncols % 8 || g.d % 8) return hipErrorInvalidValue;
-#define X(P_, Q_) if (g.n == FastCfg<P_, Q_>::n) return launch_cfg<FastCfg<P_, Q_>>(tab, g, tables, rest_scale, tap, dump, stop, st);
+    const int n = g.n, head_dim = g.d;
+#define X(P_, Q_, C_) if (FREQKV_FAST_MATCH(P_, Q_, C_)) return launch_cfg<FastCfg<P_, Q_, C_>>(tab, g, tables, rest_scale, tap, dump, stop, st);
     FREQKV_FAST_CFGS(X)
 #undef X
     return hipErrorInvalidValue;

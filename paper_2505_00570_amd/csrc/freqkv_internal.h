@@ -117,11 +117,12 @@ hipError_t launch_contract_f32(const SlabTable& tab, const Geom& g, const float*
                                const float* ws, float* tap, hipStream_t st);
 
 // ---- factored transform (spans n = 4pq, Lc = n/2, bf16 caches): one kernel, no workspace ------------------
-// Is there a compiled kernel for this span?  (p, q) are the coprime odd factors of n/4.
-bool fast_supported(int n, int Lc, int* p, int* q);
-size_t fast_table_bytes(int n);                       // stage matrices in fragment order + the middle step's maps
-size_t fast_lds_halfs(int n);                         // fp16 values of one workgroup's LDS image (diagnostics)
-void fast_build_tables_host(int n, char* out);        // fp64, rounded once; `out` is host memory
+// Is there a compiled kernel for this span and head_dim?  (p, q) are the coprime odd factors of n/4, `channels`
+// the channels of a head-tensor one workgroup owns (head_dim is a multiple of it).
+bool fast_supported(int n, int Lc, int head_dim, int* p, int* q, int* channels);
+size_t fast_table_bytes(int n, int head_dim);         // stage matrices in fragment order + the middle step's maps
+size_t fast_lds_halfs(int n, int head_dim);           // fp16 values of one workgroup's LDS image (diagnostics)
+void fast_build_tables_host(int n, int head_dim, char* out);   // fp64, rounded once; `out` is host memory
 // rest_scale: what is left of the operator's 1/n after the scaled stages (1/2; sqrt(n/Lc)/2 without the
 // rescale of Eq. 3).  dump/stop: diagnostic, see the kernel; pass nullptr, 0.
 hipError_t launch_fast(const SlabTable& tab, const Geom& g, const void* tables, float rest_scale, float* tap,
