@@ -870,9 +870,9 @@ hipError_t launch_cfg(const SlabTable& tab, const Geom& g, const void* tables, f
 }
 
 // The factorizations with compiled kernels, n = 4 p q with window = n + 4 sinks: the paper's two windows (8192,
-// 4096), two shorter ones (2048, 1024) and two small spans for tests (1260, 140).  The span 4092 has two: 16
+// 4096), two shorter ones (2048, 1024) and two small spans for tests (1260, 140).  Spans up to 4092 have two: 16
 // channels per workgroup where head_dim allows (the first match in this list is taken), 8 otherwise.
-#define FREQKV_FAST_CFGS(X) X(23, 89, 8) X(11, 93, 16) X(11, 93, 8) X(7, 73, 8) X(3, 85, 8) X(7, 45, 8) X(5, 7, 8)
+#define FREQKV_FAST_CFGS(X) X(23, 89, 8) X(11, 93, 16) X(11, 93, 8) X(7, 73, 16) X(7, 73, 8) X(3, 85, 16) X(3, 85, 8) X(7, 45, 8) X(5, 7, 8)
 #define FREQKV_FAST_MATCH(P_, Q_, C_) (n == FastCfg<P_, Q_, C_>::n && head_dim % C_ == 0)
 
 }  // namespace
