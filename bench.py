@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * (5.244e5 + 9.187e5) + 1.0 * (2.62e5 + 5.24e5)) * 1024}
 TRAFFIC_BYTES_SINGLE_FOLD = {"llama3_8b_128k": (2.0 * 2.622e6 + 1.0 * 5.24e5) * 1024}
 # the same for the factored transform's single kernel (profiles/fast_llama3_8b_128k_pmc.txt)
-FAST_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.385e5 + 1.0 * 5.24e5) * 1024}
+FAST_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.4e5 + 1.0 * 5.24e5) * 1024}
 # the same for k_attend_partial (profiles/attend_llama3_8b_128k_pmc.txt)
 ATTEND_TRAFFIC_BYTES_PER_LAUNCH = {"llama3_8b_128k": (2.0 * 5.248e5 + 1.0 * 1608) * 1024}
 # the same for k_attend_prefill (profiles/prefill_llama3_8b_128k.txt)
