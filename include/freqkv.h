@@ -170,11 +170,11 @@ FREQKV_API freqkv_status_t freqkv_plan(const freqkv_layout_t* layout, int n_head
  *            (device, n, Lc, dtype, flags) builds and caches the basis table (one allocation).
  * retain_ratio == 1 (Lc == n) is the identity and enqueues nothing (FREQKV_OK).
  * Value range (bf16 caches): the matrix cores take fp16 operands, whose range is narrower than bfloat16's.
- * Every head-tensor (every 8-channel slice of one in the factored form) is therefore scaled by an exact
+ * Every head-tensor (every 8- or 16-channel slice of one in the factored form) is therefore scaled by an exact
  * power of two, chosen from the largest magnitude of its span, on its way in and back on its way out, so
  * finite cache values of any magnitude neither overflow nor sink into fp16 subnormals; only values more
  * than 2^24 times smaller than the largest of their head-tensor (slice) lose precision.  An inf or
- * nan in the span makes the results of its channels non-finite (of its whole 8-channel slice in the factored form).  Basis entries below 6e-5 are fp16 subnormals (absolute error
+ * nan in the span makes the results of its channels non-finite (of its whole slice in the factored form).  Basis entries below 6e-5 are fp16 subnormals (absolute error
  * 2^-25, far below the tolerance).
  * On a negative status no device memory has been written.
  */

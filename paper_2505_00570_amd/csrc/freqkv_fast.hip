@@ -14,9 +14,9 @@
 //             residues (t mod 4, t mod p, t mod q) the length-n DFT is a 4 x p x q DFT with no twiddle factors
 //             between its stages, and likewise 2 x p x q for the inverse.
 //
-// One workgroup owns 8 channels of one head-tensor for all rows (column ownership): it reads its 16 bytes of
-// every span row straight from the cache, keeps every intermediate in LDS, and writes its 16 bytes of the Lc
-// result rows back.  No workspace, no second pass over HBM, and no in-place hazard: nobody else touches
+// One workgroup owns 8 channels (16 where LDS holds them: the shorter spans) of one head-tensor for all rows
+// (column ownership): it reads its 16 (32) bytes of every span row straight from the cache, keeps every
+// intermediate in LDS, and writes its 16 (32) bytes of the Lc result rows back.  No workspace, no second pass over HBM, and no in-place hazard: nobody else touches
 // these channels.  The length-p and length-q stages are small dense DFT matrices applied on the matrix cores
 // (fp16 operands, fp32 accumulation) to the rows or columns of LDS-resident tiles; the length-4 and length-2
 // stages are butterflies folded into the load and the store; the step between the two transforms (twiddles,
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     // sqrt(pq) / 2 < 64 after the butterfly's 1/2, so every intermediate stays below the fp16 limit, and 2^-e undoes
     // the scale exactly at the end
     int e = 0;
-    const bool nonfinite = (amax >> 7) == 255;         // an inf or nan somewhere in the slice: its 8 channels come out nan
+    const bool nonfinite = (amax >> 7) == 255;         // an inf or nan somewhere in the slice: its channels come out nan
     {
         const int E = (int)(amax >> 7);                // exponent field of the largest magnitude
         if (E > 0 && E < 255) e = 135 - E;
