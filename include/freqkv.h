@@ -327,13 +327,13 @@ FREQKV_API freqkv_status_t freqkv_attend_prefill(const void* q, const void* k, c
 /*
  * Diagnostic of the factored transform (variant 6), used by the tests to check its stages one by one: runs
  * the kernel on the K cache of layer 0 up to and including stage `stop` (1 load and length-4 butterfly,
- * 2 q-point forward stage, 3 p-point forward stage, 4 step between the transforms, 5 p-point inverse stage,
- * 6 q-point inverse stage), copies the fp16 LDS image of the workgroup that owns channels 0..7 of the first
+ * 2 q-point forward stage, 3 p-point forward stage, 4 step between the transforms, 5 p-point inverse stage;
+ * the q-point inverse stage writes straight to the cache and leaves no image), copies the fp16 LDS image of the workgroup that owns channels 0..7 of the first
  * head-tensor to `dump` (device memory, dump_bytes >= what the span needs, at most 160 KiB) and writes
  * nothing to the cache.  stop = 8 (one workgroup per task) or 9 (the persistent grid of a real call) instead
  * runs the whole transform on the K cache of layer 0 (the cache IS
  * written) and leaves, per workgroup, 9 int64 shader-clock readings in dump (start, then after each of the
- * stages above and after the store, then the moment the rows had arrived inside stage 1;
+ * stages above (the sixth repeats the fifth) and after the last stage, then the moment the rows had arrived inside stage 1;
  * dump_bytes >= 72 * batch * n_heads * head_dim / 8).
  * retain_ratio is 0.5.  FREQKV_E_UNSUPPORTED when the span has no factored form.
  */

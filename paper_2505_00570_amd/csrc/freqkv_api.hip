@@ -782,7 +782,7 @@ freqkv_status_t freqkv_debug_fast_stage(void* k, void* v, const freqkv_layout_t*
     Shape sh;
     freqkv_status_t rc = check_shape(layout, n_heads, head_dim, window, window, n_sink, 0.5, &sh);
     if (rc < 0) return rc;
-    if (!k || !v || !dump || stop < 1 || stop > 9 || stop == 7) return FREQKV_E_INVALID;
+    if (!k || !v || !dump || stop < 1 || stop > 9 || stop == 6 || stop == 7) return FREQKV_E_INVALID;
     if (sh.variant != kFast) return FREQKV_E_UNSUPPORTED;
     int channels = 8;
     fast_supported(sh.n, sh.Lc, sh.d, nullptr, nullptr, &channels);

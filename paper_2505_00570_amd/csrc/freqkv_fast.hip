@@ -30,9 +30,9 @@
 //   stage P  complex DFT over j2:               D[g][f][f2]                                    (in place)
 //   middle   per (f2, f3): the four arrays' coefficients -> U of the even and of the odd k:  G[(k1,ch)][f][k2]
 //   stage P' inverse complex DFT over k2:       E[(k1,m2,ch)][Re 0..47 | Im 48..95]    (other half of LDS)
-//   stage Q' half-complex -> real over k3:      u[(k1,m2)][m3][ch]                      (first half again)
-//   store    length-2 butterfly over k1, output index m = m1 (Lc/2) + m2 (Lc/p) + m3 (Lc/q) mod Lc, rows
-//            y_{2m} = u_m, y_{2m+1} = u_{Lc-1-m}, one rounding to bf16
+//   stage Q' half-complex -> real over k3, the length-2 butterfly over k1 on its accumulators, and the store:
+//            output index m = m1 (Lc/2) + m2 (Lc/p) + m3 (Lc/q) mod Lc, rows y_{2m} = u_m, y_{2m+1} = u_{Lc-1-m},
+//            one rounding to bf16, straight from the registers to the cache
 #include "freqkv_internal.h"
 
 #include <cmath>
@@ -154,7 +154,7 @@ __device__ __forceinline__ half8 p_fragment(const _Float16* col, int RS, int k)
 }
 
 // dump: diagnostic only.  When not null, workgroup 0 copies its LDS there after phase `stop` (1 load ...
-// 6 stage Q') and every workgroup returns without writing the cache.
+// 5 stage P') and every workgroup returns without writing the cache.
 template <class Cfg, int NW, bool DIAG>
 __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, const char* __restrict__ tables_arg,
                                                  float rest_scale, float* __restrict__ tap,
@@ -591,9 +591,15 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
     __syncthreads();
     take_stamp(IC<5>{});
     if (dump_and_stop(5)) return;
+    take_stamp(IC<6>{});
 
-    // ---- phase 6: stage Q'.  Rows (k1, m2, ch) x contraction (Re | Im of k3, 96) -> m3; 4 consecutive rows of a
-    // lane are 4 channels: u[(k1, m2)][m3][ch] into the first half of LDS.
+    // ---- phase 6: stage Q' and the store.  Rows (k1, m2, ch) x contraction (Re | Im of k3, 96) -> m3.  A wave takes
+    // a tile of 32 rows with k1 = 0 together with the tile of the same (m2, ch) with k1 = 1, so the length-2
+    // butterfly over k1 is done on the fp32 accumulators: y_a = u0 + u1 belongs to output index m_a, y_b = u0 - u1
+    // to m_b = m_a + Lc/2.  A lane holds column m3 and, per group of four registers, four channels of one m2; the
+    // lane 32 further on holds the next four.  The two exchange what the other needs (the lower lane keeps y_a, the
+    // upper y_b), and each writes one 16-byte piece of one result row: no LDS round trip, one rounding (to bf16).
+    if (DIAG && dump && !stamp) return;
     {
         half8 bqi[3][6];
         const half8* tq = (const half8*)(tables + Cfg::OFF_QI) + lane;
@@ -606,106 +612,77 @@ __global__ __launch_bounds__(NW * 64, 1) void k_fast(SlabTable tab, Geom g, cons
             static_for<6>([&](auto ks) { pin(bqi[ct.value][ks.value]); });
         });
         pf(IC<12>{});
-        constexpr int NT6 = 2 * C * J2 / 32;
-        constexpr int TU = (NT6 + NW - 1) / NW;        // all tiles of a wave in flight together (1, 2 or 3)
-        static_assert(TU <= 3, "tiles of a wave fit the register file");
-        for (int t0 = wave; t0 < NT6; t0 += NW * TU) {
-            f32x16 acc[TU][3];
-            static_for<TU>([&](auto tu) {
-                static_for<3>([&](auto ct) { static_for<16>([&](auto r) { acc[tu.value][ct.value][r.value] = 0.f; }); });
-            });
-            const _Float16* src[TU];
-            int rot[TU];
-            static_for<TU>([&](auto tu) {
-                int t = t0 + NW * tu.value;
-                if (t > NT6 - 1) t = NT6 - 1;          // a tile past the end repeats the last one and is not written
-                const int row = t * 32 + l32;
-                src[tu.value] = lds + Y0 + row * 96;
-                rot[tu.value] = rot12(row) + lhi;
-            });
-            static_for<6>([&](auto ks) {
-                static_for<TU>([&](auto tu) {
-                    const half8 a = *(const half8*)(src[tu.value] + wrap12(wrap12(ks.value * 2 + rot[tu.value])) * 8);
-                    static_for<3>([&](auto ct) {
-                        acc[tu.value][ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                            a, bqi[ct.value][ks.value], acc[tu.value][ct.value], 0, 0, 0);
-                    });
-                });
-            });
-            static_for<TU>([&](auto tu) {
-                const int t = t0 + NW * tu.value;
-                static_for<3>([&](auto ct) {
-                    const int m3 = ct.value * 32 + l32;
-                    if (m3 < Q && t < NT6) {
-                        static_for<4>([&](auto r4) {
-                            const int v0 = t * 32 + 8 * r4.value + 4 * lhi;       // (k1 J2 + m2) C + ch, ch a multiple of 4
-                            const half4 o = cvt4(acc[tu.value][ct.value][4 * r4.value], acc[tu.value][ct.value][4 * r4.value + 1], acc[tu.value][ct.value][4 * r4.value + 2], acc[tu.value][ct.value][4 * r4.value + 3]);
-                            *(half4*)(lds + ((v0 / C) * 96 + m3) * C + (v0 % C)) = o;
-                        });
-                    }
-                });
-            });
-        }
-    }
-    pf(IC<13>{});
-    __syncthreads();
-    take_stamp(IC<6>{});
-    if (dump_and_stop(6)) return;
-    if (DIAG && dump && !stamp) return;
-
-    // ---- phase 7: store
-    {
+        constexpr int NPAIR = J2 * C / 32;             // tiles per k1
+        static_assert(NPAIR <= NW, "one tile pair per wave");
         float* tp = nullptr;
         if (tap) tp = tap + ((g.tap_slab0 * g.hts_per_slab + ht) * (long long)Lc) * g.d + c0;
-        // positions recomputed from an opaque copy of the lane index: shared with the load stage's, the quotients
-        // would be kept alive (spilled) across all stages, and a reload queues behind the rows in flight
-        int tid_s = tid;
-        asm volatile("" : "+v"(tid_s));
-        static_for<NIT>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            if constexpr (i == 0) pf(IC<14>{});
-            if constexpr (i == NIT / 2 && NIT > 1) pf(IC<15>{});
-            const int pos = tid_s + NT * i;
-            if (pos >= Cfg::NPOS) return;
-            const int m2 = pos / Q, m3 = pos - m2 * Q;
-            const _Float16* u0 = lds + ((0 * J2 + m2) * 96 + m3) * C;
-            const _Float16* u1 = lds + ((1 * J2 + m2) * 96 + m3) * C;
-            int ma = (m2 * (2 * Q) + m3 * (2 * P)) % Lc;
-            int mb = ma + N;
-            if (mb >= Lc) mb -= Lc;
-            const int ra = makhoul_row(ma, Lc), rb = makhoul_row(mb, Lc);
-            static_for<CV>([&](auto vc) {
-                constexpr int v = decltype(vc)::value;
-                const half8 g0 = *(const half8*)(u0 + 8 * v), g1 = *(const half8*)(u1 + 8 * v);
-                float va[8], vb[8];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const float a = (float)g0[c], b = (float)g1[c];
-                    va[c] = (a + b) * unsc;
-                    vb[c] = (a - b) * unsc;
-                }
-                if (nonfinite) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) va[c] = vb[c] = __builtin_nanf("");
-                }
-                u32x4 pa, pb;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    pa[c] = pack_bf16x2(va[2 * c], va[2 * c + 1]);
-                    pb[c] = pack_bf16x2(vb[2 * c], vb[2 * c + 1]);
-                }
-                *(u32x4*)(base + (uint32_t)ra * rowb32 + 16 * v) = pa;
-                *(u32x4*)(base + (uint32_t)rb * rowb32 + 16 * v) = pb;
-                if (tp) {
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) {
-                        tp[(long long)ra * g.d + 8 * v + c] = va[c];
-                        tp[(long long)rb * g.d + 8 * v + c] = vb[c];
-                    }
-                }
+        if (wave < NPAIR) {
+            const int t = wave;
+            f32x16 acc0[3], acc1[3];
+            static_for<3>([&](auto ct) {
+                static_for<16>([&](auto r) { acc0[ct.value][r.value] = 0.f; acc1[ct.value][r.value] = 0.f; });
             });
-        });
-        if constexpr (NIT == 1) pf(IC<15>{});
+            const int row0 = t * 32 + l32, row1 = (t + NPAIR) * 32 + l32;
+            const _Float16* src0 = lds + Y0 + row0 * 96;
+            const _Float16* src1 = lds + Y0 + row1 * 96;
+            const int rot0 = rot12(row0) + lhi, rot1 = rot12(row1) + lhi;
+            static_for<6>([&](auto ks) {
+                const half8 a0 = *(const half8*)(src0 + wrap12(wrap12(ks.value * 2 + rot0)) * 8);
+                const half8 a1 = *(const half8*)(src1 + wrap12(wrap12(ks.value * 2 + rot1)) * 8);
+                static_for<3>([&](auto ct) {
+                    acc0[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, bqi[ct.value][ks.value], acc0[ct.value], 0, 0, 0);
+                    acc1[ct.value] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, bqi[ct.value][ks.value], acc1[ct.value], 0, 0, 0);
+                });
+            });
+            pf(IC<13>{});
+            static_for<3>([&](auto ct) {
+                if constexpr (decltype(ct)::value == 1) pf(IC<14>{});
+                if constexpr (decltype(ct)::value == 2) pf(IC<15>{});
+                const int m3 = ct.value * 32 + l32;
+                static_for<4>([&](auto r4) {
+                    // rows 32 t + 8 r4 + 4 lhi + (0..3): (k1 J2 + m2) C + channel; wave-uniform up to the lhi term
+                    const int vu = t * 32 + 8 * r4.value;
+                    const int m2 = vu / C, cb = vu - m2 * C;            // cb: first channel of this lane pair's 8
+                    float ya[4], yb[4];
+                    static_for<4>([&](auto i) {
+                        const float u0 = acc0[ct.value][4 * r4.value + i.value], u1 = acc1[ct.value][4 * r4.value + i.value];
+                        ya[i.value] = nonfinite ? __builtin_nanf("") : (u0 + u1) * unsc;
+                        yb[i.value] = nonfinite ? __builtin_nanf("") : (u0 - u1) * unsc;
+                    });
+                    const uint32_t a_lo = pack_bf16x2(ya[0], ya[1]), a_hi = pack_bf16x2(ya[2], ya[3]);
+                    const uint32_t b_lo = pack_bf16x2(yb[0], yb[1]), b_hi = pack_bf16x2(yb[2], yb[3]);
+                    // the lower lane keeps y_a and receives the upper lane's y_a (channels +4); the upper lane keeps y_b
+                    const uint32_t r_lo = (uint32_t)__shfl_xor((int)(lhi ? a_lo : b_lo), 32);
+                    const uint32_t r_hi = (uint32_t)__shfl_xor((int)(lhi ? a_hi : b_hi), 32);
+                    int ma = (m2 * (2 * Q) + m3 * (2 * P)) % Lc;
+                    int mb = ma + N;
+                    if (mb >= Lc) mb -= Lc;
+                    const int orow = lhi ? makhoul_row(mb, Lc) : makhoul_row(ma, Lc);
+                    const u32x4 piece = lhi ? u32x4{r_lo, r_hi, b_lo, b_hi} : u32x4{a_lo, a_hi, r_lo, r_hi};
+                    const bool ok = m3 < Q && m2 < P;
+                    if (ok) *(u32x4*)(base + (uint32_t)orow * rowb32 + 2 * cb) = piece;
+                    if (tp) {
+                        // the fp32 results before the rounding: the same exchange, in fp32
+                        float mine[4], theirs[4];
+                        static_for<4>([&](auto i) {
+                            mine[i.value] = lhi ? yb[i.value] : ya[i.value];
+                            theirs[i.value] = __shfl_xor(lhi ? ya[i.value] : yb[i.value], 32);
+                        });
+                        if (ok) {
+                            float* o = tp + (long long)orow * g.d + cb;
+                            static_for<4>([&](auto i) {
+                                o[(lhi ? 4 : 0) + i.value] = mine[i.value];
+                                o[(lhi ? 0 : 4) + i.value] = theirs[i.value];
+                            });
+                        }
+                    }
+                });
+            });
+        } else {
+            pf(IC<13>{});
+            pf(IC<14>{});
+            pf(IC<15>{});
+        }
     }
     if constexpr (DIAG) if (stamp) {
         __syncthreads();
